@@ -1,0 +1,192 @@
+"""fp64 CPU oracle of the SVIP hot path -- TEST INFRASTRUCTURE, not the product.
+
+Thin ctypes loader around ``svip_oracle.c`` (plain C, gcc -O2).  Only ``tests/``, the
+smoke check and the benchmark's CPU-baseline leg may import this package; it shares
+nothing with the HIP library and never imports it.
+
+All array arguments are converted to contiguous float64 / int64 numpy arrays; logits in
+bf16 or fp32 are widened exactly before they get here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "svip_oracle.c")
+_LIB = os.path.join(_HERE, "libsvip_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc; returns the path of the shared object."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-o", tmp, _SRC, "-lm"]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_D = ctypes.POINTER(ctypes.c_double)
+_L = ctypes.POINTER(ctypes.c_long)
+_U8 = ctypes.POINTER(ctypes.c_ubyte)
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        lib.oracle_softmax_row.restype = ctypes.c_double
+        lib.oracle_softmax_row.argtypes = [_D, ctypes.c_long, ctypes.c_double, _D]
+        lib.oracle_entropy_row.restype = ctypes.c_double
+        lib.oracle_entropy_row.argtypes = [_D, ctypes.c_long]
+        lib.oracle_inverse_cdf.restype = ctypes.c_long
+        lib.oracle_inverse_cdf.argtypes = [_D, ctypes.c_long, ctypes.c_double, _D]
+        lib.oracle_draft_step.restype = None
+        lib.oracle_draft_step.argtypes = [
+            _D, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_double,
+            ctypes.c_long, ctypes.c_long, _D, _U8, _L, _D, _D, _D, _U8, _D, _D]
+        lib.oracle_verify.restype = None
+        lib.oracle_verify.argtypes = [
+            _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
+            _L, _L, _D, _D, _L, _L, _D, _D, _D]
+        lib.oracle_pair_stats.restype = None
+        lib.oracle_pair_stats.argtypes = [_D, _D, ctypes.c_long, ctypes.c_double, _D]
+        lib.oracle_sd_position_trials.restype = None
+        lib.oracle_sd_position_trials.argtypes = [
+            _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_ulonglong, ctypes.c_int, _L, _L]
+        _lib = lib
+    return _lib
+
+
+def _f64(a) -> np.ndarray:
+    if hasattr(a, "detach"):  # torch tensor (any float dtype, CPU)
+        a = a.detach().to("cpu").double().numpy()
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i64(a) -> np.ndarray:
+    if hasattr(a, "detach"):
+        a = a.detach().to("cpu").long().numpy()
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def _p(a: np.ndarray, t):
+    return a.ctypes.data_as(t)
+
+
+def softmax_row(z, T: float = 1.0):
+    """(prob[V], logsumexp) of one row of logits at temperature T."""
+    z = _f64(z).ravel()
+    prob = np.empty_like(z)
+    lse = _load().oracle_softmax_row(_p(z, _D), z.size, float(T), _p(prob, _D))
+    return prob, lse
+
+
+def entropy_row(prob) -> float:
+    prob = _f64(prob).ravel()
+    return _load().oracle_entropy_row(_p(prob, _D), prob.size)
+
+
+def inverse_cdf(w, u: float):
+    """(index, margin) of one categorical draw from weights w with uniform u."""
+    w = _f64(w).ravel()
+    m = ctypes.c_double(0.0)
+    i = _load().oracle_inverse_cdf(_p(w, _D), w.size, float(u), ctypes.byref(m))
+    return int(i), m.value
+
+
+@dataclass
+class DraftStepResult:
+    token: np.ndarray      # int64 [B], -1 for skipped rows
+    entropy: np.ndarray    # float64 [B], nats
+    q_tok: np.ndarray      # float64 [B]
+    lse: np.ndarray        # float64 [B]
+    stop: np.ndarray       # uint8 [B]
+    margin_h: np.ndarray   # float64 [B], |sqrt(H) - h| (inf when the cap decides)
+    margin_s: np.ndarray   # float64 [B], sampler margin (fraction of total mass)
+
+
+def draft_step(z, T, h, step_j, k_max, u, stop_in=None) -> DraftStepResult:
+    """Draft-side pass over z[B, V]; see oracle_draft_step in svip_oracle.c."""
+    z = _f64(z)
+    assert z.ndim == 2
+    B, V = z.shape
+    u = _f64(u).ravel()
+    assert u.size == B
+    si = None
+    if stop_in is not None:
+        si = np.ascontiguousarray(_i64(stop_in).ravel() != 0, dtype=np.uint8)
+        assert si.size == B
+    out = DraftStepResult(
+        np.empty(B, np.int64), np.empty(B), np.empty(B), np.empty(B),
+        np.empty(B, np.uint8), np.empty(B), np.empty(B))
+    _load().oracle_draft_step(
+        _p(z, _D), B, V, V, float(T), float(h), int(step_j), int(k_max), _p(u, _D),
+        _p(si, _U8) if si is not None else None,
+        _p(out.token, _L), _p(out.entropy, _D), _p(out.q_tok, _D), _p(out.lse, _D),
+        _p(out.stop, _U8), _p(out.margin_h, _D), _p(out.margin_s, _D))
+    return out
+
+
+@dataclass
+class VerifyResult:
+    n_accepted: np.ndarray   # int64 [B]
+    next_token: np.ndarray   # int64 [B]
+    accept_prob: np.ndarray  # float64 [B, k_max]; NaN where j >= gamma[b]
+    margin: np.ndarray       # float64 [B], smallest decision margin of the sequence
+    resid_mass: np.ndarray   # float64 [B], sum max(0, p - q) at the rejection (0 if none)
+
+
+def verify(zp, zq, T, tok, gamma, ua, ur) -> VerifyResult:
+    """Target-side pass; zp[B, k+1, V], zq[B, k, V]; see oracle_verify in svip_oracle.c."""
+    zp = _f64(zp)
+    zq = _f64(zq)
+    B, kp1, V = zp.shape
+    k = kp1 - 1
+    assert zq.shape == (B, k, V)
+    tok = _i64(tok).reshape(B, k)
+    gamma = _i64(gamma).ravel()
+    ua = _f64(ua).reshape(B, k)
+    ur = _f64(ur).ravel()
+    assert gamma.size == B and ur.size == B
+    assert (gamma >= 0).all() and (gamma <= k).all()
+    for b in range(B):
+        g = int(gamma[b])
+        assert ((tok[b, :g] >= 0) & (tok[b, :g] < V)).all()
+    out = VerifyResult(
+        np.empty(B, np.int64), np.empty(B, np.int64), np.full((B, k), np.nan),
+        np.empty(B), np.empty(B))
+    _load().oracle_verify(
+        _p(zp, _D), _p(zq, _D), B, k, V, float(T), _p(tok, _L), _p(gamma, _L),
+        _p(ua, _D), _p(ur, _D), _p(out.n_accepted, _L), _p(out.next_token, _L),
+        _p(out.accept_prob, _D), _p(out.margin, _D), _p(out.resid_mass, _D))
+    return out
+
+
+def pair_stats(zp_row, zq_row, T: float = 1.0) -> dict:
+    """beta, KL(q||p), H_{q,p}, H_q and TVD of one (target, draft) row pair."""
+    zp_row = _f64(zp_row).ravel()
+    zq_row = _f64(zq_row).ravel()
+    assert zp_row.size == zq_row.size
+    out = np.empty(5)
+    _load().oracle_pair_stats(_p(zp_row, _D), _p(zq_row, _D), zp_row.size, float(T), _p(out, _D))
+    return dict(beta=out[0], kl=out[1], hqp=out[2], hq=out[3], tvd=out[4])
+
+
+def sd_position_trials(p, q, N: int, seed: int, resid_sign: int = +1):
+    """(histogram[V], n_accepted) of N brute-force draft/verify/correct trials."""
+    p = _f64(p).ravel()
+    q = _f64(q).ravel()
+    hist = np.zeros(p.size, np.int64)
+    nacc = ctypes.c_long(0)
+    _load().oracle_sd_position_trials(
+        _p(p, _D), _p(q, _D), p.size, int(N), int(seed), int(resid_sign),
+        _p(hist, _L), ctypes.byref(nacc))
+    return hist, nacc.value

@@ -1,0 +1,279 @@
+/*
+ * SVIP hot-path oracle -- TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT.
+ *
+ * A plain, slow, fp64 CPU statement of what the per-step vocabulary-wide work of
+ * SVIP (arXiv 2411.18462) computes: the draft-side pass (softmax, Shannon entropy,
+ * one categorical draw, entropy stop test) and the target-side verification pass
+ * (acceptance test per draft position, first rejection, correction or bonus draw).
+ * Only tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+ * It shares no code, header, table or constant with the HIP path.
+ *
+ * Everything is written row by row, in the order and notation of the paper:
+ *   - draft token x ~ q(.|prefix)                          Algorithm 1, "Sample" step
+ *   - stop iff sqrt(H_q) > h                               Section 2.2, Eq. (stop_condition)
+ *   - accept iff r < p(x)/q(x), r ~ U[0,1)                 Algorithm 2 (Verify, sampling)
+ *   - walk j = 1..gamma until the first failed Verify      Algorithm 1, verification loop
+ *   - correction x^ ~ norm(max(0, p - q))                  Algorithm 4 (Correct, sampling);
+ *     the listing prints q - p, which cannot preserve the target law the paper
+ *     claims in Section 1 -- the p - q direction is the one that does
+ *   - bonus token x ~ p(.|all drafts) if nothing rejected  Algorithm 1, last "Sample" step
+ * plus the diagnostics of Section 2.2: beta = sum min(p,q) (Eq. beta), KL(q||p) and
+ * the cross entropy H_{q,p} (Eq. pinsker / beta-bound).
+ *
+ * Conventions (stated where the paper is silent):
+ *   - entropy in nats; logits are divided by the temperature T before the softmax
+ *     and H is the entropy of that tempered distribution;
+ *   - "sample from weights w with one uniform u": the smallest index i whose
+ *     inclusive prefix sum C_i = w_0 + ... + w_i satisfies C_i > u * sum(w)
+ *     (ascending token index, strict inequality); if rounding leaves no such i,
+ *     the largest i with w_i > 0;
+ *   - the acceptance test is evaluated as r * q(x) < p(x) (no division), so q(x) = 0
+ *     with p(x) > 0 accepts and p(x) = 0 rejects;
+ *   - all uniforms for a round are drawn up front; positions after the first
+ *     rejection are evaluated but ignored.
+ *
+ * Every decision also reports its margin (distance of the compared quantities from
+ * the decision boundary) so that a finite-precision implementation can be compared
+ * exactly wherever the margin is not within rounding.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- one row ------------------------------------------------------------------ */
+
+/* prob[i] = softmax(z/T)[i]; returns logsumexp(z/T).  exp(-inf) contributes 0. */
+double oracle_softmax_row(const double *z, long V, double T, double *prob)
+{
+    double m = -INFINITY;
+    for (long i = 0; i < V; ++i) {
+        double zi = z[i] / T;
+        if (zi > m) m = zi;
+    }
+    double S = 0.0;
+    for (long i = 0; i < V; ++i) {
+        double e = exp(z[i] / T - m);
+        prob[i] = e;
+        S += e;
+    }
+    for (long i = 0; i < V; ++i) prob[i] /= S;
+    return m + log(S);
+}
+
+/* Shannon entropy -sum p ln p over p > 0, in nats (Section 2.2, H_q). */
+double oracle_entropy_row(const double *prob, long V)
+{
+    double H = 0.0;
+    for (long i = 0; i < V; ++i)
+        if (prob[i] > 0.0) H -= prob[i] * log(prob[i]);
+    return H > 0.0 ? H : 0.0;
+}
+
+/* One categorical draw from non-negative weights w with the uniform u in [0,1).
+ * *margin = distance of u*W from the nearer edge of the chosen cell, divided by W.
+ * Returns -1 if the total weight is not positive. */
+long oracle_inverse_cdf(const double *w, long V, double u, double *margin)
+{
+    double W = 0.0;
+    for (long i = 0; i < V; ++i) W += w[i];
+    if (margin) *margin = 0.0;
+    if (!(W > 0.0)) return -1;
+    double target = u * W;
+    double C = 0.0;
+    long last_pos = -1;
+    for (long i = 0; i < V; ++i) {
+        double Cprev = C;
+        C += w[i];
+        if (w[i] > 0.0) last_pos = i;
+        if (C > target) {
+            if (margin) {
+                double lo = target - Cprev, hi = C - target;
+                *margin = (lo < hi ? lo : hi) / W;
+            }
+            return i;
+        }
+    }
+    return last_pos; /* only reachable through rounding; margin stays 0 */
+}
+
+/* ---- draft step (Algorithm 1, drafting loop body; Eq. stop_condition) ---------- */
+
+/*
+ * For every row b with stop_in[b] == 0 (or stop_in == NULL):
+ *   q = softmax(z_b / T); H = entropy(q); token ~ q via u[b];
+ *   stop = sqrt(H) > h, or the row has reached the draft-length cap
+ *   (step_j + 1 >= k_max; Section 3 limits the draft length).
+ * Rows with stop_in[b] != 0 are skipped: token -1, stop 1, other outputs 0.
+ * margin_h = |sqrt(H) - h|, margin_s = sampler margin.
+ */
+void oracle_draft_step(const double *z, long B, long V, long row_stride,
+                       double T, double h, long step_j, long k_max,
+                       const double *u, const unsigned char *stop_in,
+                       long *token, double *entropy, double *q_tok, double *lse,
+                       unsigned char *stop, double *margin_h, double *margin_s)
+{
+    double *q = (double *)malloc(sizeof(double) * (size_t)V);
+    for (long b = 0; b < B; ++b) {
+        if (stop_in && stop_in[b]) {
+            token[b] = -1; entropy[b] = 0; q_tok[b] = 0; lse[b] = 0; stop[b] = 1;
+            margin_h[b] = INFINITY; margin_s[b] = INFINITY;
+            continue;
+        }
+        const double *zb = z + b * row_stride;
+        lse[b] = oracle_softmax_row(zb, V, T, q);
+        double H = oracle_entropy_row(q, V);
+        entropy[b] = H;
+        long x = oracle_inverse_cdf(q, V, u[b], &margin_s[b]);
+        token[b] = x;
+        q_tok[b] = x >= 0 ? q[x] : 0.0;
+        int by_entropy = sqrt(H) > h;
+        int by_cap = (step_j + 1 >= k_max);
+        stop[b] = (unsigned char)(by_entropy || by_cap);
+        margin_h[b] = by_cap ? INFINITY : fabs(sqrt(H) - h);
+    }
+    free(q);
+}
+
+/* ---- verification (Algorithm 1 verification loop; Algorithms 2 and 4) ---------- */
+
+/*
+ * zp: [B][k_max+1][V] target logits, zq: [B][k_max][V] draft logits (both dense),
+ * tok: [B][k_max] draft tokens, gamma[b] in 0..k_max, ua: [B][k_max], ur: [B].
+ * Outputs per sequence: n_accepted, next_token (correction or bonus),
+ * accept_prob[b][j] = min(1, p/q) for j < gamma[b] (others untouched),
+ * margin[b] = smallest margin among the decisions that shaped the outputs:
+ *   |ua - p/q| for every position up to and including the first rejection,
+ *   and the sampler margin of the correction / bonus draw.
+ * resid_mass[b] = sum max(0, p - q) at the rejected position (0 for a bonus draw).
+ */
+void oracle_verify(const double *zp, const double *zq, long B, long k_max, long V,
+                   double T, const long *tok, const long *gamma,
+                   const double *ua, const double *ur,
+                   long *n_accepted, long *next_token, double *accept_prob,
+                   double *margin, double *resid_mass)
+{
+    double *p = (double *)malloc(sizeof(double) * (size_t)V);
+    double *q = (double *)malloc(sizeof(double) * (size_t)V);
+    double *w = (double *)malloc(sizeof(double) * (size_t)V);
+    for (long b = 0; b < B; ++b) {
+        const double *zpb = zp + b * (k_max + 1) * V;
+        const double *zqb = zq + b * k_max * V;
+        long g = gamma[b];
+        long r = g;              /* 0-based index of the first rejection; g = none */
+        double mar = INFINITY;
+        /* evaluate every drafted position; the first failure ends the walk */
+        for (long j = 0; j < g; ++j) {
+            oracle_softmax_row(zpb + j * V, V, T, p);
+            oracle_softmax_row(zqb + j * V, V, T, q);
+            long x = tok[b * k_max + j];
+            double px = p[x], qx = q[x];
+            double ratio = qx > 0.0 ? px / qx : (px > 0.0 ? INFINITY : 0.0);
+            accept_prob[b * k_max + j] = ratio < 1.0 ? ratio : 1.0;
+            int acc = ua[b * k_max + j] * qx < px;
+            if (r == g) {        /* no rejection so far: this decision shapes the output */
+                double d = fabs(ua[b * k_max + j] - ratio);
+                if (d < mar) mar = d;
+                if (!acc) r = j;
+            }
+        }
+        n_accepted[b] = r;
+        double ms = 0.0;
+        resid_mass[b] = 0.0;
+        if (r < g) {
+            /* Correct: residual of target over draft at the rejected position */
+            oracle_softmax_row(zpb + r * V, V, T, p);
+            oracle_softmax_row(zqb + r * V, V, T, q);
+            double W = 0.0;
+            for (long i = 0; i < V; ++i) {
+                double d = p[i] - q[i];
+                w[i] = d > 0.0 ? d : 0.0;
+                W += w[i];
+            }
+            resid_mass[b] = W;
+            if (W > 0.0) {
+                next_token[b] = oracle_inverse_cdf(w, V, ur[b], &ms);
+            } else {          /* p <= q everywhere: no residual, draw from p */
+                next_token[b] = oracle_inverse_cdf(p, V, ur[b], &ms);
+                ms = 0.0;
+            }
+        } else {
+            /* every draft accepted: bonus token from the target row after the drafts */
+            oracle_softmax_row(zpb + g * V, V, T, p);
+            next_token[b] = oracle_inverse_cdf(p, V, ur[b], &ms);
+        }
+        margin[b] = ms < mar ? ms : mar;
+    }
+    free(p); free(q); free(w);
+}
+
+/* ---- diagnostics of Section 2.2 ------------------------------------------------ */
+
+/* out[0] = beta = sum min(p,q)   (Eq. beta)
+ * out[1] = KL(q||p)              (Eq. pinsker)
+ * out[2] = H_{q,p} = -sum q ln p (Eq. beta-bound)
+ * out[3] = H_q
+ * out[4] = TVD(p,q) = 0.5 sum |p-q|  (Eq. tvd) */
+void oracle_pair_stats(const double *zp_row, const double *zq_row, long V, double T,
+                       double *out)
+{
+    double *p = (double *)malloc(sizeof(double) * (size_t)V);
+    double *q = (double *)malloc(sizeof(double) * (size_t)V);
+    oracle_softmax_row(zp_row, V, T, p);
+    oracle_softmax_row(zq_row, V, T, q);
+    double beta = 0, kl = 0, hqp = 0, tvd = 0;
+    for (long i = 0; i < V; ++i) {
+        beta += p[i] < q[i] ? p[i] : q[i];
+        tvd += 0.5 * fabs(p[i] - q[i]);
+        if (q[i] > 0.0) {
+            kl += q[i] * (log(q[i]) - log(p[i]));
+            hqp -= q[i] * log(p[i]);
+        }
+    }
+    out[0] = beta; out[1] = kl; out[2] = hqp; out[3] = oracle_entropy_row(q, V); out[4] = tvd;
+    free(p); free(q);
+}
+
+/* ---- brute-force law of one speculative position (Algorithms 2 + 4) ------------ */
+
+/*
+ * N independent trials on fixed distributions p, q (already normalised, length V):
+ *   x ~ q with a fresh uniform; Verify with a fresh uniform; on failure Correct
+ *   with a fresh uniform.  hist[i] counts the emitted token, *n_acc the accepts.
+ * Uniforms come from a 64-bit SplitMix generator seeded by `seed`, 53 bits each.
+ * resid_sign = +1 uses max(0, p - q); -1 uses the printed max(0, q - p) so that a
+ * test can show that direction breaks the target law.
+ */
+static unsigned long long splitmix(unsigned long long *s)
+{
+    unsigned long long z = (*s += 0x9E3779B97F4A7C15ULL);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+static double unif(unsigned long long *s) { return (double)(splitmix(s) >> 11) * 0x1.0p-53; }
+
+void oracle_sd_position_trials(const double *p, const double *q, long V, long N,
+                               unsigned long long seed, int resid_sign,
+                               long *hist, long *n_acc)
+{
+    double *w = (double *)malloc(sizeof(double) * (size_t)V);
+    for (long i = 0; i < V; ++i) {
+        double d = resid_sign >= 0 ? p[i] - q[i] : q[i] - p[i];
+        w[i] = d > 0.0 ? d : 0.0;
+        hist[i] = 0;
+    }
+    *n_acc = 0;
+    unsigned long long s = seed;
+    for (long n = 0; n < N; ++n) {
+        long x = oracle_inverse_cdf(q, V, unif(&s), NULL);
+        double r = unif(&s);
+        if (r * q[x] < p[x]) {
+            ++*n_acc;
+        } else {
+            long y = oracle_inverse_cdf(w, V, unif(&s), NULL);
+            x = y >= 0 ? y : oracle_inverse_cdf(p, V, unif(&s), NULL);
+        }
+        ++hist[x];
+    }
+    free(w);
+}

@@ -1,0 +1,361 @@
+"""Pins for the fp64 oracle: closed forms, library routines, invariants and brute force.
+
+None of these re-type the oracle's own formulas: each compares it with a value fixed by
+mathematics (closed forms), with an independent library routine (scipy / numpy), with an
+invariant stated in the paper (Section 2.2: Eq. beta, tvd, pinsker, beta-bound; Appendix B)
+or with brute-force counting on a tiny vocabulary.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+CHI2_7DOF_999 = 24.32   # 99.9 % quantile of chi-square with 7 degrees of freedom
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------- softmax / entropy
+
+@pytest.mark.parametrize("V", [32000, 128256, 151936])
+def test_uniform_logits_entropy_is_log_V(V):
+    golden = dict(line.split() for line in open(os.path.join(GOLDEN, "log_vocab.txt"))
+                  if line.strip() and not line.startswith("#"))
+    for const in (0.0, -7.25, 3.5):
+        p, lse = oracle.softmax_row(np.full(V, const), T=1.0)
+        H = oracle.entropy_row(p)
+        assert abs(H - math.log(V)) < 1e-9
+        assert abs(H - float(golden[str(V)])) < 5e-5       # 4-decimal values in the fixture
+        assert abs(lse - (const + math.log(V))) < 1e-9
+    # any h of the paper's grid stops on a uniform row
+    u = 0.50001                     # away from a cell edge: token = floor(u V)
+    r = oracle.draft_step(np.zeros((1, V)), 1.0, 0.5, 0, 40, [u])
+    assert r.stop[0] == 1 and r.token[0] == int(u * V)
+
+
+def test_one_hot_entropy_zero_and_no_stop():
+    V = 1000
+    z = np.full((2, V), -np.inf)
+    z[0, 17] = 3.0
+    z[1, :] = 0.0
+    z[1, 999] = 1.0e4          # spike so large every other term underflows to 0
+    r = oracle.draft_step(z, 1.0, 0.2, 0, 40, [0.0, 0.999999])
+    assert list(r.token) == [17, 999]
+    assert np.all(r.entropy == 0.0) and np.all(r.stop == 0)
+    assert np.allclose(r.q_tok, 1.0) and np.allclose(r.lse, [3.0, 1.0e4])
+
+
+@pytest.mark.parametrize("V,d", [(8, 1.0), (32000, 12.0), (128256, 12.0), (50, -3.0)])
+def test_spike_over_flat_closed_form(V, d):
+    z = np.zeros(V)
+    z[V // 3] = d
+    ps = math.exp(d) / (math.exp(d) + V - 1)
+    H_exact = -ps * math.log(ps) - (1 - ps) * math.log((1 - ps) / (V - 1))
+    p, lse = oracle.softmax_row(z)
+    assert abs(p[V // 3] - ps) < 1e-12
+    assert abs(oracle.entropy_row(p) - H_exact) < 1e-10
+    assert abs(lse - math.log(math.exp(d) + V - 1)) < 1e-10
+
+
+def test_two_point_entropy_log1p_form():
+    for d in (0.0, 0.5, 4.0, 30.0):
+        p, _ = oracle.softmax_row([0.0, d])
+        # H = log(1+e^-d) + d * e^-d / (1+e^-d) for logits (0, d)
+        H = math.log1p(math.exp(-d)) + d * math.exp(-d) / (1 + math.exp(-d))
+        assert abs(oracle.entropy_row(p) - H) < 1e-13
+
+
+def test_softmax_entropy_match_scipy_and_invariances():
+    rng = _rng(1)
+    for V, T in ((8, 1.0), (1000, 0.7), (32000, 1.0), (4099, 2.5)):
+        z = rng.normal(0, 3, V)
+        p, lse = oracle.softmax_row(z, T)
+        assert np.allclose(p, scipy.special.softmax(z / T), rtol=1e-12, atol=0)
+        assert abs(lse - scipy.special.logsumexp(z / T)) < 1e-11
+        H = oracle.entropy_row(p)
+        assert abs(H - scipy.stats.entropy(scipy.special.softmax(z / T))) < 1e-11
+        # shift invariance and the temperature identity H_T(z) = H_1(z/T)
+        p2, lse2 = oracle.softmax_row(z + 5.0, T)
+        assert abs(oracle.entropy_row(p2) - H) < 1e-11 and abs(lse2 - lse - 5.0 / T) < 1e-11
+        p3, _ = oracle.softmax_row(z / T, 1.0)
+        assert abs(oracle.entropy_row(p3) - H) < 1e-11
+
+
+def test_minus_inf_logits_carry_no_mass():
+    z = np.array([0.0, -np.inf, 1.0, -np.inf])
+    p, lse = oracle.softmax_row(z)
+    assert p[1] == 0 and p[3] == 0 and abs(p.sum() - 1) < 1e-15
+    assert abs(oracle.entropy_row(p) - scipy.stats.entropy([1, math.e])) < 1e-14
+    # a zero-mass token is never drawn, whatever u
+    for u in (0.0, 0.2689, 0.27, 0.999999):
+        i, _ = oracle.inverse_cdf(p, u)
+        assert i in (0, 2)
+
+
+# ---------------------------------------------------------------- stop test (Eq. stop_condition)
+
+def test_stop_rule_two_formulations_agree():
+    """1 - sqrt(c H) < h_hat  <=>  sqrt(H) > (1 - h_hat)/sqrt(c)   (Section 2.2)."""
+    rng = _rng(2)
+    V = 64
+    n = 0
+    for _ in range(300):
+        c, h_hat = rng.uniform(0.05, 3.0), rng.uniform(0.0, 0.95)
+        z = rng.normal(0, rng.uniform(0.1, 6.0), (1, V))
+        h = (1 - h_hat) / math.sqrt(c)
+        r = oracle.draft_step(z, 1.0, h, 0, 40, [0.3])
+        if r.margin_h[0] < 1e-9:
+            continue
+        bound = 1 - math.sqrt(c * r.entropy[0])
+        assert bool(r.stop[0]) == (bound < h_hat)
+        n += 1
+    assert n > 250
+
+
+def test_stop_is_strict_and_cap_forces_stop():
+    V = 16
+    z = np.zeros((1, V))
+    H = math.log(V)
+    h_eq = math.sqrt(oracle.draft_step(z, 1.0, 9.0, 0, 40, [0.1]).entropy[0])
+    assert abs(h_eq - math.sqrt(H)) < 1e-12
+    assert oracle.draft_step(z, 1.0, h_eq, 0, 40, [0.1]).stop[0] == 0          # equality continues
+    assert oracle.draft_step(z, 1.0, np.nextafter(h_eq, 0), 0, 40, [0.1]).stop[0] == 1
+    assert oracle.draft_step(z, 1.0, 9.0, 38, 40, [0.1]).stop[0] == 0
+    r = oracle.draft_step(z, 1.0, 9.0, 39, 40, [0.1])                            # reached the cap
+    assert r.stop[0] == 1 and math.isinf(r.margin_h[0])
+
+
+def test_skipped_rows():
+    z = _rng(3).normal(0, 1, (3, 10))
+    r = oracle.draft_step(z, 1.0, 0.3, 0, 8, [0.1, 0.2, 0.3], stop_in=[0, 1, 0])
+    assert r.token[1] == -1 and r.stop[1] == 1
+    full = oracle.draft_step(z, 1.0, 0.3, 0, 8, [0.1, 0.2, 0.3])
+    assert r.token[0] == full.token[0] and r.token[2] == full.token[2]
+
+
+# ---------------------------------------------------------------- sampler
+
+def test_inverse_cdf_matches_searchsorted_on_fine_grid():
+    rng = _rng(4)
+    for V in (2, 8, 33):
+        q = rng.dirichlet(np.ones(V))
+        cdf = np.cumsum(q)
+        us = np.concatenate([np.linspace(0, 1, 4001, endpoint=False), rng.random(2000)])
+        for u in us:
+            i, margin = oracle.inverse_cdf(q, u)
+            # keep away from cell edges where cumsum rounding order could differ
+            if margin < 1e-12:
+                continue
+            assert i == int(np.searchsorted(cdf, u * cdf[-1], side="right"))
+
+
+def test_inverse_cdf_edges():
+    q = np.array([0.0, 0.25, 0.0, 0.5, 0.25, 0.0])
+    assert oracle.inverse_cdf(q, 0.0)[0] == 1           # first cell with mass
+    assert oracle.inverse_cdf(q, 0.25)[0] == 3          # strict: C_1 = 0.25 is not > 0.25
+    assert oracle.inverse_cdf(q, np.nextafter(0.25, 0))[0] == 1
+    assert oracle.inverse_cdf(q, np.nextafter(1.0, 0))[0] == 4   # never the trailing zero cell
+    assert oracle.inverse_cdf(np.zeros(4), 0.3)[0] == -1
+    # unnormalised weights give the same draw
+    assert oracle.inverse_cdf(7.0 * q, 0.6)[0] == oracle.inverse_cdf(q, 0.6)[0] == 3
+
+
+def test_draft_sampler_frequencies_chi_square():
+    rng = _rng(5)
+    V, N = 8, 1_000_000
+    z = rng.normal(0, 1.5, V)
+    q = scipy.special.softmax(z)
+    u = rng.random(N).astype(np.float32)
+    zz = np.broadcast_to(z, (N, V))
+    r = oracle.draft_step(zz, 1.0, 0.3, 0, 40, u)
+    counts = np.bincount(r.token, minlength=V)
+    chi2 = ((counts - N * q) ** 2 / (N * q)).sum()
+    assert chi2 < CHI2_7DOF_999
+    assert np.allclose(r.q_tok, q[r.token], rtol=1e-12)
+
+
+# ---------------------------------------------------------------- acceptance test (Alg. 2), Eq. beta / tvd / pinsker
+
+def test_identical_models_accept_everything_and_bonus_from_last_row():
+    rng = _rng(6)
+    B, k, V = 5, 6, 50
+    zq = rng.normal(0, 2, (B, k, V))
+    zp = np.concatenate([zq, rng.normal(0, 2, (B, 1, V))], 1)
+    tok = rng.integers(0, V, (B, k))
+    gamma = np.array([6, 3, 1, 0, 5])
+    ua = np.concatenate([rng.random((B, k - 1)), np.full((B, 1), np.nextafter(1.0, 0))], 1)
+    ur = rng.random(B)
+    r = oracle.verify(zp, zq, 1.0, tok, gamma, ua, ur)
+    assert np.array_equal(r.n_accepted, gamma)
+    for b in range(B):
+        g = gamma[b]
+        assert np.all(r.accept_prob[b, :g] == 1.0) and np.all(np.isnan(r.accept_prob[b, g:]))
+        p = scipy.special.softmax(zp[b, g])
+        assert r.next_token[b] == int(np.searchsorted(np.cumsum(p), ur[b] * np.cumsum(p)[-1], side="right"))
+        assert r.resid_mass[b] == 0.0
+
+
+def test_disjoint_supports_reject_at_first_position():
+    V, k = 10, 3
+    zq = np.full((1, k, V), -np.inf)
+    zp = np.full((1, k + 1, V), -np.inf)
+    zq[:, :, :5] = 0.0
+    zp[:, :, 5:] = np.arange(5)
+    r = oracle.verify(zp, zq, 1.0, [[2, 3, 4]], [3], [[0.0, 0.5, 0.5]], [0.37])
+    assert r.n_accepted[0] == 0 and r.accept_prob[0, 0] == 0.0
+    assert abs(r.resid_mass[0] - 1.0) < 1e-15
+    p = scipy.special.softmax(zp[0, 0])
+    assert r.next_token[0] == int(np.searchsorted(np.cumsum(p), 0.37, side="right"))
+
+
+def test_zero_draft_probability_accepts():
+    # q(x) = 0 < p(x): the test r*q < p holds for every r
+    zq = np.array([[[0.0, -np.inf, 0.0]]])
+    zp = np.array([[[0.0, 0.0, 0.0], [0.0, 0.0, 0.0]]])
+    r = oracle.verify(zp, zq, 1.0, [[1]], [1], [[0.999]], [0.5])
+    assert r.n_accepted[0] == 1 and r.accept_prob[0, 0] == 1.0
+
+
+def test_accept_probability_is_min_1_ratio_and_frequency_is_beta():
+    rng = _rng(7)
+    V = 8
+    zq, zp = rng.normal(0, 1.5, V), rng.normal(0, 1.5, V)
+    q, p = scipy.special.softmax(zq), scipy.special.softmax(zp)
+    st = oracle.pair_stats(zp, zq)
+    assert abs(st["beta"] - np.minimum(p, q).sum()) < 1e-14
+    assert abs(st["beta"] - (1 - st["tvd"])) < 1e-14                        # Eq. tvd
+    N = 400_000
+    us = rng.random(N)
+    d = oracle.draft_step(np.broadcast_to(zq, (N, V)), 1.0, 0.3, 0, 40, us)
+    ua = rng.random((N, 1))
+    zpp = np.broadcast_to(np.stack([zp, zp]), (N, 2, V))
+    r = oracle.verify(zpp, np.broadcast_to(zq, (N, 1, V)), 1.0, d.token[:, None],
+                      np.ones(N, np.int64), ua, rng.random(N))
+    assert np.allclose(r.accept_prob[:, 0], np.minimum(1.0, p[d.token] / q[d.token]), rtol=1e-12)
+    freq = r.n_accepted.mean()
+    sigma = math.sqrt(st["beta"] * (1 - st["beta"]) / N)
+    assert abs(freq - st["beta"]) < 4.5 * sigma                             # Eq. beta
+    # per-token acceptance frequency = min(1, p/q)   (Appendix A, closing remark)
+    for x in range(V):
+        sel = d.token == x
+        a = min(1.0, p[x] / q[x])
+        s = math.sqrt(max(a * (1 - a), 1e-12) / sel.sum())
+        assert abs(r.n_accepted[sel].mean() - a) < 4.5 * s + 1e-9
+
+
+def test_kl_direction_and_bounds():
+    rng = _rng(8)
+    for _ in range(200):
+        V = int(rng.integers(2, 40))
+        zq, zp = rng.normal(0, rng.uniform(0.1, 4), V), rng.normal(0, rng.uniform(0.1, 4), V)
+        q, p = scipy.special.softmax(zq), scipy.special.softmax(zp)
+        st = oracle.pair_stats(zp, zq)
+        assert abs(st["kl"] - scipy.stats.entropy(q, p)) < 1e-10           # KL(q||p), not KL(p||q)
+        assert abs(st["kl"] - (st["hqp"] - st["hq"])) < 1e-10              # Eq. beta-bound
+        assert st["beta"] >= 1 - math.sqrt(0.5 * st["kl"]) - 1e-12         # Eq. pinsker
+        assert st["beta"] >= 1 - math.sqrt(1 - math.exp(-st["kl"])) - 1e-12  # Appendix B
+
+
+# ---------------------------------------------------------------- first rejection (Alg. 1 verification loop)
+
+def test_first_rejection_all_patterns():
+    k, V = 8, 4
+    rng = _rng(9)
+    zq = np.zeros((1, k, V))
+    zq[:, :, 0] = math.log(2.0)            # q = (.4, .2, .2, .2)
+    zp = np.zeros((1, k + 1, V))           # p = uniform: p/q = .625 at token 0
+    tok = np.zeros((1, k), np.int64)
+    for g in (0, 1, 5, 8):
+        for pattern in range(1 << g):
+            bits = [(pattern >> j) & 1 for j in range(k)]
+            ua = np.array([[0.3 if bits[j] else 0.9 for j in range(k)]])
+            r = oracle.verify(zp, zq, 1.0, tok, [g], ua, [rng.random()])
+            first = next((j for j in range(g) if not bits[j]), g)
+            assert r.n_accepted[0] == first
+            assert np.allclose(r.accept_prob[0, :g], 0.625)
+            if first < g:
+                assert r.next_token[0] != 0 and abs(r.resid_mass[0] - 0.15) < 1e-15
+            if g:
+                dec = [abs(ua[0, j] - 0.625) for j in range(min(first + 1, g))]
+                assert r.margin[0] <= min(dec) + 1e-12
+
+
+# ---------------------------------------------------------------- residual direction and the output law
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_output_law_equals_target_brute_force(seed):
+    """V = 8, 10^6 draft/verify/correct trials: emitted token ~ p (chi-square, 7 dof, 99.9 %).
+    The printed q - p residual (Algorithm 4 as typeset) fails the same test."""
+    rng = _rng(seed)
+    V, N = 8, 1_000_000
+    p, q = rng.dirichlet(np.ones(V)), rng.dirichlet(np.ones(V))
+    hist, nacc = oracle.sd_position_trials(p, q, N, seed, +1)
+    assert hist.sum() == N
+    assert ((hist - N * p) ** 2 / (N * p)).sum() < CHI2_7DOF_999
+    beta = np.minimum(p, q).sum()
+    assert abs(nacc / N - beta) < 4.5 * math.sqrt(beta * (1 - beta) / N)
+    bad, _ = oracle.sd_position_trials(p, q, N, seed, -1)
+    assert ((bad - N * p) ** 2 / (N * p)).sum() > 100 * CHI2_7DOF_999
+
+
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_output_law_through_the_entry_points(seed):
+    """Same law, but through draft_step + verify themselves (k = 1, one sequence per trial)."""
+    rng = _rng(seed)
+    V, N = 8, 1_000_000
+    zq, zp, zb = rng.normal(0, 1.2, V), rng.normal(0, 1.2, V), rng.normal(0, 1.2, V)
+    p, pb = scipy.special.softmax(zp), scipy.special.softmax(zb)
+    d = oracle.draft_step(np.broadcast_to(zq, (N, V)), 1.0, 0.3, 0, 40, rng.random(N))
+    r = oracle.verify(np.broadcast_to(np.stack([zp, zb]), (N, 2, V)),
+                      np.broadcast_to(zq, (N, 1, V)), 1.0, d.token[:, None],
+                      np.ones(N, np.int64), rng.random((N, 1)), rng.random(N))
+    acc = r.n_accepted == 1
+    emitted = np.where(acc, d.token, r.next_token)
+    hist = np.bincount(emitted, minlength=V)
+    assert ((hist - N * p) ** 2 / (N * p)).sum() < CHI2_7DOF_999
+    # bonus tokens (drawn when the draft was accepted) follow the next target row
+    nb = acc.sum()
+    hb = np.bincount(r.next_token[acc], minlength=V)
+    assert ((hb - nb * pb) ** 2 / (nb * pb)).sum() < CHI2_7DOF_999
+    # corrections never return a token with p <= q
+    q = scipy.special.softmax(zq)
+    assert np.all((p > q)[r.next_token[~acc]])
+
+
+def test_exact_output_law_enumeration():
+    """P(out = i) = min(p_i, q_i) + (1 - beta) w_i / W must equal p_i, with w from oracle_verify's
+    own residual (read back through resid_mass and forced corrections on a u grid)."""
+    rng = _rng(31)
+    V = 8
+    zq, zp = rng.normal(0, 1.5, V), rng.normal(0, 1.5, V)
+    q, p = scipy.special.softmax(zq), scipy.special.softmax(zp)
+    # force a rejection at position 0 (ua just below 1 with a token where p < q) and sweep ur
+    x = int(np.argmax(q - p))
+    grid = (np.arange(200_000) + 0.5) / 200_000
+    N = grid.size
+    r = oracle.verify(np.broadcast_to(np.stack([zp, zp]), (N, 2, V)), np.broadcast_to(zq, (N, 1, V)),
+                      1.0, np.full((N, 1), x), np.ones(N, np.int64),
+                      np.full((N, 1), np.nextafter(1.0, 0)), grid)
+    assert np.all(r.n_accepted == 0)
+    w_hat = np.bincount(r.next_token, minlength=V) / N        # law of the correction
+    beta = np.minimum(p, q).sum()
+    assert abs(r.resid_mass[0] - (1 - beta)) < 1e-14
+    out_law = np.minimum(p, q) + (1 - beta) * w_hat
+    assert np.allclose(out_law, p, atol=2.0 / N)
+
+
+def test_zero_residual_falls_back_to_target():
+    # p == q exactly, rejection cannot happen for u < 1; force the branch with gamma rows equal
+    # and an acceptance uniform of exactly 1.0 (outside [0,1), used only to reach the branch)
+    z = np.log(np.array([[0.1, 0.2, 0.3, 0.4]]))
+    r = oracle.verify(np.stack([z[0], z[0]])[None], z[None], 1.0, [[2]], [1], [[1.0]], [0.45])
+    assert r.n_accepted[0] == 0 and r.resid_mass[0] == 0.0
+    assert r.next_token[0] == 2 and r.margin[0] == 0.0
