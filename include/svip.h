@@ -1,0 +1,159 @@
+/*
+ * svip.h -- C ABI of the MI355X (gfx950) hot path of SVIP, the entropy-driven draft-length
+ * policy for speculative decoding of arXiv 2411.18462.
+ *
+ * Two calls cover the per-step vocabulary-wide work of one speculative round:
+ *
+ *   svip_draft_step   one draft position for every sequence still drafting: softmax of the
+ *                     draft logits, Shannon entropy, one sampled token, and the stop test
+ *                     sqrt(H_q) > h                     (Algorithm 1, drafting loop;
+ *                                                        Section 2.2, Eq. stop_condition)
+ *   svip_verify       the whole verification of a round: acceptance test r < p(x)/q(x) at
+ *                     every drafted position, first rejection, and either the correction
+ *                     drawn from the normalised residual max(0, p - q) or, if nothing was
+ *                     rejected, the bonus token drawn from the next target row
+ *                                                       (Algorithm 1, verification loop;
+ *                                                        Algorithm 2 Verify, Algorithm 4 Correct)
+ *
+ * General rules
+ *   - Every pointer marked "device" is GPU memory of the current HIP device; "host" is CPU
+ *     memory.  The caller owns every buffer; the library allocates nothing, frees nothing
+ *     and keeps no pointer after a call returns.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without synchronising.  Outputs are valid once the stream
+ *     has reached that point.
+ *   - Logits are row-major rows of V values, bf16 or fp32.  Base pointers must be 16-byte
+ *     aligned and every stride (in elements) a multiple of 16 bytes' worth of elements
+ *     (8 for bf16, 4 for fp32).  V itself may be any positive number.
+ *   - Arithmetic: fp32 per element with fp64 combination of partial results; entropies are
+ *     in nats; logits are divided by `temperature` before the softmax and H is the entropy
+ *     of that tempered distribution.  -inf logits carry no mass; a row with no finite logit
+ *     or with NaN has undefined results.
+ *   - "Sample from weights w with one uniform u" means: the smallest token index i whose
+ *     inclusive prefix sum w_0 + ... + w_i exceeds u * sum(w) (strict), in ascending index
+ *     order.  Uniforms are caller-supplied floats in [0, 1).
+ *   - Host-checkable argument errors return a status before anything is enqueued.  Errors in
+ *     device data (token id outside [0, V), draft length outside [0, k_max]) are clamped and
+ *     recorded in a sticky flag word inside the workspace (svip_workspace_flags).
+ *   - `workspace` is device scratch of at least svip_workspace_bytes(B, k_max, V) bytes,
+ *     256-byte aligned.  Calls that run concurrently must use different workspaces.
+ *   - Same inputs give bit-identical outputs (no floating-point atomics, fixed combine order).
+ */
+#ifndef SVIP_H
+#define SVIP_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SVIP_OK = 0,
+    SVIP_ERR_NULL = 1,       /* a required pointer is NULL */
+    SVIP_ERR_SHAPE = 2,      /* B, V, k_max, step_j or a stride out of range */
+    SVIP_ERR_DTYPE = 3,      /* dtype is not one of svip_dtype */
+    SVIP_ERR_ALIGN = 4,      /* base pointer or stride not 16-byte aligned */
+    SVIP_ERR_WORKSPACE = 5,  /* workspace NULL, misaligned or too small */
+    SVIP_ERR_PARAM = 6,      /* temperature <= 0 or not finite, h negative or NaN */
+    SVIP_ERR_HIP = 7         /* a HIP runtime call failed */
+} svip_status;
+
+typedef enum { SVIP_F32 = 0, SVIP_BF16 = 1 } svip_dtype;
+
+/* Bits of the sticky device-data flag word. */
+enum { SVIP_FLAG_BAD_TOKEN = 1, SVIP_FLAG_BAD_DRAFT_LEN = 2 };
+
+/* Largest k_max (draft positions per round) the library accepts. */
+#define SVIP_MAX_K 1024
+
+/* Human-readable name of a status; static storage, never freed. */
+const char *svip_status_string(int status);
+
+/* Bytes of device workspace that both calls need for batches of up to B sequences with up
+ * to k_max draft positions over a vocabulary of V.  Pure host function; 0 on bad arguments. */
+size_t svip_workspace_bytes(int B, int k_max, int V);
+
+/* Zero the sticky flag word (enqueued on the stream).  Call once after allocating a
+ * workspace; the two calls below only ever set bits. */
+svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Copy the flag word to *flags_host (host).  Synchronises the stream. */
+svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsigned *flags_host);
+
+/*
+ * One draft position for every sequence that is still drafting.
+ *
+ * For each row b in [0, B) with stop_in == NULL or stop_in[b] == 0:
+ *   q = softmax(draft_logits[b, :] / temperature)
+ *   H = -sum q ln q                                            (Section 2.2, H_q)
+ *   token ~ q with the uniform u_sample[b * io_stride]         (Algorithm 1, "Sample x ~ q")
+ *   stop = sqrt(H) > h  or  step_j + 1 >= k_max                (Eq. stop_condition; the cap
+ *                                                               is the paper's draft-length limit)
+ * and writes, at index b * io_stride of each per-row output array,
+ *   token_out, entropy_out = H, q_tok_out = q[token], lse_out = logsumexp(logits / temperature),
+ * plus stop_out[b] and, if draft_len_out != NULL, draft_len_out[b] = step_j + 1.
+ * Rows with stop_in[b] != 0 are not read; they get token_out = -1 and stop_out[b] = 1 and
+ * nothing else is written for them.
+ *
+ * io_stride lets the per-row arrays be columns of [B, k_max] buffers (pass the address of
+ * column step_j and io_stride = k_max), which is the layout svip_verify consumes; likewise
+ * draft_logits may point at position step_j of a [B, k_max, V] buffer with
+ * row_stride = k_max * V.  stop_out may alias stop_in (in-place update of one flag array
+ * across the steps of a round).  entropy_out and q_tok_out may be NULL.
+ */
+svip_status svip_draft_step(
+    const void *draft_logits,        /* device, row b at element offset b * row_stride */
+    svip_dtype dtype, int B, int V, long long row_stride,
+    float temperature, float h,
+    int step_j, int k_max,           /* 0 <= step_j < k_max <= SVIP_MAX_K */
+    const float *u_sample,           /* device, uniforms in [0,1), row b at b * io_stride */
+    const unsigned char *stop_in,    /* device [B] or NULL */
+    int *token_out,                  /* device, b * io_stride */
+    float *entropy_out,              /* device, b * io_stride, or NULL */
+    float *q_tok_out,                /* device, b * io_stride, or NULL */
+    double *lse_out,                 /* device, b * io_stride */
+    unsigned char *stop_out,         /* device [B] */
+    int *draft_len_out,              /* device [B] or NULL */
+    long long io_stride,             /* >= 1 */
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Verification of one round for every sequence.
+ *
+ * For each sequence b with g = draft_len[b] drafted tokens x_0..x_{g-1} (0 <= g <= k_max):
+ *   for j < g:  p_j = softmax(target_logits[b, j, :] / temperature),
+ *               q_j = softmax(draft_logits[b, j, :] / temperature),
+ *               accept_j = u_accept[b, j] * q_j(x_j) < p_j(x_j)         (Algorithm 2)
+ *               accept_prob_out[b, j] = min(1, p_j(x_j) / q_j(x_j))
+ *   r = first j with accept_j false, or g if there is none;  n_accepted_out[b] = r
+ *   if r < g:  next_token_out[b] ~ max(0, p_r - q_r) (normalised)       (Algorithm 4)
+ *              (if that residual has no mass: ~ p_r)
+ *   else:      next_token_out[b] ~ p_g, the target row after the drafts (Algorithm 1, bonus token)
+ *   both drawn with u_resample[b].
+ * Entries of accept_prob_out at j >= g are left untouched.
+ *
+ * draft_lse[b, j] = logsumexp(draft_logits[b, j, :] / temperature) as written by
+ * svip_draft_step; if NULL the library recomputes it, reading every drafted draft row.
+ * With draft_lse given, only the draft row at the rejected position is read.
+ */
+svip_status svip_verify(
+    const void *target_logits,       /* device, row (b, j) at b * seq_stride_t + j * row_stride, j <= k_max */
+    const void *draft_logits,        /* device, row (b, j) at b * seq_stride_d + j * row_stride, j <  k_max */
+    svip_dtype dtype, int B, int k_max, int V,
+    long long seq_stride_t, long long seq_stride_d, long long row_stride,
+    float temperature,
+    const int *draft_tokens,         /* device [B, k_max] */
+    const int *draft_len,            /* device [B] */
+    const double *draft_lse,         /* device [B, k_max] or NULL */
+    const float *u_accept,           /* device [B, k_max], uniforms in [0,1) */
+    const float *u_resample,         /* device [B], uniforms in [0,1) */
+    int *n_accepted_out,             /* device [B] */
+    int *next_token_out,             /* device [B] */
+    float *accept_prob_out,          /* device [B, k_max] or NULL */
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVIP_H */

@@ -1,0 +1,17 @@
+"""MI355X-native hot path of SVIP (arXiv 2411.18462): thin Python binding of libsvip.so.
+
+Every step of the path runs in the HIP kernels behind the C ABI of ``include/svip.h``; this
+package only marshals torch tensors (device memory, strides, the current HIP stream) into
+that ABI.  There is no CPU or PyTorch fallback: if the library has not been built, ``load()``
+raises.
+
+    import paper_2411_18462_amd as svip
+    ws = svip.new_workspace(B, k_max, V)
+    svip.draft_step(logits[:, j], ..., workspace=ws)      # Algorithm 1, drafting loop
+    svip.verify(target, draft, ..., workspace=ws)         # Algorithm 1, verification loop
+"""
+from .binding import (SvipError, draft_step, load, new_workspace, verify, workspace_bytes,
+                      workspace_flags, MAX_K, FLAG_BAD_TOKEN, FLAG_BAD_DRAFT_LEN)
+
+__all__ = ["SvipError", "draft_step", "load", "new_workspace", "verify", "workspace_bytes",
+           "workspace_flags", "MAX_K", "FLAG_BAD_TOKEN", "FLAG_BAD_DRAFT_LEN"]

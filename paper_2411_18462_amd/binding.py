@@ -1,0 +1,170 @@
+"""ctypes binding of libsvip.so: argument marshalling only (see include/svip.h)."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsvip.so")
+_lib = None
+
+MAX_K = 1024
+FLAG_BAD_TOKEN = 1
+FLAG_BAD_DRAFT_LEN = 2
+_DTYPES = {torch.float32: 0, torch.bfloat16: 1}
+
+# every symbol include/svip.h declares
+EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_reset",
+           "svip_workspace_flags", "svip_draft_step", "svip_verify")
+
+
+class SvipError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(text)
+        self.status = status
+
+
+def load():
+    """Load libsvip.so (built by ``paper_2411_18462_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is not built; run `python -m paper_2411_18462_amd.build` "
+            "(hipcc, gfx950).  There is no fallback path.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, ll, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_float, ctypes.c_size_t
+    lib.svip_status_string.restype = ctypes.c_char_p
+    lib.svip_status_string.argtypes = [i]
+    lib.svip_workspace_bytes.restype = sz
+    lib.svip_workspace_bytes.argtypes = [i, i, i]
+    lib.svip_workspace_reset.restype = i
+    lib.svip_workspace_reset.argtypes = [vp, sz, vp]
+    lib.svip_workspace_flags.restype = i
+    lib.svip_workspace_flags.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint)]
+    lib.svip_draft_step.restype = i
+    lib.svip_draft_step.argtypes = [vp, i, i, i, ll, f, f, i, i, vp, vp, vp, vp, vp, vp, vp, vp, ll, vp, sz, vp]
+    lib.svip_verify.restype = i
+    lib.svip_verify.argtypes = [vp, vp, i, i, i, i, ll, ll, ll, f, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise SvipError(status, load().svip_status_string(status).decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _col(t, B, dtype, name, stride=None):
+    """Pointer and row stride of a per-row array: a [B] tensor, possibly a column view."""
+    if t is None:
+        return None, stride
+    if t.dim() != 1 or t.shape[0] != B:
+        raise ValueError(f"{name} must have shape [{B}]")
+    s = t.stride(0) if B > 1 else (stride or 1)
+    if stride is not None and B > 1 and s != stride:
+        raise ValueError(f"{name}: all per-row arrays must share one stride ({s} vs {stride})")
+    return _ptr(t, dtype, name), s
+
+
+def workspace_bytes(B: int, k_max: int, V: int) -> int:
+    return int(load().svip_workspace_bytes(B, k_max, V))
+
+
+def new_workspace(B: int, k_max: int, V: int, device="cuda", stream=None) -> torch.Tensor:
+    """Allocate a workspace tensor for batches up to (B, k_max, V) and zero its flag word."""
+    n = workspace_bytes(B, k_max, V)
+    if n == 0:
+        raise SvipError(2, "svip_workspace_bytes: bad B, k_max or V")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    _check(load().svip_workspace_reset(ws.data_ptr(), n, _stream(stream)))
+    return ws
+
+
+def workspace_flags(workspace: torch.Tensor, stream=None) -> int:
+    out = ctypes.c_uint(0)
+    _check(load().svip_workspace_flags(workspace.data_ptr(), _stream(stream), ctypes.byref(out)))
+    return out.value
+
+
+def draft_step(draft_logits, *, temperature, h, step_j, k_max, u_sample, token_out, lse_out,
+               stop_out, workspace, stop_in=None, entropy_out=None, q_tok_out=None,
+               draft_len_out=None, stream=None):
+    """svip_draft_step.  draft_logits: [B, V] view (unit stride along V); u_sample, token_out,
+    entropy_out, q_tok_out, lse_out: [B] tensors or column views sharing one stride;
+    stop_in / stop_out / draft_len_out: contiguous [B]."""
+    if draft_logits.dim() != 2 or draft_logits.stride(1) != 1:
+        raise ValueError("draft_logits must be [B, V] with unit stride along V")
+    B, V = draft_logits.shape
+    row_stride = draft_logits.stride(0) if B > 1 else max(V, draft_logits.stride(0))
+    if draft_logits.dtype not in _DTYPES:
+        raise SvipError(3, "logits must be float32 or bfloat16")
+    pu, ios = _col(u_sample, B, torch.float32, "u_sample")
+    pt, ios = _col(token_out, B, torch.int32, "token_out", ios)
+    pe, ios = _col(entropy_out, B, torch.float32, "entropy_out", ios)
+    pq, ios = _col(q_tok_out, B, torch.float32, "q_tok_out", ios)
+    pl, ios = _col(lse_out, B, torch.float64, "lse_out", ios)
+    for t, n in ((stop_in, "stop_in"), (stop_out, "stop_out"), (draft_len_out, "draft_len_out")):
+        if t is not None and (t.dim() != 1 or t.shape[0] != B or not t.is_contiguous()):
+            raise ValueError(f"{n} must be contiguous [{B}]")
+    _check(load().svip_draft_step(
+        _ptr(draft_logits, None, "draft_logits"), _DTYPES[draft_logits.dtype], B, V, row_stride,
+        float(temperature), float(h), int(step_j), int(k_max), pu,
+        _ptr(stop_in, torch.uint8, "stop_in"), pt, pe, pq, pl,
+        _ptr(stop_out, torch.uint8, "stop_out"), _ptr(draft_len_out, torch.int32, "draft_len_out"),
+        ios or 1, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def verify(target_logits, draft_logits, *, temperature, draft_tokens, draft_len, u_accept,
+           u_resample, n_accepted_out, next_token_out, workspace, draft_lse=None,
+           accept_prob_out=None, stream=None):
+    """svip_verify.  target_logits [B, k+1, V], draft_logits [B, k, V] (unit stride along V,
+    equal stride along the position axis); [B, k] arrays contiguous."""
+    if target_logits.dim() != 3 or draft_logits.dim() != 3:
+        raise ValueError("logits must be [B, k+1, V] and [B, k, V]")
+    B, kp1, V = target_logits.shape
+    k = kp1 - 1
+    if tuple(draft_logits.shape) != (B, k, V):
+        raise ValueError(f"draft_logits must be [{B}, {k}, {V}]")
+    if target_logits.dtype != draft_logits.dtype or target_logits.dtype not in _DTYPES:
+        raise SvipError(3, "logits must both be float32 or both bfloat16")
+    if target_logits.stride(2) != 1 or draft_logits.stride(2) != 1:
+        raise ValueError("logits need unit stride along V")
+    row_stride = target_logits.stride(1)
+    if k > 1 and draft_logits.stride(1) != row_stride:
+        raise ValueError("target and draft logits must share the stride along the position axis")
+    seq_t = target_logits.stride(0) if B > 1 else kp1 * row_stride
+    seq_d = draft_logits.stride(0) if B > 1 else k * row_stride
+    for t, shape, n in ((draft_tokens, (B, k), "draft_tokens"), (draft_len, (B,), "draft_len"),
+                        (draft_lse, (B, k), "draft_lse"), (u_accept, (B, k), "u_accept"),
+                        (u_resample, (B,), "u_resample"), (n_accepted_out, (B,), "n_accepted_out"),
+                        (next_token_out, (B,), "next_token_out"), (accept_prob_out, (B, k), "accept_prob_out")):
+        if t is not None and (tuple(t.shape) != shape or not t.is_contiguous()):
+            raise ValueError(f"{n} must be contiguous {list(shape)}")
+    _check(load().svip_verify(
+        _ptr(target_logits, None, "target_logits"), _ptr(draft_logits, None, "draft_logits"),
+        _DTYPES[target_logits.dtype], B, k, V, seq_t, seq_d, row_stride, float(temperature),
+        _ptr(draft_tokens, torch.int32, "draft_tokens"), _ptr(draft_len, torch.int32, "draft_len"),
+        _ptr(draft_lse, torch.float64, "draft_lse"), _ptr(u_accept, torch.float32, "u_accept"),
+        _ptr(u_resample, torch.float32, "u_resample"), _ptr(n_accepted_out, torch.int32, "n_accepted_out"),
+        _ptr(next_token_out, torch.int32, "next_token_out"), _ptr(accept_prob_out, torch.float32, "accept_prob_out"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))

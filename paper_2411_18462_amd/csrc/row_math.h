@@ -1,0 +1,466 @@
+// Per-row building blocks of the SVIP kernels: 128-bit logit loads, the scaled exponential,
+// streaming softmax statistics of a row slice, and the in-slice inverse-CDF search.
+//
+// Geometry.  A row of V logits is cut into vectors of 16 bytes (8 bf16 / 4 fp32), tiles of
+// WG consecutive vectors (one per thread, so a wave reads 1 KiB contiguous), and `ns` slices
+// of `tps` consecutive tiles.  One workgroup handles one slice of one row.
+//
+// Arithmetic.  With c = log2(e)/T split into fp32 hi + lo parts, a logit z contributes
+// exp2((z - m) * c) relative to a reference m (statistics) or exp2(z * c - L) with
+// L = logsumexp * log2(e) (probabilities).  Both products use the hi/lo split so that the
+// rounding of c does not bias every term of a row in the same direction.  Per-element work
+// is fp32 (v_exp_f32); everything that combines partial sums is fp64.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "wave_ops.h"
+
+namespace svip {
+
+constexpr int WG = 256;              // threads per workgroup
+constexpr int NWAVE = WG / 64;
+constexpr int MAX_SLICES = 64;       // a wave merges one slice per lane
+constexpr int UNROLL = 8;            // vectors in flight per thread
+constexpr float X_FLOOR = -200.0f;   // exp2 of anything below is 0 in fp32; also squashes NaN from -inf logits
+
+struct bf16 { uint16_t bits; };
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename DT> struct VecOf;
+template <> struct VecOf<float> { static constexpr int N = 4; };
+template <> struct VecOf<bf16> { static constexpr int N = 8; };
+
+struct Geo {
+    int V;        // logits per row
+    int ntiles;   // ceil(ceil(V / N) / WG)
+    int ns;       // slices per row, <= MAX_SLICES
+    int tps;      // tiles per slice, ns * tps >= ntiles
+};
+
+struct Scale {
+    float c_hi, c_lo;   // log2(e) / T
+    double c;
+    double inv_T;
+};
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
+__device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// v_max_f32 / v_max3_f32 issued directly.  The instructions return the other operand when
+// one is NaN; going through fmaxf() instead makes the compiler quiet every input first
+// (one more instruction per logit).
+__device__ __forceinline__ float vmax(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// Raw 16-byte vector of a row: loaded first, unpacked to fp32 later, so that a batch of
+// loads is in flight before the first use.
+template <typename DT> struct RawOf;
+template <> struct RawOf<float> { typedef f32x4 type; };
+template <> struct RawOf<bf16> { typedef u32x4 type; };
+
+// Unchecked load of vector vi: every element must lie inside the row.
+template <typename DT>
+__device__ __forceinline__ typename RawOf<DT>::type load_raw(const DT *row, int vi)
+{
+    typedef typename RawOf<DT>::type R;
+    return __builtin_nontemporal_load(reinterpret_cast<const R *>(row) + vi);
+}
+
+// Checked load for the last, partial tile of a row: elements at or beyond V read as -inf and
+// nothing past the row is touched.
+__device__ __forceinline__ f32x4 load_raw_checked(const float *row, int vi, int V)
+{
+    const int base = vi * 4;
+    f32x4 r;
+    r.x = base + 0 < V ? row[base + 0] : neg_inf();
+    r.y = base + 1 < V ? row[base + 1] : neg_inf();
+    r.z = base + 2 < V ? row[base + 2] : neg_inf();
+    r.w = base + 3 < V ? row[base + 3] : neg_inf();
+    return r;
+}
+__device__ __forceinline__ u32x4 load_raw_checked(const bf16 *row, int vi, int V)
+{
+    const int base = vi * 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t lo = base + 2 * e < V ? row[base + 2 * e].bits : 0xFF80u;       // bf16 -inf
+        const uint32_t hi = base + 2 * e + 1 < V ? row[base + 2 * e + 1].bits : 0xFF80u;
+        w[e] = lo | (hi << 16);
+    }
+    u32x4 r;
+    r.x = w[0]; r.y = w[1]; r.z = w[2]; r.w = w[3];
+    return r;
+}
+
+__device__ __forceinline__ void unpack(const f32x4 &v, float (&z)[4])
+{
+    z[0] = v.x; z[1] = v.y; z[2] = v.z; z[3] = v.w;
+}
+__device__ __forceinline__ void unpack(const u32x4 &v, float (&z)[8])
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        z[2 * e] = __uint_as_float(w[e] << 16);
+        z[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+    }
+}
+
+template <typename DT>
+__device__ __forceinline__ float load_one(const DT *row, int i);
+template <>
+__device__ __forceinline__ float load_one<float>(const float *row, int i) { return row[i]; }
+template <>
+__device__ __forceinline__ float load_one<bf16>(const bf16 *row, int i)
+{
+    return __uint_as_float((uint32_t)row[i].bits << 16);
+}
+
+template <int N>
+__device__ __forceinline__ float tree_sum(const float (&v)[N])
+{
+    if constexpr (N == 4) {
+        return (v[0] + v[1]) + (v[2] + v[3]);
+    } else {
+        static_assert(N == 8, "vector width");
+        return ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+    }
+}
+template <int N>
+__device__ __forceinline__ float tree_max(const float (&v)[N])
+{
+    if constexpr (N == 4) {
+        return vmax(vmax3(v[0], v[1], v[2]), v[3]);
+    } else {
+        static_assert(N == 8, "vector width");
+        return vmax3(vmax3(v[0], v[1], v[2]), vmax3(v[3], v[4], v[5]), vmax(v[6], v[7]));
+    }
+}
+
+// (z - m) * c in exp2 units, floored (see X_FLOOR).
+__device__ __forceinline__ float scaled_diff(float z, float m, const Scale &sc)
+{
+    const float d = z - m;
+    return vmax(fmaf(d, sc.c_hi, d * sc.c_lo), X_FLOOR);
+}
+
+// Probability-like weight exp2(z * c - L), L given as fp32 hi + lo.
+struct ExpRef {
+    float c_hi, c_lo, L_hi, L_lo;
+    __device__ __forceinline__ float operator()(float z) const
+    {
+        const float x = fmaf(z, c_hi, -L_hi) + fmaf(z, c_lo, -L_lo);
+        return exp2_raw(vmax(x, X_FLOOR));
+    }
+};
+__device__ __forceinline__ ExpRef make_exp_ref(const Scale &sc, double L)
+{
+    ExpRef r;
+    r.c_hi = sc.c_hi;
+    r.c_lo = sc.c_lo;
+    r.L_hi = (float)L;
+    r.L_lo = (float)(L - (double)r.L_hi);
+    return r;
+}
+
+// Softmax statistics of a slice relative to its own maximum m:
+//   S = sum exp2((z - m) c),   t = sum exp2((z - m) c) * (z - m) c    (t only if WITH_T).
+struct Partial {
+    float m;
+    float pad;
+    double S;
+    double t;
+};
+
+// One batch of NU vectors per thread folded into the thread's running (m, S, t).
+template <int N, int NU, bool WITH_T>
+__device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, float &S, float &t,
+                                           const Scale &sc)
+{
+    float mb = tree_max<N>(z[0]);
+#pragma unroll
+    for (int u = 1; u < NU; ++u) mb = vmax(mb, tree_max<N>(z[u]));
+    if (mb > m) {
+        if (m != neg_inf()) {
+            const float xd = scaled_diff(m, mb, sc);
+            const float f = exp2_raw(xd);
+            if (WITH_T) t = f * fmaf(xd, S, t);
+            S *= f;
+        }
+        m = mb;
+    }
+    const float mref = (m == neg_inf()) ? 0.f : m;
+    float Sb = 0.f, tb = 0.f;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        float e[N], ex[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const float x = scaled_diff(z[u][i], mref, sc);
+            e[i] = exp2_raw(x);
+            if (WITH_T) ex[i] = e[i] * x;
+        }
+        // group sums are formed first, then added to the batch sum: the running sums only
+        // ever take one addition per batch
+        Sb += tree_sum<N>(e);
+        if (WITH_T) tb += tree_sum<N>(ex);
+    }
+    S += Sb;
+    if (WITH_T) t += tb;
+}
+
+template <typename DT, int NU, bool WITH_T>
+__device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, float &S, float &t,
+                                            const Scale &sc)
+{
+    constexpr int N = VecOf<DT>::N;
+    typename RawOf<DT>::type raw[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) raw[u] = load_raw<DT>(row, (t0 + u) * WG + (int)threadIdx.x);
+    float z[NU][N];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) unpack(raw[u], z[u]);
+    accumulate<N, NU, WITH_T>(z, m, S, t, sc);
+}
+
+// Streaming statistics of tiles [tb, te) of one row.  Every thread keeps a running maximum
+// of its own elements (rescaling its sums on the rare increase), so the loop has no
+// barrier; the workgroup combines at the end.  Tiles that lie wholly inside the row are read
+// in unchecked batches of 8/4/2/1 vectors per thread; only the row's last tile can be
+// partial and is read with bounds checks.  Result valid in thread 0.
+template <typename DT, bool WITH_T>
+__device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int te, const Scale &sc,
+                                               double *lds /* >= 2 * NWAVE doubles */)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x;
+    float m = neg_inf(), S = 0.f, t = 0.f;
+    const int fe = min(te, V / (WG * N));      // end of the tiles that are wholly inside the row
+    int t0 = tb;
+    for (; t0 + 8 <= fe; t0 += 8) stats_batch<DT, 8, WITH_T>(row, t0, m, S, t, sc);
+    if (t0 + 4 <= fe) { stats_batch<DT, 4, WITH_T>(row, t0, m, S, t, sc); t0 += 4; }
+    if (t0 + 2 <= fe) { stats_batch<DT, 2, WITH_T>(row, t0, m, S, t, sc); t0 += 2; }
+    if (t0 + 1 <= fe) { stats_batch<DT, 1, WITH_T>(row, t0, m, S, t, sc); t0 += 1; }
+    if (t0 < te) {
+        float z[1][N];
+        unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
+        accumulate<N, 1, WITH_T>(z, m, S, t, sc);
+    }
+
+    // workgroup maximum
+    const int wave = tid >> 6, lane = tid & 63;
+    float *ldsf = reinterpret_cast<float *>(lds);
+    const float mw = wave_max(m);
+    if (lane == 0) ldsf[wave] = mw;
+    __syncthreads();
+    float mg = ldsf[0];
+#pragma unroll
+    for (int w = 1; w < NWAVE; ++w) mg = fmaxf(mg, ldsf[w]);
+    __syncthreads();
+
+    // rescale every thread to the workgroup maximum and add up in fp64
+    double Sd = 0.0, td = 0.0;
+    if (m != neg_inf()) {
+        const float xd = scaled_diff(m, mg, sc);
+        const double f = (double)exp2_raw(xd);
+        Sd = f * (double)S;
+        if (WITH_T) td = f * ((double)t + (double)xd * (double)S);
+    }
+    Sd = wave_sum(Sd);
+    if (WITH_T) td = wave_sum(td);
+    if (lane == 0) {
+        lds[wave] = Sd;
+        lds[NWAVE + wave] = td;
+    }
+    __syncthreads();
+    Partial p;
+    p.m = mg;
+    p.pad = 0.f;
+    p.S = 0.0;
+    p.t = 0.0;
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) {
+            p.S += lds[w];
+            p.t += lds[NWAVE + w];
+        }
+    }
+    return p;
+}
+
+// Merge of up to MAX_SLICES slice partials by one wave (lane s holds slice s; lanes >= ns
+// pass m = -inf).  Returns wave-uniform reference m, and per lane the slice mass M and its
+// t-term, both relative to m; all in fp64.
+struct Merged {
+    float m;     // row maximum of the raw logits
+    double M;    // this lane's slice mass, sum exp2((z - m) c) over the slice
+    double tt;   // this lane's sum exp2((z - m) c) * (z - m) c
+};
+__device__ __forceinline__ Merged merge_lane(float ms, double Ss, double ts, const Scale &sc)
+{
+    Merged r;
+    r.m = wave_max(ms);
+    r.M = 0.0;
+    r.tt = 0.0;
+    if (ms != neg_inf() && Ss > 0.0) {
+        const double xd = ((double)ms - (double)r.m) * sc.c;
+        const double f = exp2(xd);
+        r.M = f * Ss;
+        r.tt = f * (ts + xd * Ss);
+    }
+    return r;
+}
+
+// ---- in-slice inverse CDF ---------------------------------------------------------
+//
+// Finds the smallest token index i inside tiles [tb, te) whose inclusive prefix of weights,
+// counted from the start of the slice, exceeds `target`.  Weights come from a functor wf:
+// wf.load(vi) / wf.load_checked(vi) fetch the raw vector(s) and wf.weights(pack, w) turns them
+// into the N weights of vector vi (fp32, >= 0).  Prefixes are fp64: 8-element group
+// sums in fp32, lanes -> waves -> tiles in fp64.  If rounding leaves no such index, the last
+// index of the slice with positive weight is returned (or -1 if the slice has no mass).
+// All threads of the workgroup must call; the result (token, its weight) is uniform.
+struct LocateLds {
+    double wtot[NWAVE][UNROLL];
+    int key;
+    int tok;
+    int last;
+    float w;
+};
+
+template <int N, typename WF>
+__device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double target, LocateLds &L,
+                                               float *weight_out)
+{
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    constexpr int NOKEY = 0x7FFFFFFF;
+    if (tid == 0) {
+        L.key = NOKEY;
+        L.tok = -1;
+        L.last = -1;
+        L.w = 0.f;
+    }
+    __syncthreads();
+    const int fe = min(te, wf.V / (WG * N));   // end of the tiles wholly inside the row
+    double run = 0.0;
+    int last = -1;
+    for (int t0 = tb; t0 < te; t0 += UNROLL) {
+        float w[UNROLL][N];
+        float g[UNROLL];
+        double incl[UNROLL];
+        typename WF::Pack pk[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (t0 + u < fe) pk[u] = wf.load((t0 + u) * WG + tid);
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            if (t0 + u < fe) {
+                wf.weights(pk[u], w[u]);
+            } else if (t0 + u < te) {
+                wf.weights(wf.load_checked((t0 + u) * WG + tid), w[u]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < N; ++e) w[u][e] = 0.f;
+            }
+            g[u] = tree_sum<N>(w[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) incl[u] = wave_inclusive_sum((double)g[u]);
+        if (lane == 63) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) L.wtot[wave][u] = incl[u];
+        }
+        __syncthreads();
+        double base = run;
+        int mykey = NOKEY, myu = 0;
+        double myexcl = 0.0;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            double before = 0.0, tot = 0.0;
+#pragma unroll
+            for (int w2 = 0; w2 < NWAVE; ++w2) {
+                const double x = L.wtot[w2][u];
+                if (w2 < wave) before += x;
+                tot += x;
+            }
+            const double P = base + before + incl[u];
+            if (mykey == NOKEY && g[u] > 0.f && P > target) {
+                mykey = u * WG + tid;
+                myu = u;
+                myexcl = base + before + (incl[u] - (double)g[u]);
+            }
+            base += tot;
+        }
+        if (mykey != NOKEY) atomicMin(&L.key, mykey);
+        __syncthreads();
+        const int key = L.key;
+        if (key != NOKEY) {
+            if (key == mykey) {
+                double C = myexcl;
+                int pick = -1;
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    if (u == myu) {
+                        int lastpos = -1;
+#pragma unroll
+                        for (int e = 0; e < N; ++e) {
+                            C += (double)w[u][e];
+                            if (w[u][e] > 0.f) {
+                                lastpos = e;
+                                if (pick < 0 && C > target) pick = e;
+                            }
+                        }
+                        if (pick < 0) pick = lastpos;
+                        L.tok = ((t0 + u) * WG + tid) * N + pick;
+                        float wv = 0.f;
+#pragma unroll
+                        for (int e = 0; e < N; ++e)
+                            if (e == pick) wv = w[u][e];
+                        L.w = wv;
+                    }
+                }
+            }
+            break;
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+#pragma unroll
+            for (int e = 0; e < N; ++e)
+                if (w[u][e] > 0.f) last = max(last, ((t0 + u) * WG + tid) * N + e);
+        }
+        run = base;
+        __syncthreads();
+    }
+    if (L.key == NOKEY) {      // uniform: nobody found a crossing
+        if (last >= 0) atomicMax(&L.last, last);
+        __syncthreads();
+        if (tid == 0 && L.last >= 0) {
+            float one[N];
+            wf.weights(wf.load_checked(L.last / N), one);
+            float wv = 0.f;
+#pragma unroll
+            for (int e = 0; e < N; ++e)
+                if (e == L.last % N) wv = one[e];
+            L.tok = L.last;
+            L.w = wv;
+        }
+    }
+    __syncthreads();
+    *weight_out = L.w;
+    return L.tok;
+}
+
+}  // namespace svip

@@ -1,0 +1,692 @@
+// SVIP hot path for MI355X (gfx950): kernels and the C ABI declared in include/svip.h.
+//
+// svip_draft_step  =  k_stats<WITH_T>   (grid: slices x rows)   per-slice (m, S, t)
+//                     k_draft_finish    (grid: rows)            merge, H, stop test, inverse CDF
+// svip_verify      =  k_stats           (grid: slices x target rows [+ draft rows])
+//                     k_accept          (grid: sequences, one wave)  p/q test, first rejection
+//                     k_resid_mass      (grid: slices x sequences)   residual / bonus slice masses
+//                     k_resid_finish    (grid: sequences)            inverse CDF of the residual
+//
+// The passes are bound by HBM reads of the logits; there is no dense contraction, hence no MFMA.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "../../include/svip.h"
+#include "row_math.h"
+
+namespace svip {
+
+// ---- workspace layout ----------------------------------------------------------------
+
+struct SeqRec {          // what k_accept hands to the residual kernels, one per sequence
+    double Lp;           // logsumexp(target row r) * log2(e)
+    double Lq;           // logsumexp(draft row r) * log2(e) (residual mode only)
+    int r;               // target row to sample from (first rejection, or draft_len for a bonus)
+    int resid;           // 1: residual of row r, 0: bonus from row r
+};
+
+struct Workspace {
+    unsigned *flags;     // sticky device-data flags
+    Partial *part;       // [rows][ns] slice statistics
+    SeqRec *rec;         // [B]
+    double *mass;        // [B][MAX_SLICES][2] residual mass, target mass per slice
+};
+
+constexpr size_t HEADER_BYTES = 256;
+__host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static size_t ws_part_bytes(int B, int k) { return align256((size_t)B * (2 * (size_t)k + 1) * MAX_SLICES * sizeof(Partial)); }
+static size_t ws_rec_bytes(int B) { return align256((size_t)B * sizeof(SeqRec)); }
+static size_t ws_mass_bytes(int B) { return align256((size_t)B * MAX_SLICES * 2 * sizeof(double)); }
+
+static Workspace carve(void *ws, int B, int k)
+{
+    char *p = static_cast<char *>(ws);
+    Workspace w;
+    w.flags = reinterpret_cast<unsigned *>(p);
+    p += HEADER_BYTES;
+    w.part = reinterpret_cast<Partial *>(p);
+    p += ws_part_bytes(B, k);
+    w.rec = reinterpret_cast<SeqRec *>(p);
+    p += ws_rec_bytes(B);
+    w.mass = reinterpret_cast<double *>(p);
+    return w;
+}
+
+// ---- kernel arguments ------------------------------------------------------------------
+
+struct DraftArgs {
+    const void *logits;
+    long long row_stride;
+    int B;
+    Geo geo;
+    Scale sc;
+    float h;
+    int step_j, k_max;
+    const float *u;
+    const unsigned char *stop_in;
+    int *token;
+    float *entropy;
+    float *q_tok;
+    double *lse;
+    unsigned char *stop;
+    int *draft_len;
+    long long io_stride;
+    Partial *part;
+};
+
+struct VerifyArgs {
+    const void *target;
+    const void *draft;
+    long long seq_t, seq_d, row_stride;
+    int B, k;
+    Geo geo;       // slicing of the statistics pass
+    Geo geo_s;     // slicing of the sampling pass (slices of at most UNROLL tiles when possible)
+    Scale sc;
+    const int *tokens;
+    const int *draft_len;
+    const double *draft_lse;
+    const float *u_accept;
+    const float *u_resample;
+    int *n_accepted;
+    int *next_token;
+    float *accept_prob;
+    Workspace ws;
+};
+
+__device__ __forceinline__ int clamp_len(int g, int k, unsigned *flags)
+{
+    if (g < 0 || g > k) {
+        atomicOr(flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
+        g = g < 0 ? 0 : k;
+    }
+    return g;
+}
+
+// ---- statistics pass ---------------------------------------------------------------------
+
+// Draft step: row y = sequence b.
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
+{
+    __shared__ double lds[2 * NWAVE];
+    const int s = blockIdx.x, b = blockIdx.y;
+    if (a.stop_in && a.stop_in[b]) return;
+    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
+    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    Partial p = slice_stats<DT, true>(row, a.geo.V, tb, te, a.sc, lds);
+    if (threadIdx.x == 0) a.part[(size_t)b * a.geo.ns + s] = p;
+}
+
+// Verify: rows y < B (k+1) are target rows (b, j), skipped when j > draft_len[b]; when the
+// draft logsumexps must be recomputed, rows y >= B (k+1) are draft rows (b, j), j < draft_len[b].
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
+{
+    __shared__ double lds[2 * NWAVE];
+    const int s = blockIdx.x;
+    int y = blockIdx.y;
+    const int nt = a.B * (a.k + 1);
+    const DT *row;
+    if (y < nt) {
+        const int b = y / (a.k + 1), j = y - b * (a.k + 1);
+        int g = a.draft_len[b];
+        g = g < 0 ? 0 : (g > a.k ? a.k : g);
+        if (j > g) return;
+        row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
+    } else {
+        const int yd = y - nt;
+        const int b = yd / a.k, j = yd - b * a.k;
+        int g = a.draft_len[b];
+        g = g < 0 ? 0 : (g > a.k ? a.k : g);
+        if (j >= g) return;
+        row = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)j * a.row_stride;
+    }
+    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    Partial p = slice_stats<DT, false>(row, a.geo.V, tb, te, a.sc, lds);
+    if (threadIdx.x == 0) a.ws.part[(size_t)y * a.geo.ns + s] = p;
+}
+
+// ---- weights for the inverse CDF ---------------------------------------------------------
+
+template <typename DT>
+struct SoftmaxWeights {        // w_i = exp2(z_i c - L)
+    typedef typename RawOf<DT>::type Pack;
+    const DT *row;
+    int V;
+    ExpRef ex;
+    __device__ __forceinline__ Pack load(int vi) const { return load_raw<DT>(row, vi); }
+    __device__ __forceinline__ Pack load_checked(int vi) const { return load_raw_checked(row, vi, V); }
+    __device__ __forceinline__ void weights(const Pack &pk, float (&w)[VecOf<DT>::N]) const
+    {
+        float z[VecOf<DT>::N];
+        unpack(pk, z);
+#pragma unroll
+        for (int e = 0; e < VecOf<DT>::N; ++e) w[e] = ex(z[e]);
+    }
+};
+
+template <typename DT>
+struct ResidualWeights {       // w_i = max(0, p_i - q_i), normalised p and q
+    struct Pack { typename RawOf<DT>::type p, q; };
+    const DT *prow, *qrow;
+    int V;
+    ExpRef exp_p, exp_q;
+    __device__ __forceinline__ Pack load(int vi) const
+    {
+        Pack pk;
+        pk.p = load_raw<DT>(prow, vi);
+        pk.q = load_raw<DT>(qrow, vi);
+        return pk;
+    }
+    __device__ __forceinline__ Pack load_checked(int vi) const
+    {
+        Pack pk;
+        pk.p = load_raw_checked(prow, vi, V);
+        pk.q = load_raw_checked(qrow, vi, V);
+        return pk;
+    }
+    __device__ __forceinline__ void weights(const Pack &pk, float (&w)[VecOf<DT>::N]) const
+    {
+        float zp[VecOf<DT>::N], zq[VecOf<DT>::N];
+        unpack(pk.p, zp);
+        unpack(pk.q, zq);
+#pragma unroll
+        for (int e = 0; e < VecOf<DT>::N; ++e) w[e] = fmaxf(exp_p(zp[e]) - exp_q(zq[e]), 0.f);
+    }
+};
+
+// Choice of the slice that contains `target` among per-lane slice masses M (lane order =
+// slice order).  Returns (uniform) the slice and the target relative to the slice start.
+__device__ __forceinline__ int pick_slice(double M, double target, double incl, double *local_target)
+{
+    const unsigned long long cross = __ballot(M > 0.0 && incl > target);
+    const unsigned long long mass = __ballot(M > 0.0);
+    int s;
+    if (cross) s = __ffsll((long long)cross) - 1;
+    else if (mass) s = 63 - __clzll((long long)mass);
+    else s = 0;
+    const double excl = read_lane(incl - M, s);
+    *local_target = target - excl;
+    return s;
+}
+
+// ---- draft step, second kernel --------------------------------------------------------------
+
+struct FinishLds {
+    LocateLds loc;
+    double target, L, S;
+    int slice;
+};
+
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_draft_finish(DraftArgs a)
+{
+    constexpr int N = VecOf<DT>::N;
+    __shared__ FinishLds sh;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const long long o = (long long)b * a.io_stride;
+    if (a.stop_in && a.stop_in[b]) {
+        if (tid == 0) {
+            a.token[o] = -1;
+            a.stop[b] = 1;
+        }
+        return;
+    }
+    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
+    double H = 0.0, lse = 0.0;
+    if (tid < 64) {
+        float ms = neg_inf();
+        double Ss = 0.0, ts = 0.0;
+        if (tid < a.geo.ns) {
+            const Partial p = a.part[(size_t)b * a.geo.ns + tid];
+            ms = p.m;
+            Ss = p.S;
+            ts = p.t;
+        }
+        const Merged mg = merge_lane(ms, Ss, ts, a.sc);
+        const double incl = wave_inclusive_sum(mg.M);
+        const double S = read_lane(incl, 63);
+        const double tt = wave_sum(mg.tt);
+        // H = ln S - (sum e x ln2) / S  for weights e = exp2(x): the entropy of e / S
+        const double lnS = log(S);
+        H = lnS - 0.6931471805599453 * tt / S;
+        H = H > 0.0 ? H : 0.0;
+        lse = (double)mg.m * a.sc.inv_T + lnS;
+        const double target = (double)a.u[o] * S;
+        double local;
+        const int s = pick_slice(mg.M, target, incl, &local);
+        if (tid == 0) {
+            sh.target = local;
+            sh.L = (double)mg.m * a.sc.c;
+            sh.S = S;
+            sh.slice = s;
+        }
+    }
+    __syncthreads();
+    SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, sh.L)};
+    const int tb = sh.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    float wtok;
+    const int tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    if (tid == 0) {
+        a.token[o] = tok;
+        if (a.entropy) a.entropy[o] = (float)H;
+        if (a.q_tok) a.q_tok[o] = (float)((double)wtok / sh.S);
+        a.lse[o] = lse;
+        const bool stop = (sqrt(H) > (double)a.h) || (a.step_j + 1 >= a.k_max);
+        a.stop[b] = stop ? 1 : 0;
+        if (a.draft_len) a.draft_len[b] = a.step_j + 1;
+    }
+}
+
+// ---- verify: acceptance test and first rejection -------------------------------------------
+
+// logsumexp * log2(e) of statistics row y, merged serially over its slices in fp64.
+__device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns, const Scale &sc)
+{
+    float m = neg_inf();
+    for (int s = 0; s < ns; ++s) m = fmaxf(m, part[y * ns + s].m);
+    double S = 0.0;
+    for (int s = 0; s < ns; ++s) {
+        const Partial p = part[y * ns + s];
+        if (p.m != neg_inf() && p.S > 0.0) S += p.S * exp2(((double)p.m - (double)m) * sc.c);
+    }
+    return (double)m * sc.c + log2(S);
+}
+
+template <typename DT>
+__global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int g = clamp_len(a.draft_len[b], a.k, a.ws.flags);
+    const DT *tgt = static_cast<const DT *>(a.target) + (long long)b * a.seq_t;
+    const DT *drf = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d;
+    const size_t yt = (size_t)b * (a.k + 1);
+    const size_t yd = (size_t)a.B * (a.k + 1) + (size_t)b * a.k;
+    constexpr double LOG2E = 1.4426950408889634;
+    int r = g;
+    double Lq_r = 0.0;
+    for (int j0 = 0; j0 < g; j0 += 64) {
+        const int j = j0 + lane;
+        bool reject = false;
+        double Lq = 0.0;
+        if (j < g) {
+            int x = a.tokens[(size_t)b * a.k + j];
+            if (x < 0 || x >= a.geo.V) {
+                atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_TOKEN);
+                x = x < 0 ? 0 : a.geo.V - 1;
+            }
+            const double Lp = row_L(a.ws.part, yt + j, a.geo.ns, a.sc);
+            Lq = a.draft_lse ? a.draft_lse[(size_t)b * a.k + j] * LOG2E
+                             : row_L(a.ws.part, yd + j, a.geo.ns, a.sc);
+            const double zp = (double)load_one<DT>(tgt + (long long)j * a.row_stride, x);
+            const double zq = (double)load_one<DT>(drf + (long long)j * a.row_stride, x);
+            const double p = exp2(zp * a.sc.c - Lp);
+            const double q = exp2(zq * a.sc.c - Lq);
+            const double u = (double)a.u_accept[(size_t)b * a.k + j];
+            reject = !(u * q < p);
+            if (a.accept_prob) {
+                const double ratio = q > 0.0 ? p / q : (p > 0.0 ? 1.0 : 0.0);
+                a.accept_prob[(size_t)b * a.k + j] = (float)(ratio < 1.0 ? ratio : 1.0);
+            }
+        }
+        const unsigned long long rej = __ballot(reject);
+        if (rej && r == g) {
+            const int first = __ffsll((long long)rej) - 1;
+            r = j0 + first;
+            Lq_r = read_lane(Lq, first);
+            if (!a.accept_prob) break;     // later positions cannot change the outputs
+        }
+    }
+    if (lane == 0) {
+        a.n_accepted[b] = r;
+        SeqRec rec;
+        rec.r = r;
+        rec.resid = r < g ? 1 : 0;
+        rec.Lp = row_L(a.ws.part, yt + r, a.geo.ns, a.sc);
+        rec.Lq = Lq_r;
+        a.ws.rec[b] = rec;
+    }
+}
+
+// ---- verify: residual / bonus sampling ------------------------------------------------------
+
+// One batch of NU vectors per thread of the rejected position's rows: adds the residual
+// mass max(0, p - q) (if RESID) and the target mass p of the batch.
+template <typename DT, int NU, bool RESID, bool CHECKED>
+__device__ __forceinline__ void mass_batch(const DT *prow, const DT *qrow, int V, int t0, const ExpRef &ep,
+                                           const ExpRef &eq, float &Wacc, float &Pacc)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x;
+    typename RawOf<DT>::type rp[NU], rq[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        const int vi = (t0 + u) * WG + tid;
+        rp[u] = CHECKED ? load_raw_checked(prow, vi, V) : load_raw<DT>(prow, vi);
+        if (RESID) rq[u] = CHECKED ? load_raw_checked(qrow, vi, V) : load_raw<DT>(qrow, vi);
+    }
+    float Wb = 0.f, Pb = 0.f;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        float zp[N], pw[N];
+        unpack(rp[u], zp);
+#pragma unroll
+        for (int e = 0; e < N; ++e) pw[e] = ep(zp[e]);
+        Pb += tree_sum<N>(pw);
+        if (RESID) {
+            float zq[N], w[N];
+            unpack(rq[u], zq);
+#pragma unroll
+            for (int e = 0; e < N; ++e) w[e] = fmaxf(pw[e] - eq(zq[e]), 0.f);
+            Wb += tree_sum<N>(w);
+        }
+    }
+    Wacc += Wb;
+    Pacc += Pb;
+}
+
+template <typename DT, bool RESID>
+__device__ __forceinline__ void slice_mass(const DT *prow, const DT *qrow, int V, int tb, int te,
+                                           const ExpRef &ep, const ExpRef &eq, float &Wacc, float &Pacc)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int fe = min(te, V / (WG * N));
+    int t0 = tb;
+    for (; t0 + 4 <= fe; t0 += 4) mass_batch<DT, 4, RESID, false>(prow, qrow, V, t0, ep, eq, Wacc, Pacc);
+    if (t0 + 2 <= fe) { mass_batch<DT, 2, RESID, false>(prow, qrow, V, t0, ep, eq, Wacc, Pacc); t0 += 2; }
+    if (t0 + 1 <= fe) { mass_batch<DT, 1, RESID, false>(prow, qrow, V, t0, ep, eq, Wacc, Pacc); t0 += 1; }
+    if (t0 < te) mass_batch<DT, 1, RESID, true>(prow, qrow, V, t0, ep, eq, Wacc, Pacc);
+}
+
+// Slice masses of the weights to sample from: [0] residual max(0, p - q), [1] target p.
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_resid_mass(VerifyArgs a)
+{
+    __shared__ double lds[2 * NWAVE];
+    const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const SeqRec rec = a.ws.rec[b];
+    const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
+    const DT *qrow = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)rec.r * a.row_stride;
+    const ExpRef ep = make_exp_ref(a.sc, rec.Lp), eq = make_exp_ref(a.sc, rec.Lq);
+    const int tb = s * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
+    float Wacc = 0.f, Pacc = 0.f;
+    if (rec.resid) slice_mass<DT, true>(prow, qrow, a.geo_s.V, tb, te, ep, eq, Wacc, Pacc);
+    else slice_mass<DT, false>(prow, qrow, a.geo_s.V, tb, te, ep, eq, Wacc, Pacc);
+    const double Wd = wave_sum((double)Wacc), Pd = wave_sum((double)Pacc);
+    const int wave = tid >> 6, lane = tid & 63;
+    if (lane == 0) {
+        lds[wave] = Wd;
+        lds[NWAVE + wave] = Pd;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double W = 0.0, P = 0.0;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) {
+            W += lds[w];
+            P += lds[NWAVE + w];
+        }
+        double *out = a.ws.mass + ((size_t)b * MAX_SLICES + s) * 2;
+        out[0] = W;
+        out[1] = P;
+    }
+}
+
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_resid_finish(VerifyArgs a)
+{
+    constexpr int N = VecOf<DT>::N;
+    __shared__ FinishLds sh;
+    __shared__ int use_resid;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const SeqRec rec = a.ws.rec[b];
+    if (tid < 64) {
+        double W = 0.0, P = 0.0;
+        if (tid < a.geo_s.ns) {
+            const double *in = a.ws.mass + ((size_t)b * MAX_SLICES + tid) * 2;
+            W = in[0];
+            P = in[1];
+        }
+        const double inclW = wave_inclusive_sum(W), inclP = wave_inclusive_sum(P);
+        const double totW = read_lane(inclW, 63), totP = read_lane(inclP, 63);
+        const bool resid = rec.resid && totW > 0.0;   // no residual mass: draw from the target row
+        const double M = resid ? W : P, incl = resid ? inclW : inclP, tot = resid ? totW : totP;
+        const double target = (double)a.u_resample[b] * tot;
+        double local;
+        const int s = pick_slice(M, target, incl, &local);
+        if (tid == 0) {
+            sh.target = local;
+            sh.slice = s;
+            use_resid = resid ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
+    const DT *qrow = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)rec.r * a.row_stride;
+    const int tb = sh.slice * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
+    float wtok;
+    int tok;
+    if (use_resid) {
+        ResidualWeights<DT> wf{prow, qrow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp), make_exp_ref(a.sc, rec.Lq)};
+        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    } else {
+        SoftmaxWeights<DT> wf{prow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp)};
+        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    }
+    if (tid == 0) a.next_token[b] = tok;
+}
+
+__global__ void k_zero_flags(unsigned *flags) { *flags = 0u; }
+
+// ---- host side -------------------------------------------------------------------------------
+
+static int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return v && *v ? atoi(v) : dflt;
+}
+
+// Slices per row: enough workgroups to fill 256 CUs several times over, at most MAX_SLICES,
+// and (want_one_batch) slices of at most UNROLL tiles so the sampler scans one batch.
+static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int forced_ns)
+{
+    Geo g;
+    g.V = V;
+    const int nvec = (V + vec - 1) / vec;
+    g.ntiles = (nvec + WG - 1) / WG;
+    long long ns = (2048 + rows - 1) / rows;          // aim at >= 2048 workgroups ...
+    if (ns * 4 > g.ntiles) ns = g.ntiles / 4;         // ... of at least 4 tiles each
+    if (want_one_batch) {
+        const long long need = (g.ntiles + UNROLL - 1) / UNROLL;
+        if (ns < need) ns = need;
+    }
+    if (forced_ns > 0) ns = forced_ns;
+    if (ns > MAX_SLICES) ns = MAX_SLICES;
+    if (ns > g.ntiles) ns = g.ntiles;
+    if (ns < 1) ns = 1;
+    g.tps = (g.ntiles + (int)ns - 1) / (int)ns;
+    g.ns = (g.ntiles + g.tps - 1) / g.tps;
+    return g;
+}
+
+static Scale make_scale(float temperature)
+{
+    Scale s;
+    s.inv_T = 1.0 / (double)temperature;
+    s.c = 1.4426950408889634 * s.inv_T;
+    s.c_hi = (float)s.c;
+    s.c_lo = (float)(s.c - (double)s.c_hi);
+    return s;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static svip_status check_launch()
+{
+    return hipGetLastError() == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
+}
+
+}  // namespace svip
+
+using namespace svip;
+
+extern "C" {
+
+const char *svip_status_string(int status)
+{
+    switch (status) {
+        case SVIP_OK: return "SVIP_OK";
+        case SVIP_ERR_NULL: return "SVIP_ERR_NULL: a required pointer is NULL";
+        case SVIP_ERR_SHAPE: return "SVIP_ERR_SHAPE: size, position or stride out of range";
+        case SVIP_ERR_DTYPE: return "SVIP_ERR_DTYPE: unknown logits dtype";
+        case SVIP_ERR_ALIGN: return "SVIP_ERR_ALIGN: pointer or stride not 16-byte aligned";
+        case SVIP_ERR_WORKSPACE: return "SVIP_ERR_WORKSPACE: workspace missing, misaligned or too small";
+        case SVIP_ERR_PARAM: return "SVIP_ERR_PARAM: temperature or threshold out of range";
+        case SVIP_ERR_HIP: return "SVIP_ERR_HIP: HIP runtime error";
+        default: return "SVIP: unknown status";
+    }
+}
+
+size_t svip_workspace_bytes(int B, int k_max, int V)
+{
+    if (B <= 0 || k_max < 1 || k_max > SVIP_MAX_K || V <= 0) return 0;
+    return HEADER_BYTES + ws_part_bytes(B, k_max) + ws_rec_bytes(B) + ws_mass_bytes(B);
+}
+
+svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!workspace || workspace_bytes < HEADER_BYTES || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return SVIP_ERR_WORKSPACE;
+    hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(1), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<unsigned *>(workspace));
+    return check_launch();
+}
+
+svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsigned *flags_host)
+{
+    if (!workspace) return SVIP_ERR_WORKSPACE;
+    if (!flags_host) return SVIP_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(flags_host, workspace, sizeof(unsigned), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return SVIP_ERR_HIP;
+    return hipStreamSynchronize(st) == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
+}
+
+svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+                            float temperature, float h, int step_j, int k_max, const float *u_sample,
+                            const unsigned char *stop_in, int *token_out, float *entropy_out,
+                            float *q_tok_out, double *lse_out, unsigned char *stop_out,
+                            int *draft_len_out, long long io_stride, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    if (!draft_logits || !u_sample || !token_out || !lse_out || !stop_out) return SVIP_ERR_NULL;
+    if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (B <= 0 || B > 65535 || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || step_j < 0 ||
+        step_j >= k_max || io_stride < 1 || row_stride < V)
+        return SVIP_ERR_SHAPE;
+    const int vec = dtype == SVIP_BF16 ? 8 : 4;
+    if (!aligned16(draft_logits) || row_stride % vec != 0) return SVIP_ERR_ALIGN;
+    if (!(temperature > 0.f) || !isfinite(temperature) || !(h >= 0.f)) return SVIP_ERR_PARAM;
+    // the workspace only has to hold this call's partials: B rows
+    const size_t need = HEADER_BYTES + align256((size_t)B * MAX_SLICES * sizeof(Partial));
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+        return SVIP_ERR_WORKSPACE;
+
+    DraftArgs a;
+    a.logits = draft_logits;
+    a.row_stride = row_stride;
+    a.B = B;
+    a.geo = make_geo(V, vec, B, true, env_int("SVIP_DRAFT_SLICES", 0));
+    a.sc = make_scale(temperature);
+    a.h = h;
+    a.step_j = step_j;
+    a.k_max = k_max;
+    a.u = u_sample;
+    a.stop_in = stop_in;
+    a.token = token_out;
+    a.entropy = entropy_out;
+    a.q_tok = q_tok_out;
+    a.lse = lse_out;
+    a.stop = stop_out;
+    a.draft_len = draft_len_out;
+    a.io_stride = io_stride;
+    a.part = reinterpret_cast<Partial *>(static_cast<char *>(workspace) + HEADER_BYTES);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid1(a.geo.ns, B), grid2(B);
+    if (dtype == SVIP_BF16) {
+        hipLaunchKernelGGL(k_draft_stats<bf16>, grid1, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_draft_finish<bf16>, grid2, dim3(WG), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(k_draft_stats<float>, grid1, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_draft_finish<float>, grid2, dim3(WG), 0, st, a);
+    }
+    return check_launch();
+}
+
+svip_status svip_verify(const void *target_logits, const void *draft_logits, svip_dtype dtype, int B,
+                        int k_max, int V, long long seq_stride_t, long long seq_stride_d,
+                        long long row_stride, float temperature, const int *draft_tokens,
+                        const int *draft_len, const double *draft_lse, const float *u_accept,
+                        const float *u_resample, int *n_accepted_out, int *next_token_out,
+                        float *accept_prob_out, void *workspace, size_t workspace_bytes,
+                        void *hip_stream)
+{
+    if (!target_logits || !draft_logits || !draft_tokens || !draft_len || !u_accept || !u_resample ||
+        !n_accepted_out || !next_token_out)
+        return SVIP_ERR_NULL;
+    if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (B <= 0 || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || row_stride < V ||
+        seq_stride_t < (long long)k_max * row_stride + V || seq_stride_d < (long long)(k_max - 1) * row_stride + V)
+        return SVIP_ERR_SHAPE;
+    const long long nrows = (long long)B * (2LL * k_max + 1);
+    if (nrows > 65535) return SVIP_ERR_SHAPE;          // grid.y limit of the statistics pass
+    const int vec = dtype == SVIP_BF16 ? 8 : 4;
+    if (!aligned16(target_logits) || !aligned16(draft_logits) || row_stride % vec != 0 ||
+        seq_stride_t % vec != 0 || seq_stride_d % vec != 0)
+        return SVIP_ERR_ALIGN;
+    if (!(temperature > 0.f) || !isfinite(temperature)) return SVIP_ERR_PARAM;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
+        workspace_bytes < svip_workspace_bytes(B, k_max, V))
+        return SVIP_ERR_WORKSPACE;
+
+    VerifyArgs a;
+    a.target = target_logits;
+    a.draft = draft_logits;
+    a.seq_t = seq_stride_t;
+    a.seq_d = seq_stride_d;
+    a.row_stride = row_stride;
+    a.B = B;
+    a.k = k_max;
+    const int stat_rows = B * (k_max + 1) + (draft_lse ? 0 : B * k_max);
+    a.geo = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    a.geo_s = make_geo(V, vec, B, true, env_int("SVIP_SAMPLE_SLICES", 0));
+    a.sc = make_scale(temperature);
+    a.tokens = draft_tokens;
+    a.draft_len = draft_len;
+    a.draft_lse = draft_lse;
+    a.u_accept = u_accept;
+    a.u_resample = u_resample;
+    a.n_accepted = n_accepted_out;
+    a.next_token = next_token_out;
+    a.accept_prob = accept_prob_out;
+    a.ws = carve(workspace, B, k_max);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 g_stats(a.geo.ns, stat_rows), g_seq(B), g_mass(a.geo_s.ns, B);
+    if (dtype == SVIP_BF16) {
+        hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_accept<bf16>, g_seq, dim3(64), 0, st, a);
+        hipLaunchKernelGGL(k_resid_mass<bf16>, g_mass, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_resid_finish<bf16>, g_seq, dim3(WG), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(k_verify_stats<float>, g_stats, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_accept<float>, g_seq, dim3(64), 0, st, a);
+        hipLaunchKernelGGL(k_resid_mass<float>, g_mass, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_resid_finish<float>, g_seq, dim3(WG), 0, st, a);
+    }
+    return check_launch();
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Wave64 cross-lane primitives for gfx950 built on DPP moves (no LDS traffic).
+//
+// A wave has 64 lanes in 4 DPP rows of 16.  row_reduce() leaves the combination of a row's
+// 16 values in every lane of that row (quad_perm xor-1, xor-2, then row rotations by 4 and
+// 8); wave_reduce() then combines the four row results read from lanes 15/31/47/63 with
+// v_readlane, so the result is wave-uniform and always associated in the same order.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace svip {
+
+constexpr int DPP_QUAD_XOR1 = 0xB1;   // quad_perm:[1,0,3,2]
+constexpr int DPP_QUAD_XOR2 = 0x4E;   // quad_perm:[2,3,0,1]
+constexpr int DPP_ROW_ROR4 = 0x124;   // row_ror:4
+constexpr int DPP_ROW_ROR8 = 0x128;   // row_ror:8
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __int_as_float(dpp_mov<CTRL>(__float_as_int(v)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov(double v)
+{
+    int lo = dpp_mov<CTRL>(__double2loint(v));
+    int hi = dpp_mov<CTRL>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ int read_lane(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ float read_lane(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ double read_lane(double v, int lane)
+{
+    int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+struct OpSum {
+    template <typename T> __device__ __forceinline__ T operator()(T a, T b) const { return a + b; }
+};
+struct OpMax {
+    __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); }
+    __device__ __forceinline__ int operator()(int a, int b) const { return a > b ? a : b; }
+};
+
+template <typename T, typename Op>
+__device__ __forceinline__ T row_reduce(T v, Op op)
+{
+    v = op(v, dpp_mov<DPP_QUAD_XOR1>(v));
+    v = op(v, dpp_mov<DPP_QUAD_XOR2>(v));
+    v = op(v, dpp_mov<DPP_ROW_ROR4>(v));
+    v = op(v, dpp_mov<DPP_ROW_ROR8>(v));
+    return v;
+}
+
+// Wave-uniform combination of all 64 lanes' values.
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_reduce(T v, Op op)
+{
+    v = row_reduce(v, op);
+    T r0 = read_lane(v, 15), r1 = read_lane(v, 31), r2 = read_lane(v, 47), r3 = read_lane(v, 63);
+    return op(op(r0, r1), op(r2, r3));
+}
+
+__device__ __forceinline__ float wave_max(float v) { return wave_reduce(v, OpMax{}); }
+__device__ __forceinline__ double wave_sum(double v) { return wave_reduce(v, OpSum{}); }
+
+// Inclusive prefix sum over the lanes of a wave (lane order), Hillis-Steele in fp64.
+__device__ __forceinline__ double wave_inclusive_sum(double v)
+{
+    const int lane = __lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        double o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+}  // namespace svip

@@ -1,0 +1,181 @@
+"""Shared pieces of the GPU parity tests: run a round through the C ABI, run the same round
+through the oracle, compare to the stated bar.
+
+Bar (from the benchmark spec): token ids, stop flags, accepted counts and corrected /
+bonus tokens must be identical to the fp64 oracle wherever the oracle's decision margin is at
+least MARGIN; entropies and probabilities must agree to REL.  Inside the margin the GPU's
+choice must still be a valid neighbour (its cell touches the threshold within 2 * MARGIN).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+
+MARGIN = 1e-6
+REL = 1e-4
+
+
+class Round:
+    """Device buffers of one speculative round in the layout the C ABI chains through."""
+
+    def __init__(self, svip, draft, target, u_sample, u_accept, u_resample, T, h):
+        self.svip = svip
+        self.draft = draft.cuda()
+        self.target = target.cuda()
+        self.B, self.k, self.V = self.draft.shape
+        self.T, self.h = T, h
+        dev = self.draft.device
+        B, k = self.B, self.k
+        self.u_sample = u_sample.cuda().contiguous()
+        self.u_accept = u_accept.cuda().contiguous()
+        self.u_resample = u_resample.cuda().contiguous()
+        self.tokens = torch.full((B, k), -7, dtype=torch.int32, device=dev)
+        self.entropy = torch.full((B, k), float("nan"), dtype=torch.float32, device=dev)
+        self.q_tok = torch.full((B, k), float("nan"), dtype=torch.float32, device=dev)
+        self.lse = torch.full((B, k), float("nan"), dtype=torch.float64, device=dev)
+        self.stop = torch.zeros(B, dtype=torch.uint8, device=dev)
+        self.stop_hist = torch.zeros(k, B, dtype=torch.uint8, device=dev)
+        self.draft_len = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.n_accepted = torch.full((B,), -7, dtype=torch.int32, device=dev)
+        self.next_token = torch.full((B,), -7, dtype=torch.int32, device=dev)
+        self.accept_prob = torch.full((B, k), float("nan"), dtype=torch.float32, device=dev)
+        self.ws = svip.new_workspace(B, k, self.V)
+
+    def draft_all(self, chain=True):
+        """k draft steps; chain=True threads the stop flags like Algorithm 1's drafting loop,
+        chain=False evaluates every position of every row."""
+        for j in range(self.k):
+            self.svip.draft_step(
+                self.draft[:, j], temperature=self.T, h=self.h, step_j=j, k_max=self.k,
+                u_sample=self.u_sample[:, j], stop_in=self.stop if chain else None,
+                token_out=self.tokens[:, j], entropy_out=self.entropy[:, j],
+                q_tok_out=self.q_tok[:, j], lse_out=self.lse[:, j],
+                stop_out=self.stop if chain else self.stop_hist[j],
+                draft_len_out=self.draft_len if chain else None, workspace=self.ws)
+            if chain:
+                self.stop_hist[j].copy_(self.stop)
+        torch.cuda.synchronize()
+
+    def verify(self, tokens=None, draft_len=None, lse="given"):
+        tok = self.tokens if tokens is None else tokens
+        dl = self.draft_len if draft_len is None else draft_len
+        self.svip.verify(
+            self.target, self.draft, temperature=self.T, draft_tokens=tok, draft_len=dl,
+            draft_lse=None if lse is None else (self.lse if isinstance(lse, str) else lse),
+            u_accept=self.u_accept, u_resample=self.u_resample,
+            n_accepted_out=self.n_accepted, next_token_out=self.next_token,
+            accept_prob_out=self.accept_prob, workspace=self.ws)
+        torch.cuda.synchronize()
+
+
+def cell_is_valid(prob, tok, u, tol):
+    """True if token `tok` is a legitimate draw for uniform u up to `tol` of cumulative mass."""
+    if tok < 0 or tok >= prob.size or not prob[tok] > 0:
+        return False
+    c = np.cumsum(prob)
+    lo = c[tok - 1] if tok > 0 else 0.0
+    t = u * c[-1]
+    return lo - tol * c[-1] <= t <= c[tok] + tol * c[-1]
+
+
+def check_draft_rows(draft_cpu, T, h, k_max, u_sample, gpu, rows=None, steps=None, stats=None):
+    """Compare unchained draft-step outputs of `gpu` (a Round after draft_all(chain=False))
+    with the oracle for rows x steps.  Returns a dict of counts."""
+    B, k, V = draft_cpu.shape
+    rows = range(B) if rows is None else rows
+    steps = range(k) if steps is None else steps
+    tok = gpu.tokens.cpu().numpy()
+    ent = gpu.entropy.cpu().numpy()
+    qt = gpu.q_tok.cpu().numpy()
+    lse = gpu.lse.cpu().numpy()
+    stop = gpu.stop_hist.cpu().numpy()
+    st = dict(rows=0, tok_excluded=0, tok_excluded_diff=0, stop_excluded=0,
+              max_rel_H=0.0, max_rel_q=0.0, max_abs_lse=0.0) if stats is None else stats
+    for j in steps:
+        idx = list(rows)
+        z = draft_cpu[idx, j].double().numpy()
+        o = oracle.draft_step(z, T, h, j, k_max, u_sample[idx, j].double().numpy())
+        for n, b in enumerate(idx):
+            st["rows"] += 1
+            where = f"row {b} step {j}"
+            if o.margin_s[n] >= MARGIN:
+                assert tok[b, j] == o.token[n], f"{where}: token {tok[b, j]} != oracle {o.token[n]} (margin {o.margin_s[n]:.3g})"
+            else:
+                st["tok_excluded"] += 1
+                if tok[b, j] != o.token[n]:
+                    st["tok_excluded_diff"] += 1
+                    p, _ = oracle.softmax_row(z[n], T)
+                    assert cell_is_valid(p, int(tok[b, j]), float(u_sample[b, j]), 2 * MARGIN), where
+            if o.margin_h[n] >= MARGIN:
+                assert stop[j, b] == o.stop[n], f"{where}: stop {stop[j, b]} != oracle {o.stop[n]}"
+            else:
+                st["stop_excluded"] += 1
+            H = o.entropy[n]
+            relH = abs(ent[b, j] - H) / max(H, 1e-30) if H > 0 else abs(ent[b, j])
+            assert relH <= REL or abs(ent[b, j] - H) <= 1e-9, f"{where}: H {ent[b, j]} vs {H}"
+            st["max_rel_H"] = max(st["max_rel_H"], relH if H > 1e-9 else 0.0)
+            st["max_abs_lse"] = max(st["max_abs_lse"], abs(lse[b, j] - o.lse[n]))
+            assert abs(lse[b, j] - o.lse[n]) <= 1e-5 * max(1.0, abs(o.lse[n])), f"{where}: lse"
+            if tok[b, j] == o.token[n]:
+                relq = abs(qt[b, j] - o.q_tok[n]) / max(o.q_tok[n], 1e-300)
+                assert relq <= REL or abs(qt[b, j] - o.q_tok[n]) <= 1e-37, f"{where}: q_tok {qt[b, j]} vs {o.q_tok[n]}"
+                st["max_rel_q"] = max(st["max_rel_q"], relq if o.q_tok[n] > 1e-37 else 0.0)
+    return st
+
+
+def oracle_chain(draft_cpu, T, h, u_sample):
+    """Algorithm 1's drafting loop through the oracle: tokens [B, k] (-1 where not drafted),
+    draft_len [B], lse [B, k], min decision margin per row over its drafted steps."""
+    B, k, V = draft_cpu.shape
+    tokens = np.full((B, k), -1, np.int64)
+    lse = np.zeros((B, k))
+    dl = np.zeros(B, np.int64)
+    margin = np.full(B, np.inf)
+    stop = np.zeros(B, np.uint8)
+    for j in range(k):
+        o = oracle.draft_step(draft_cpu[:, j].double().numpy(), T, h, j, k, u_sample[:, j].double().numpy(),
+                              stop_in=stop)
+        act = stop == 0
+        tokens[act, j] = o.token[act]
+        lse[act, j] = o.lse[act]
+        dl[act] = j + 1
+        margin[act] = np.minimum(margin[act], np.minimum(o.margin_h[act], o.margin_s[act]))
+        stop = o.stop.copy()
+    return tokens, dl, lse, margin
+
+
+def check_verify(draft_cpu, target_cpu, T, tokens, draft_len, u_accept, u_resample, gpu, rows=None,
+                 stats=None):
+    """Compare verify outputs of `gpu` with the oracle for sequences `rows`."""
+    B, k, V = draft_cpu.shape
+    rows = list(range(B)) if rows is None else list(rows)
+    nacc = gpu.n_accepted.cpu().numpy()
+    nxt = gpu.next_token.cpu().numpy()
+    ap = gpu.accept_prob.cpu().numpy()
+    st = dict(seqs=0, excluded=0, excluded_diff=0, max_rel_a=0.0) if stats is None else stats
+    for b in rows:
+        o = oracle.verify(target_cpu[b:b + 1].double().numpy(), draft_cpu[b:b + 1].double().numpy(), T,
+                          np.clip(tokens[b:b + 1], 0, V - 1), draft_len[b:b + 1],
+                          u_accept[b:b + 1].double().numpy(), u_resample[b:b + 1].double().numpy())
+        g = int(draft_len[b])
+        st["seqs"] += 1
+        where = f"sequence {b}"
+        a_ref = o.accept_prob[0, :g]
+        a_gpu = ap[b, :g].astype(np.float64)
+        rel = np.abs(a_gpu - a_ref) / np.maximum(a_ref, 1e-300)
+        ok = (rel <= REL) | (np.abs(a_gpu - a_ref) <= 1e-37)
+        assert ok.all(), f"{where}: accept_prob {a_gpu} vs {a_ref}"
+        if g:
+            st["max_rel_a"] = max(st["max_rel_a"], float(np.where(a_ref > 1e-37, rel, 0).max()))
+        assert np.isnan(ap[b, g:]).all(), f"{where}: accept_prob written beyond draft_len"
+        assert 0 <= nacc[b] <= g and 0 <= nxt[b] < V, where
+        if o.margin[0] >= MARGIN:
+            assert nacc[b] == o.n_accepted[0], f"{where}: n_accepted {nacc[b]} != {o.n_accepted[0]}"
+            assert nxt[b] == o.next_token[0], f"{where}: next_token {nxt[b]} != {o.next_token[0]} (margin {o.margin[0]:.3g})"
+        else:
+            st["excluded"] += 1
+            if nacc[b] != o.n_accepted[0] or nxt[b] != o.next_token[0]:
+                st["excluded_diff"] += 1
+    return st
