@@ -1,0 +1,291 @@
+#!/usr/bin/env python3
+"""Benchmark of the SVIP hot path on one MI355X.
+
+A step is one speculative round of the whole path over one batch: k_max chained
+svip_draft_step calls (stop flags threaded on the device) followed by svip_verify.
+Workload: BASELINE config 3 -- B = 64 sequences, V = 128256 bf16 logits, k_max = 16,
+T = 1.0, low/high-entropy row mixture, target = draft + N(0, 1.5^2) -- with the entropy
+threshold set above every synthetic row's sqrt(H), so every sequence drafts all k_max
+positions (only the cap stops it) and verification reads all 17 target rows of every
+sequence: the case the bandwidth target is quoted on.  An extra, untimed-in-`value` pass
+reports the same round under the threshold that separates the mixture (h = 3.0).
+
+Prints ONE JSON line (see the build contract): rows/s over the whole round, a `roofline`
+object for the dominant kernel (the statistics pass of svip_verify, timed with HIP events
+around every launch of the timed region) and a `cpu_baseline` object (the fp64 oracle on the
+host cores, on a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+H_FULL = 4.0               # above sqrt(ln V): no synthetic row stops before the cap
+NSETS = 2                  # input sets rotated between steps (2 x 542 MB > last-level cache)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch the draft steps eagerly")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences in the oracle sample (0 = auto)")
+    return ap.parse_args()
+
+
+class RoundBuffers:
+    def __init__(self, svip, w, draft, target, us, ua, ur):
+        import torch
+        self.svip, self.w = svip, w
+        self.draft, self.target = draft, target
+        B, k, V = draft.shape
+        self.B, self.k, self.V = B, k, V
+        dev = draft.device
+        self.us, self.ua, self.ur = us, ua, ur
+        self.tokens = torch.zeros(B, k, dtype=torch.int32, device=dev)
+        self.entropy = torch.zeros(B, k, dtype=torch.float32, device=dev)
+        self.q_tok = torch.zeros(B, k, dtype=torch.float32, device=dev)
+        self.lse = torch.zeros(B, k, dtype=torch.float64, device=dev)
+        self.stop = torch.zeros(B, dtype=torch.uint8, device=dev)
+        self.draft_len = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.n_accepted = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.next_token = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.accept_prob = torch.zeros(B, k, dtype=torch.float32, device=dev)
+        self.ws = svip.new_workspace(B, k, V)
+        self.graph = None
+
+    def draft_round(self, h):
+        """Algorithm 1's drafting loop, flags threaded on the device (no host sync)."""
+        self.stop.zero_()
+        for j in range(self.k):
+            self.svip.draft_step(
+                self.draft[:, j], temperature=self.w.T, h=h, step_j=j, k_max=self.k,
+                u_sample=self.us[:, j], stop_in=self.stop, token_out=self.tokens[:, j],
+                entropy_out=self.entropy[:, j], q_tok_out=self.q_tok[:, j], lse_out=self.lse[:, j],
+                stop_out=self.stop, draft_len_out=self.draft_len, workspace=self.ws)
+
+    def capture(self, h):
+        import torch
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.draft_round(h)
+        self.graph = g
+
+    def verify(self):
+        self.svip.verify(
+            self.target, self.draft, temperature=self.w.T, draft_tokens=self.tokens,
+            draft_len=self.draft_len, draft_lse=self.lse, u_accept=self.ua, u_resample=self.ur,
+            n_accepted_out=self.n_accepted, next_token_out=self.next_token,
+            accept_prob_out=self.accept_prob, workspace=self.ws)
+
+    def step(self, h):
+        if self.graph is not None:
+            self.graph.replay()
+        else:
+            self.draft_round(h)
+        self.verify()
+
+
+def timed(sets, h, steps, warmup, svip, profile):
+    import torch
+    for i in range(warmup):
+        sets[i % len(sets)].step(h)
+    torch.cuda.synchronize()
+    if profile:
+        svip.profile_begin(steps)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        sets[i % len(sets)].step(h)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern = svip.profile_end() if profile else (0.0, 0)
+    return dt, kern
+
+
+def cpu_baseline(w, h, nseq, threads):
+    """The fp64 oracle, as it stands, over `nseq` sequences of the same workload: the same
+    round (chained draft steps + verify) per sequence, sequences spread over host threads."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    import oracle
+    import svip_inputs as si
+    oracle.build()
+    T, hh = float(np.float32(w.T)), float(np.float32(h))
+
+    def one(b):
+        s = si.gen_sequence(w, b, seed=0)
+        zq = s["draft"].double().numpy()
+        zp = s["target"].double().numpy()
+        stop = np.zeros(1, np.uint8)
+        toks = np.zeros((1, w.k), np.int64)
+        g = 0
+        t0 = time.perf_counter()
+        for j in range(w.k):
+            if stop[0]:
+                break
+            o = oracle.draft_step(zq[j:j + 1], T, hh, j, w.k, s["u_sample"][j:j + 1].double().numpy())
+            toks[0, j] = o.token[0]
+            stop = o.stop
+            g = j + 1
+        oracle.verify(zp[None], zq[None], T, toks, np.array([g]), s["u_accept"][None].double().numpy(),
+                      s["u_resample"].reshape(1).double().numpy())
+        return time.perf_counter() - t0, 2 * g + 1
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        res = list(ex.map(one, range(nseq)))
+    wall = time.perf_counter() - t0
+    rows = sum(r[1] for r in res)
+    busy = sum(r[0] for r in res)
+    return rows, wall, busy
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards over sequences with no "
+              "exchange; see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2411_18462_amd as svip
+    import svip_inputs as si
+
+    svip.load()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    w = si.workload(a.workload)
+    t_gen = time.perf_counter()
+    batch = si.gen_batch(w, seed=0)
+    t_gen = time.perf_counter() - t_gen
+    dev = torch.device("cuda:0")
+    d0, t0 = batch["draft"].to(dev), batch["target"].to(dev)
+    us, ua, ur = batch["u_sample"].to(dev), batch["u_accept"].to(dev), batch["u_resample"].to(dev)
+    # further sets hold the same sequences in rotated order at other addresses
+    sets = [RoundBuffers(svip, w, d0, t0, us, ua, ur)]
+    for n in range(1, NSETS):
+        sets.append(RoundBuffers(svip, w, d0.roll(n, 0).contiguous(), t0.roll(n, 0).contiguous(),
+                                 us.roll(n, 0).contiguous(), ua.roll(n, 0).contiguous(),
+                                 ur.roll(n, 0).contiguous()))
+    B, k, V = sets[0].B, sets[0].k, sets[0].V
+    esz = d0.element_size()
+
+    def prepare(h):
+        for s in sets:
+            s.graph = None
+            s.step(h)                      # also warms allocator and caches before capture
+        torch.cuda.synchronize()
+        if not a.no_graph:
+            for s in sets:
+                s.capture(h)
+        torch.cuda.synchronize()
+
+    # ---- headline: every sequence drafts k_max positions ---------------------------------
+    prepare(H_FULL)
+    dt, (kern_ms, kern_n) = timed(sets, H_FULL, a.steps, a.warmup, svip, True)
+    dl = sets[0].draft_len.cpu().numpy().astype(np.int64)
+    nacc = sets[0].n_accepted.cpu().numpy()
+    assert (dl == k).all(), "headline workload must draft every position"
+    rows_per_step = int(dl.sum() + (dl + 1).sum())
+    n_rej = int((nacc < dl).sum())
+    stats_bytes = int((dl + 1).sum()) * V * esz          # target rows streamed by the statistics pass
+    verify_bytes = stats_bytes + n_rej * V * esz         # + the draft row at each rejection
+    draft_bytes = int(dl.sum()) * V * esz
+    kern_us = 1e3 * kern_ms / max(kern_n, 1)
+    achieved = stats_bytes / (kern_us * 1e-6) / 1e9 if kern_n else 0.0
+
+    # phases on their own (same buffers, same launch mode), for the record
+    def phase(fn, n):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(n):
+            fn(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n
+
+    n_ph = max(10, a.steps // 2)
+    t_draft = phase(lambda s: s.graph.replay() if s.graph is not None else s.draft_round(H_FULL), n_ph)
+    t_verify = phase(lambda s: s.verify(), n_ph)
+
+    # ---- the same round under the separating threshold (variable draft lengths) ----------
+    prepare(w.h)
+    dt_h, _ = timed(sets, w.h, max(10, a.steps // 2), 3, svip, False)
+    dl_h = sets[0].draft_len.cpu().numpy().astype(np.int64)
+    rows_h = int(dl_h.sum() + (dl_h + 1).sum())
+    steps_h = max(10, a.steps // 2)
+
+    out = {
+        "metric": "draft+verify rows/sec and achieved HBM GB/s (% peak) at V=128K bf16, B=64",
+        "value": rows_per_step * a.steps / dt,
+        "unit": "rows/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": 1e3 * dt / a.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: B={B} V={V} {w.dtype} logits, k_max={k}, T={w.T}, low/high-entropy mixture, "
+                        f"target=draft+N(0,{w.noise}^2); threshold h={H_FULL} so all {k} positions are drafted "
+                        f"and all {k + 1} target rows verified; {n_rej}/{B} sequences reject",
+            "rows_per_step": rows_per_step,
+            "draft_launch": "eager" if a.no_graph else "hip-graph of k_max svip_draft_step calls",
+            "input_sets_rotated": NSETS,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "k_verify_stats<bf16> (statistics pass of svip_verify)",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "bytes_per_launch": stats_bytes,
+            "avg_kernel_us": kern_us,
+            "launches_timed": kern_n,
+        },
+        "phases": {
+            "draft_round_us": 1e6 * t_draft,
+            "draft_GBps": draft_bytes / t_draft / 1e9,
+            "verify_us": 1e6 * t_verify,
+            "verify_GBps": verify_bytes / t_verify / 1e9,
+            "whole_round_GBps": (draft_bytes + verify_bytes) * a.steps / dt / 1e9,
+        },
+        "svip_policy_h3": {
+            "h": w.h,
+            "rows_per_step": rows_h,
+            "mean_draft_len": float(dl_h.mean()),
+            "rows_per_s": rows_h * steps_h / dt_h,
+            "ms_per_step": 1e3 * dt_h / steps_h,
+        },
+    }
+
+    if not a.no_cpu_baseline:
+        threads = min(16, os.cpu_count() or 1)
+        nseq = a.cpu_seqs or B
+        rows, wall, busy = cpu_baseline(w, H_FULL, nseq, threads)
+        out["cpu_baseline"] = {
+            "value": rows / wall,
+            "unit": "rows/s",
+            "cores": threads,
+            "kind": "oracle",
+            "sample": f"{nseq} of {B} sequences of the same round (chained draft steps + verify), "
+                      f"{rows} rows, {wall:.1f} s wall, {busy:.1f} s summed thread time",
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

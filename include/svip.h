@@ -153,6 +153,17 @@ svip_status svip_verify(
     float *accept_prob_out,          /* device [B, k_max] or NULL */
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Timing hook for benchmarks: between svip_profile_begin and svip_profile_end every
+ * svip_verify call brackets its statistics kernel (the pass that streams the target rows,
+ * the dominant kernel of the path) with HIP events on the call's stream, for at most
+ * max_samples calls.  svip_profile_end waits for those events, returns the summed kernel
+ * time in milliseconds and the number of samples through host pointers, and releases the
+ * events.  Process-wide state: not for concurrent use from several threads.
+ */
+svip_status svip_profile_begin(int max_samples);
+svip_status svip_profile_end(double *total_ms_host, int *samples_host);
+
 #ifdef __cplusplus
 }
 #endif

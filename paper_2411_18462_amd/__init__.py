@@ -11,7 +11,8 @@ raises.
     svip.verify(target, draft, ..., workspace=ws)         # Algorithm 1, verification loop
 """
 from .binding import (SvipError, draft_step, load, new_workspace, verify, workspace_bytes,
-                      workspace_flags, MAX_K, FLAG_BAD_TOKEN, FLAG_BAD_DRAFT_LEN)
+                      workspace_flags, profile_begin, profile_end, MAX_K, FLAG_BAD_TOKEN,
+                      FLAG_BAD_DRAFT_LEN)
 
 __all__ = ["SvipError", "draft_step", "load", "new_workspace", "verify", "workspace_bytes",
-           "workspace_flags", "MAX_K", "FLAG_BAD_TOKEN", "FLAG_BAD_DRAFT_LEN"]
+           "workspace_flags", "profile_begin", "profile_end", "MAX_K", "FLAG_BAD_TOKEN", "FLAG_BAD_DRAFT_LEN"]

@@ -17,7 +17,8 @@ _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 
 # every symbol include/svip.h declares
 EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_reset",
-           "svip_workspace_flags", "svip_draft_step", "svip_verify")
+           "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_profile_begin",
+           "svip_profile_end")
 
 
 class SvipError(RuntimeError):
@@ -49,6 +50,10 @@ def load():
     lib.svip_draft_step.argtypes = [vp, i, i, i, ll, f, f, i, i, vp, vp, vp, vp, vp, vp, vp, vp, ll, vp, sz, vp]
     lib.svip_verify.restype = i
     lib.svip_verify.argtypes = [vp, vp, i, i, i, i, ll, ll, ll, f, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.svip_profile_begin.restype = i
+    lib.svip_profile_begin.argtypes = [i]
+    lib.svip_profile_end.restype = i
+    lib.svip_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i)]
     _lib = lib
     return lib
 
@@ -168,3 +173,15 @@ def verify(target_logits, draft_logits, *, temperature, draft_tokens, draft_len,
         _ptr(u_resample, torch.float32, "u_resample"), _ptr(n_accepted_out, torch.int32, "n_accepted_out"),
         _ptr(next_token_out, torch.int32, "next_token_out"), _ptr(accept_prob_out, torch.float32, "accept_prob_out"),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def profile_begin(max_samples: int):
+    """Start timing the statistics kernel of the next `max_samples` verify calls."""
+    _check(load().svip_profile_begin(int(max_samples)))
+
+
+def profile_end():
+    """(total milliseconds, samples) of the statistics kernel since profile_begin."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
+    _check(load().svip_profile_end(ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value

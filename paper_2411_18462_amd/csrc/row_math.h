@@ -21,7 +21,8 @@ namespace svip {
 constexpr int WG = 256;              // threads per workgroup
 constexpr int NWAVE = WG / 64;
 constexpr int MAX_SLICES = 64;       // a wave merges one slice per lane
-constexpr int UNROLL = 8;            // vectors in flight per thread
+constexpr int UNROLL = 8;            // vectors in flight per thread in the statistics pass
+constexpr int LOCATE_UNROLL = 4;     // tiles per batch of the inverse-CDF search
 constexpr float X_FLOOR = -200.0f;   // exp2 of anything below is 0 in fp32; also squashes NaN from -inf logits
 
 struct bf16 { uint16_t bits; };
@@ -329,12 +330,12 @@ __device__ __forceinline__ Merged merge_lane(float ms, double Ss, double ts, con
 // Finds the smallest token index i inside tiles [tb, te) whose inclusive prefix of weights,
 // counted from the start of the slice, exceeds `target`.  Weights come from a functor wf:
 // wf.load(vi) / wf.load_checked(vi) fetch the raw vector(s) and wf.weights(pack, w) turns them
-// into the N weights of vector vi (fp32, >= 0).  Prefixes are fp64: 8-element group
+// into the N weights of vector vi (fp32, >= 0).  Prefixes are fp64: per-vector group
 // sums in fp32, lanes -> waves -> tiles in fp64.  If rounding leaves no such index, the last
 // index of the slice with positive weight is returned (or -1 if the slice has no mass).
 // All threads of the workgroup must call; the result (token, its weight) is uniform.
 struct LocateLds {
-    double wtot[NWAVE][UNROLL];
+    double wtot[NWAVE][LOCATE_UNROLL];
     int key;
     int tok;
     int last;
@@ -345,6 +346,7 @@ template <int N, typename WF>
 __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double target, LocateLds &L,
                                                float *weight_out)
 {
+    constexpr int LU = LOCATE_UNROLL;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     constexpr int NOKEY = 0x7FFFFFFF;
     if (tid == 0) {
@@ -357,16 +359,16 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
     const int fe = min(te, wf.V / (WG * N));   // end of the tiles wholly inside the row
     double run = 0.0;
     int last = -1;
-    for (int t0 = tb; t0 < te; t0 += UNROLL) {
-        float w[UNROLL][N];
-        float g[UNROLL];
-        double incl[UNROLL];
-        typename WF::Pack pk[UNROLL];
+    for (int t0 = tb; t0 < te; t0 += LU) {
+        float w[LU][N];
+        float g[LU];
+        double incl[LU];
+        typename WF::Pack pk[LU];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
+        for (int u = 0; u < LU; ++u)
             if (t0 + u < fe) pk[u] = wf.load((t0 + u) * WG + tid);
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+        for (int u = 0; u < LU; ++u) {
             if (t0 + u < fe) {
                 wf.weights(pk[u], w[u]);
             } else if (t0 + u < te) {
@@ -376,19 +378,21 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
                 for (int e = 0; e < N; ++e) w[u][e] = 0.f;
             }
             g[u] = tree_sum<N>(w[u]);
+            incl[u] = 0.0;
         }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) incl[u] = wave_inclusive_sum((double)g[u]);
+        for (int u = 0; u < LU; ++u)
+            if (t0 + u < te) incl[u] = wave_inclusive_sum((double)g[u]);
         if (lane == 63) {
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) L.wtot[wave][u] = incl[u];
+            for (int u = 0; u < LU; ++u) L.wtot[wave][u] = incl[u];
         }
         __syncthreads();
         double base = run;
         int mykey = NOKEY, myu = 0;
         double myexcl = 0.0;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+        for (int u = 0; u < LU; ++u) {
             double before = 0.0, tot = 0.0;
 #pragma unroll
             for (int w2 = 0; w2 < NWAVE; ++w2) {
@@ -412,7 +416,7 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
                 double C = myexcl;
                 int pick = -1;
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) {
+                for (int u = 0; u < LU; ++u) {
                     if (u == myu) {
                         int lastpos = -1;
 #pragma unroll
@@ -436,7 +440,7 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
             break;
         }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+        for (int u = 0; u < LU; ++u) {
 #pragma unroll
             for (int e = 0; e < N; ++e)
                 if (w[u][e] > 0.f) last = max(last, ((t0 + u) * WG + tid) * N + e);
@@ -461,6 +465,65 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
     __syncthreads();
     *weight_out = L.w;
     return L.tok;
+}
+
+// ---- "last workgroup finishes" -------------------------------------------------------
+//
+// Every workgroup of a group (the slices of a row, or all statistics workgroups of a
+// sequence) publishes its result, then calls arrive_last(); exactly one call per group -- the
+// one that arrives last -- returns true, after which that workgroup may fetch what the others
+// published.  The counter is left at zero for the next launch.
+//
+// Coherence across the XCDs' L2 caches without cache-wide write-backs: results are published
+// with device-scope atomic exchanges whose return values are awaited (so they have been
+// performed at the device's coherence point before the arrival counter is bumped), the
+// counter is a device-scope atomic, and the last workgroup fetches with device-scope atomic
+// loads, which do not hit in a non-coherent cache.
+__device__ __forceinline__ void publish64(unsigned long long *p, unsigned long long v)
+{
+    const unsigned long long old = __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" : : "v"((unsigned)old));     // keep the returning form of the atomic
+}
+__device__ __forceinline__ unsigned long long fetch64(const unsigned long long *p)
+{
+    return __hip_atomic_load(const_cast<unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_f64(double *p, double v)
+{
+    publish64(reinterpret_cast<unsigned long long *>(p), (unsigned long long)__double_as_longlong(v));
+}
+__device__ __forceinline__ double fetch_f64(const double *p)
+{
+    return __longlong_as_double((long long)fetch64(reinterpret_cast<const unsigned long long *>(p)));
+}
+__device__ __forceinline__ void publish_partial(Partial *slot, const Partial &p)
+{
+    publish64(reinterpret_cast<unsigned long long *>(&slot->m), (unsigned long long)__float_as_uint(p.m));
+    publish_f64(&slot->S, p.S);
+    publish_f64(&slot->t, p.t);
+}
+__device__ __forceinline__ Partial fetch_partial(const Partial *slot)
+{
+    Partial p;
+    p.m = __uint_as_float((unsigned)fetch64(reinterpret_cast<const unsigned long long *>(&slot->m)));
+    p.pad = 0.f;
+    p.S = fetch_f64(&slot->S);
+    p.t = fetch_f64(&slot->t);
+    return p;
+}
+
+// To be called by all threads after thread 0 has published the workgroup's result.
+__device__ __forceinline__ bool arrive_last(unsigned *counter, unsigned expected, int *lds_flag)
+{
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the exchanges above have returned
+        const unsigned old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = (old + 1u == expected);
+        if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *lds_flag = last ? 1 : 0;
+    }
+    __syncthreads();
+    return *lds_flag != 0;
 }
 
 }  // namespace svip

@@ -1,11 +1,13 @@
 // SVIP hot path for MI355X (gfx950): kernels and the C ABI declared in include/svip.h.
 //
-// svip_draft_step  =  k_stats<WITH_T>   (grid: slices x rows)   per-slice (m, S, t)
-//                     k_draft_finish    (grid: rows)            merge, H, stop test, inverse CDF
-// svip_verify      =  k_stats           (grid: slices x target rows [+ draft rows])
-//                     k_accept          (grid: sequences, one wave)  p/q test, first rejection
-//                     k_resid_mass      (grid: slices x sequences)   residual / bonus slice masses
-//                     k_resid_finish    (grid: sequences)            inverse CDF of the residual
+// svip_draft_step  =  k_draft   (grid: slices x rows)  per-slice (m, S, t); the workgroup that
+//                               finishes a row last merges its slices, applies the stop test
+//                               and locates the sampled token (inverse CDF)
+// svip_verify      =  k_verify  (grid: slices x target rows [+ draft rows])  per-slice (m, S);
+//                               the workgroup that finishes a sequence last runs the p/q
+//                               acceptance test and the ballot scan for the first rejection
+//                     k_resid   (grid: slices x sequences)  slice masses of the residual (or of
+//                               the bonus row); the last workgroup of a sequence locates the token
 //
 // The passes are bound by HBM reads of the logits; there is no dense contraction, hence no MFMA.
 #include <hip/hip_runtime.h>
@@ -20,7 +22,7 @@ namespace svip {
 
 // ---- workspace layout ----------------------------------------------------------------
 
-struct SeqRec {          // what k_accept hands to the residual kernels, one per sequence
+struct SeqRec {          // what the acceptance scan hands to the residual pass, one per sequence
     double Lp;           // logsumexp(target row r) * log2(e)
     double Lq;           // logsumexp(draft row r) * log2(e) (residual mode only)
     int r;               // target row to sample from (first rejection, or draft_len for a bonus)
@@ -29,12 +31,18 @@ struct SeqRec {          // what k_accept hands to the residual kernels, one per
 
 struct Workspace {
     unsigned *flags;     // sticky device-data flags
+    unsigned *cnt_a;     // [B] arrival counters: draft rows / verify sequences (zero between launches)
+    unsigned *cnt_b;     // [B] arrival counters of the residual pass
     Partial *part;       // [rows][ns] slice statistics
     SeqRec *rec;         // [B]
     double *mass;        // [B][MAX_SLICES][2] residual mass, target mass per slice
 };
 
-constexpr size_t HEADER_BYTES = 256;
+// Fixed header, independent of the batch: the flag word, then two arrays of MAX_BATCH arrival
+// counters.  svip_workspace_reset zeroes it; every launch leaves the counters at zero again.
+constexpr int MAX_BATCH = 65535;                 // also the grid.y limit of a launch
+constexpr size_t FLAG_BYTES = 256;
+constexpr size_t HEADER_BYTES = FLAG_BYTES + 2 * 65536 * sizeof(unsigned);
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static size_t ws_part_bytes(int B, int k) { return align256((size_t)B * (2 * (size_t)k + 1) * MAX_SLICES * sizeof(Partial)); }
@@ -46,6 +54,8 @@ static Workspace carve(void *ws, int B, int k)
     char *p = static_cast<char *>(ws);
     Workspace w;
     w.flags = reinterpret_cast<unsigned *>(p);
+    w.cnt_a = reinterpret_cast<unsigned *>(p + FLAG_BYTES);
+    w.cnt_b = w.cnt_a + 65536;
     p += HEADER_BYTES;
     w.part = reinterpret_cast<Partial *>(p);
     p += ws_part_bytes(B, k);
@@ -75,6 +85,7 @@ struct DraftArgs {
     int *draft_len;
     long long io_stride;
     Partial *part;
+    unsigned *cnt;
 };
 
 struct VerifyArgs {
@@ -83,7 +94,7 @@ struct VerifyArgs {
     long long seq_t, seq_d, row_stride;
     int B, k;
     Geo geo;       // slicing of the statistics pass
-    Geo geo_s;     // slicing of the sampling pass (slices of at most UNROLL tiles when possible)
+    Geo geo_s;     // slicing of the sampling pass (slices of at most LOCATE_UNROLL tiles when possible)
     Scale sc;
     const int *tokens;
     const int *draft_len;
@@ -103,50 +114,6 @@ __device__ __forceinline__ int clamp_len(int g, int k, unsigned *flags)
         g = g < 0 ? 0 : k;
     }
     return g;
-}
-
-// ---- statistics pass ---------------------------------------------------------------------
-
-// Draft step: row y = sequence b.
-template <typename DT>
-__global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
-{
-    __shared__ double lds[2 * NWAVE];
-    const int s = blockIdx.x, b = blockIdx.y;
-    if (a.stop_in && a.stop_in[b]) return;
-    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
-    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    Partial p = slice_stats<DT, true>(row, a.geo.V, tb, te, a.sc, lds);
-    if (threadIdx.x == 0) a.part[(size_t)b * a.geo.ns + s] = p;
-}
-
-// Verify: rows y < B (k+1) are target rows (b, j), skipped when j > draft_len[b]; when the
-// draft logsumexps must be recomputed, rows y >= B (k+1) are draft rows (b, j), j < draft_len[b].
-template <typename DT>
-__global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
-{
-    __shared__ double lds[2 * NWAVE];
-    const int s = blockIdx.x;
-    int y = blockIdx.y;
-    const int nt = a.B * (a.k + 1);
-    const DT *row;
-    if (y < nt) {
-        const int b = y / (a.k + 1), j = y - b * (a.k + 1);
-        int g = a.draft_len[b];
-        g = g < 0 ? 0 : (g > a.k ? a.k : g);
-        if (j > g) return;
-        row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
-    } else {
-        const int yd = y - nt;
-        const int b = yd / a.k, j = yd - b * a.k;
-        int g = a.draft_len[b];
-        g = g < 0 ? 0 : (g > a.k ? a.k : g);
-        if (j >= g) return;
-        row = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)j * a.row_stride;
-    }
-    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    Partial p = slice_stats<DT, false>(row, a.geo.V, tb, te, a.sc, lds);
-    if (threadIdx.x == 0) a.ws.part[(size_t)y * a.geo.ns + s] = p;
 }
 
 // ---- weights for the inverse CDF ---------------------------------------------------------
@@ -213,7 +180,7 @@ __device__ __forceinline__ int pick_slice(double M, double target, double incl, 
     return s;
 }
 
-// ---- draft step, second kernel --------------------------------------------------------------
+// ---- draft step -------------------------------------------------------------------------------
 
 struct FinishLds {
     LocateLds loc;
@@ -221,27 +188,20 @@ struct FinishLds {
     int slice;
 };
 
+// Merge of a row's slices, entropy and stop test, inverse CDF; run by the workgroup that
+// finished the row last.
 template <typename DT>
-__global__ __launch_bounds__(WG) void k_draft_finish(DraftArgs a)
+__device__ __forceinline__ void draft_finish(const DraftArgs &a, int b, const DT *row, FinishLds &sh)
 {
     constexpr int N = VecOf<DT>::N;
-    __shared__ FinishLds sh;
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const long long o = (long long)b * a.io_stride;
-    if (a.stop_in && a.stop_in[b]) {
-        if (tid == 0) {
-            a.token[o] = -1;
-            a.stop[b] = 1;
-        }
-        return;
-    }
-    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
     double H = 0.0, lse = 0.0;
     if (tid < 64) {
         float ms = neg_inf();
         double Ss = 0.0, ts = 0.0;
         if (tid < a.geo.ns) {
-            const Partial p = a.part[(size_t)b * a.geo.ns + tid];
+            const Partial p = fetch_partial(&a.part[(size_t)b * a.geo.ns + tid]);
             ms = p.m;
             Ss = p.S;
             ts = p.t;
@@ -281,26 +241,51 @@ __global__ __launch_bounds__(WG) void k_draft_finish(DraftArgs a)
     }
 }
 
+// grid (slices, rows): workgroup (s, b) streams slice s of row b.
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_draft(DraftArgs a)
+{
+    __shared__ double lds[2 * NWAVE];
+    __shared__ FinishLds sh;
+    __shared__ int last_flag;
+    const int s = blockIdx.x, b = blockIdx.y;
+    if (a.stop_in && a.stop_in[b]) {
+        if (s == 0 && threadIdx.x == 0) {
+            a.token[(long long)b * a.io_stride] = -1;
+            a.stop[b] = 1;
+        }
+        return;
+    }
+    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
+    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const Partial p = slice_stats<DT, true>(row, a.geo.V, tb, te, a.sc, lds);
+    if (threadIdx.x == 0) publish_partial(&a.part[(size_t)b * a.geo.ns + s], p);
+    if (!arrive_last(a.cnt + b, (unsigned)a.geo.ns, &last_flag)) return;
+    draft_finish<DT>(a, b, row, sh);
+}
+
 // ---- verify: acceptance test and first rejection -------------------------------------------
 
 // logsumexp * log2(e) of statistics row y, merged serially over its slices in fp64.
 __device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns, const Scale &sc)
 {
     float m = neg_inf();
-    for (int s = 0; s < ns; ++s) m = fmaxf(m, part[y * ns + s].m);
+    for (int s = 0; s < ns; ++s) m = fmaxf(m, fetch_partial(&part[y * ns + s]).m);
     double S = 0.0;
     for (int s = 0; s < ns; ++s) {
-        const Partial p = part[y * ns + s];
+        const Partial p = fetch_partial(&part[y * ns + s]);
         if (p.m != neg_inf() && p.S > 0.0) S += p.S * exp2(((double)p.m - (double)m) * sc.c);
     }
     return (double)m * sc.c + log2(S);
 }
 
+// Acceptance test at every drafted position of sequence b and first-rejection scan, by one
+// wave (lane = position, 64 positions per pass); run by the workgroup that finished the
+// sequence's statistics last.
 template <typename DT>
-__global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
+__device__ __forceinline__ void accept_scan(const VerifyArgs &a, int b, int g)
 {
-    const int b = blockIdx.x, lane = threadIdx.x;
-    const int g = clamp_len(a.draft_len[b], a.k, a.ws.flags);
+    const int lane = threadIdx.x;
     const DT *tgt = static_cast<const DT *>(a.target) + (long long)b * a.seq_t;
     const DT *drf = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d;
     const size_t yt = (size_t)b * (a.k + 1);
@@ -348,6 +333,47 @@ __global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
         rec.Lp = row_L(a.ws.part, yt + r, a.geo.ns, a.sc);
         rec.Lq = Lq_r;
         a.ws.rec[b] = rec;
+    }
+}
+
+// grid (slices, rows).  Rows y < B (k+1) are target rows (b, j), needed for j <= draft_len[b];
+// when the draft logsumexps must be recomputed, rows y >= B (k+1) are draft rows (b, j),
+// needed for j < draft_len[b].  Workgroups of rows that are not needed exit at once.
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_verify(VerifyArgs a)
+{
+    __shared__ double lds[2 * NWAVE];
+    __shared__ int last_flag;
+    const int s = blockIdx.x;
+    const int y = blockIdx.y;
+    const int nt = a.B * (a.k + 1);
+    const bool recompute = a.draft_lse == nullptr;
+    const DT *row;
+    int b, g;
+    if (y < nt) {
+        b = y / (a.k + 1);
+        const int j = y - b * (a.k + 1);
+        g = a.draft_len[b];
+        g = g < 0 ? 0 : (g > a.k ? a.k : g);
+        if (j > g) return;
+        row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
+    } else {
+        const int yd = y - nt;
+        b = yd / a.k;
+        const int j = yd - b * a.k;
+        g = a.draft_len[b];
+        g = g < 0 ? 0 : (g > a.k ? a.k : g);
+        if (j >= g) return;
+        row = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)j * a.row_stride;
+    }
+    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const Partial p = slice_stats<DT, false>(row, a.geo.V, tb, te, a.sc, lds);
+    if (threadIdx.x == 0) publish_partial(&a.ws.part[(size_t)y * a.geo.ns + s], p);
+    const unsigned expected = (unsigned)a.geo.ns * (unsigned)(g + 1 + (recompute ? g : 0));
+    if (!arrive_last(a.ws.cnt_a + b, expected, &last_flag)) return;
+    if (threadIdx.x < 64) {
+        clamp_len(a.draft_len[b], a.k, a.ws.flags);      // records an out-of-range draft length
+        accept_scan<DT>(a, b, g);
     }
 }
 
@@ -401,11 +427,57 @@ __device__ __forceinline__ void slice_mass(const DT *prow, const DT *qrow, int V
     if (t0 < te) mass_batch<DT, 1, RESID, true>(prow, qrow, V, t0, ep, eq, Wacc, Pacc);
 }
 
-// Slice masses of the weights to sample from: [0] residual max(0, p - q), [1] target p.
+// Choice between residual and target weights, slice selection and inverse CDF for
+// sequence b; run by the workgroup that finished the sequence's slice masses last.
 template <typename DT>
-__global__ __launch_bounds__(WG) void k_resid_mass(VerifyArgs a)
+__device__ __forceinline__ void resid_finish(const VerifyArgs &a, int b, const SeqRec &rec, const DT *prow,
+                                             const DT *qrow, FinishLds &sh, int *use_resid)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x;
+    if (tid < 64) {
+        double W = 0.0, P = 0.0;
+        if (tid < a.geo_s.ns) {
+            const double *in = a.ws.mass + ((size_t)b * MAX_SLICES + tid) * 2;
+            W = fetch_f64(in);
+            P = fetch_f64(in + 1);
+        }
+        const double inclW = wave_inclusive_sum(W), inclP = wave_inclusive_sum(P);
+        const double totW = read_lane(inclW, 63), totP = read_lane(inclP, 63);
+        const bool resid = rec.resid && totW > 0.0;   // no residual mass: draw from the target row
+        const double M = resid ? W : P, incl = resid ? inclW : inclP, tot = resid ? totW : totP;
+        const double target = (double)a.u_resample[b] * tot;
+        double local;
+        const int s = pick_slice(M, target, incl, &local);
+        if (tid == 0) {
+            sh.target = local;
+            sh.slice = s;
+            *use_resid = resid ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    const int tb = sh.slice * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
+    float wtok;
+    int tok;
+    if (*use_resid) {
+        ResidualWeights<DT> wf{prow, qrow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp), make_exp_ref(a.sc, rec.Lq)};
+        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    } else {
+        SoftmaxWeights<DT> wf{prow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp)};
+        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    }
+    if (tid == 0) a.next_token[b] = tok;
+}
+
+// grid (slices, sequences): slice masses of the weights to sample from -- [0] residual
+// max(0, p - q) at the rejected position, [1] target p of the row to sample -- then the last
+// workgroup of the sequence draws the token.
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_resid(VerifyArgs a)
 {
     __shared__ double lds[2 * NWAVE];
+    __shared__ FinishLds sh;
+    __shared__ int last_flag, use_resid;
     const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const SeqRec rec = a.ws.rec[b];
     const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
@@ -430,56 +502,19 @@ __global__ __launch_bounds__(WG) void k_resid_mass(VerifyArgs a)
             P += lds[NWAVE + w];
         }
         double *out = a.ws.mass + ((size_t)b * MAX_SLICES + s) * 2;
-        out[0] = W;
-        out[1] = P;
+        publish_f64(out, W);
+        publish_f64(out + 1, P);
     }
+    if (!arrive_last(a.ws.cnt_b + b, (unsigned)a.geo_s.ns, &last_flag)) return;
+    resid_finish<DT>(a, b, rec, prow, qrow, sh, &use_resid);
 }
 
-template <typename DT>
-__global__ __launch_bounds__(WG) void k_resid_finish(VerifyArgs a)
+__global__ void k_zero_header(unsigned *flags, unsigned *cnt, int n)
 {
-    constexpr int N = VecOf<DT>::N;
-    __shared__ FinishLds sh;
-    __shared__ int use_resid;
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const SeqRec rec = a.ws.rec[b];
-    if (tid < 64) {
-        double W = 0.0, P = 0.0;
-        if (tid < a.geo_s.ns) {
-            const double *in = a.ws.mass + ((size_t)b * MAX_SLICES + tid) * 2;
-            W = in[0];
-            P = in[1];
-        }
-        const double inclW = wave_inclusive_sum(W), inclP = wave_inclusive_sum(P);
-        const double totW = read_lane(inclW, 63), totP = read_lane(inclP, 63);
-        const bool resid = rec.resid && totW > 0.0;   // no residual mass: draw from the target row
-        const double M = resid ? W : P, incl = resid ? inclW : inclP, tot = resid ? totW : totP;
-        const double target = (double)a.u_resample[b] * tot;
-        double local;
-        const int s = pick_slice(M, target, incl, &local);
-        if (tid == 0) {
-            sh.target = local;
-            sh.slice = s;
-            use_resid = resid ? 1 : 0;
-        }
-    }
-    __syncthreads();
-    const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
-    const DT *qrow = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)rec.r * a.row_stride;
-    const int tb = sh.slice * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
-    float wtok;
-    int tok;
-    if (use_resid) {
-        ResidualWeights<DT> wf{prow, qrow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp), make_exp_ref(a.sc, rec.Lq)};
-        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
-    } else {
-        SoftmaxWeights<DT> wf{prow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp)};
-        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
-    }
-    if (tid == 0) a.next_token[b] = tok;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) *flags = 0u;
+    if (i < n) cnt[i] = 0u;
 }
-
-__global__ void k_zero_flags(unsigned *flags) { *flags = 0u; }
 
 // ---- host side -------------------------------------------------------------------------------
 
@@ -490,7 +525,7 @@ static int env_int(const char *name, int dflt)
 }
 
 // Slices per row: enough workgroups to fill 256 CUs several times over, at most MAX_SLICES,
-// and (want_one_batch) slices of at most UNROLL tiles so the sampler scans one batch.
+// and (want_one_batch) slices of at most LOCATE_UNROLL tiles so the sampler scans one batch.
 static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int forced_ns)
 {
     Geo g;
@@ -500,7 +535,7 @@ static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int for
     long long ns = (2048 + rows - 1) / rows;          // aim at >= 2048 workgroups ...
     if (ns * 4 > g.ntiles) ns = g.ntiles / 4;         // ... of at least 4 tiles each
     if (want_one_batch) {
-        const long long need = (g.ntiles + UNROLL - 1) / UNROLL;
+        const long long need = (g.ntiles + LOCATE_UNROLL - 1) / LOCATE_UNROLL;
         if (ns < need) ns = need;
     }
     if (forced_ns > 0) ns = forced_ns;
@@ -528,6 +563,13 @@ static svip_status check_launch()
 {
     return hipGetLastError() == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
 }
+
+// benchmark timing hook (see svip_profile_begin)
+struct Profile {
+    hipEvent_t *ev = nullptr;   // pairs: start, stop
+    int cap = 0, used = 0;
+};
+static Profile g_prof;
 
 }  // namespace svip
 
@@ -560,8 +602,10 @@ svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *
 {
     if (!workspace || workspace_bytes < HEADER_BYTES || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return SVIP_ERR_WORKSPACE;
-    hipLaunchKernelGGL(k_zero_flags, dim3(1), dim3(1), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<unsigned *>(workspace));
+    unsigned *flags = static_cast<unsigned *>(workspace);
+    unsigned *cnt = reinterpret_cast<unsigned *>(static_cast<char *>(workspace) + FLAG_BYTES);
+    hipLaunchKernelGGL(k_zero_header, dim3(2 * 65536 / 256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       flags, cnt, 2 * 65536);
     return check_launch();
 }
 
@@ -584,7 +628,7 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
 {
     if (!draft_logits || !u_sample || !token_out || !lse_out || !stop_out) return SVIP_ERR_NULL;
     if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
-    if (B <= 0 || B > 65535 || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || step_j < 0 ||
+    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || step_j < 0 ||
         step_j >= k_max || io_stride < 1 || row_stride < V)
         return SVIP_ERR_SHAPE;
     const int vec = dtype == SVIP_BF16 ? 8 : 4;
@@ -614,15 +658,11 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
     a.draft_len = draft_len_out;
     a.io_stride = io_stride;
     a.part = reinterpret_cast<Partial *>(static_cast<char *>(workspace) + HEADER_BYTES);
+    a.cnt = reinterpret_cast<unsigned *>(static_cast<char *>(workspace) + FLAG_BYTES);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid1(a.geo.ns, B), grid2(B);
-    if (dtype == SVIP_BF16) {
-        hipLaunchKernelGGL(k_draft_stats<bf16>, grid1, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_draft_finish<bf16>, grid2, dim3(WG), 0, st, a);
-    } else {
-        hipLaunchKernelGGL(k_draft_stats<float>, grid1, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_draft_finish<float>, grid2, dim3(WG), 0, st, a);
-    }
+    const dim3 grid(a.geo.ns, B);
+    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_draft<bf16>, grid, dim3(WG), 0, st, a);
+    else hipLaunchKernelGGL(k_draft<float>, grid, dim3(WG), 0, st, a);
     return check_launch();
 }
 
@@ -674,19 +714,57 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
     a.accept_prob = accept_prob_out;
     a.ws = carve(workspace, B, k_max);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 g_stats(a.geo.ns, stat_rows), g_seq(B), g_mass(a.geo_s.ns, B);
-    if (dtype == SVIP_BF16) {
-        hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_accept<bf16>, g_seq, dim3(64), 0, st, a);
-        hipLaunchKernelGGL(k_resid_mass<bf16>, g_mass, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_resid_finish<bf16>, g_seq, dim3(WG), 0, st, a);
-    } else {
-        hipLaunchKernelGGL(k_verify_stats<float>, g_stats, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_accept<float>, g_seq, dim3(64), 0, st, a);
-        hipLaunchKernelGGL(k_resid_mass<float>, g_mass, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_resid_finish<float>, g_seq, dim3(WG), 0, st, a);
+    const dim3 g_stats(a.geo.ns, stat_rows), g_mass(a.geo_s.ns, B);
+    const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
+    if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], st);
+    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify<bf16>, g_stats, dim3(WG), 0, st, a);
+    else hipLaunchKernelGGL(k_verify<float>, g_stats, dim3(WG), 0, st, a);
+    if (timed) {
+        (void)hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st);
+        ++g_prof.used;
     }
+    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_resid<bf16>, g_mass, dim3(WG), 0, st, a);
+    else hipLaunchKernelGGL(k_resid<float>, g_mass, dim3(WG), 0, st, a);
     return check_launch();
+}
+
+svip_status svip_profile_begin(int max_samples)
+{
+    if (max_samples < 1 || g_prof.ev) return SVIP_ERR_PARAM;
+    g_prof.ev = static_cast<hipEvent_t *>(malloc(sizeof(hipEvent_t) * 2 * (size_t)max_samples));
+    if (!g_prof.ev) return SVIP_ERR_HIP;
+    for (int i = 0; i < 2 * max_samples; ++i) {
+        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
+            free(g_prof.ev);
+            g_prof = Profile();
+            return SVIP_ERR_HIP;
+        }
+    }
+    g_prof.cap = max_samples;
+    g_prof.used = 0;
+    return SVIP_OK;
+}
+
+svip_status svip_profile_end(double *total_ms_host, int *samples_host)
+{
+    if (!total_ms_host || !samples_host) return SVIP_ERR_NULL;
+    if (!g_prof.ev) return SVIP_ERR_PARAM;
+    double total = 0.0;
+    svip_status rc = SVIP_OK;
+    for (int i = 0; i < g_prof.used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess)
+            rc = SVIP_ERR_HIP;
+        total += ms;
+    }
+    *total_ms_host = total;
+    *samples_host = g_prof.used;
+    for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    free(g_prof.ev);
+    g_prof = Profile();
+    return rc;
 }
 
 }  // extern "C"

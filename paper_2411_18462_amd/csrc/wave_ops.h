@@ -74,15 +74,26 @@ __device__ __forceinline__ T wave_reduce(T v, Op op)
 __device__ __forceinline__ float wave_max(float v) { return wave_reduce(v, OpMax{}); }
 __device__ __forceinline__ double wave_sum(double v) { return wave_reduce(v, OpSum{}); }
 
-// Inclusive prefix sum over the lanes of a wave (lane order), Hillis-Steele in fp64.
+// DPP move that yields 0 where a lane has no source (row shifts) or its row is masked out.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_mov_or_zero(double v)
+{
+    int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xF, true);
+    int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xF, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Inclusive prefix sum over the lanes of a wave (lane order) in fp64: Hillis-Steele inside
+// each DPP row (row_shr 1, 2, 4, 8), then the row totals are carried across rows with
+// row_bcast:15 (into rows 1 and 3) and row_bcast:31 (into rows 2 and 3).
 __device__ __forceinline__ double wave_inclusive_sum(double v)
 {
-    const int lane = __lane_id();
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        double o = __shfl_up(v, d, 64);
-        if (lane >= d) v += o;
-    }
+    v += dpp_mov_or_zero<0x111, 0xF>(v);
+    v += dpp_mov_or_zero<0x112, 0xF>(v);
+    v += dpp_mov_or_zero<0x114, 0xF>(v);
+    v += dpp_mov_or_zero<0x118, 0xF>(v);
+    v += dpp_mov_or_zero<0x142, 0xA>(v);
+    v += dpp_mov_or_zero<0x143, 0xC>(v);
     return v;
 }
 
