@@ -237,42 +237,22 @@ __device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, flo
     accumulate<N, NU, WITH_T>(z, m, S, t, sc);
 }
 
-// Streaming statistics of tiles [tb, te) of one row.  Every thread keeps a running maximum
-// of its own elements (rescaling its sums on the rare increase), so the loop has no
-// barrier; the workgroup combines at the end.  Tiles that lie wholly inside the row are read
-// in unchecked batches of 8/4/2/1 vectors per thread; only the row's last tile can be
-// partial and is read with bounds checks.  Result valid in thread 0.
-template <typename DT, bool WITH_T>
-__device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int te, const Scale &sc,
-                                               double *lds /* >= 2 * NWAVE doubles */)
+// Workgroup combination of the per-thread (m, S, t): maximum first, then every thread
+// rescales to it and the sums are added in fp64.  Result valid in thread 0.
+template <bool WITH_T>
+__device__ __forceinline__ Partial wg_combine(float m, float S, float t, const Scale &sc,
+                                              double *lds /* >= 2 * NWAVE doubles */)
 {
-    constexpr int N = VecOf<DT>::N;
-    const int tid = threadIdx.x;
-    float m = neg_inf(), S = 0.f, t = 0.f;
-    const int fe = min(te, V / (WG * N));      // end of the tiles that are wholly inside the row
-    int t0 = tb;
-    for (; t0 + 8 <= fe; t0 += 8) stats_batch<DT, 8, WITH_T>(row, t0, m, S, t, sc);
-    if (t0 + 4 <= fe) { stats_batch<DT, 4, WITH_T>(row, t0, m, S, t, sc); t0 += 4; }
-    if (t0 + 2 <= fe) { stats_batch<DT, 2, WITH_T>(row, t0, m, S, t, sc); t0 += 2; }
-    if (t0 + 1 <= fe) { stats_batch<DT, 1, WITH_T>(row, t0, m, S, t, sc); t0 += 1; }
-    if (t0 < te) {
-        float z[1][N];
-        unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
-        accumulate<N, 1, WITH_T>(z, m, S, t, sc);
-    }
-
-    // workgroup maximum
-    const int wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     float *ldsf = reinterpret_cast<float *>(lds);
     const float mw = wave_max(m);
+    __syncthreads();                      // the buffer may still be in use by an earlier call
     if (lane == 0) ldsf[wave] = mw;
     __syncthreads();
     float mg = ldsf[0];
 #pragma unroll
     for (int w = 1; w < NWAVE; ++w) mg = fmaxf(mg, ldsf[w]);
     __syncthreads();
-
-    // rescale every thread to the workgroup maximum and add up in fp64
     double Sd = 0.0, td = 0.0;
     if (m != neg_inf()) {
         const float xd = scaled_diff(m, mg, sc);
@@ -302,6 +282,32 @@ __device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int
     return p;
 }
 
+// Streaming statistics of tiles [tb, te) of one row.  Every thread keeps a running maximum
+// of its own elements (rescaling its sums on the rare increase), so the loop has no
+// barrier; the workgroup combines at the end.  Tiles that lie wholly inside the row are read
+// in unchecked batches of 8/4/2/1 vectors per thread; only the row's last tile can be
+// partial and is read with bounds checks.  Result valid in thread 0.
+template <typename DT, bool WITH_T>
+__device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int te, const Scale &sc,
+                                               double *lds /* >= 2 * NWAVE doubles */)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x;
+    float m = neg_inf(), S = 0.f, t = 0.f;
+    const int fe = min(te, V / (WG * N));      // end of the tiles that are wholly inside the row
+    int t0 = tb;
+    for (; t0 + 8 <= fe; t0 += 8) stats_batch<DT, 8, WITH_T>(row, t0, m, S, t, sc);
+    if (t0 + 4 <= fe) { stats_batch<DT, 4, WITH_T>(row, t0, m, S, t, sc); t0 += 4; }
+    if (t0 + 2 <= fe) { stats_batch<DT, 2, WITH_T>(row, t0, m, S, t, sc); t0 += 2; }
+    if (t0 + 1 <= fe) { stats_batch<DT, 1, WITH_T>(row, t0, m, S, t, sc); t0 += 1; }
+    if (t0 < te) {
+        float z[1][N];
+        unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
+        accumulate<N, 1, WITH_T>(z, m, S, t, sc);
+    }
+    return wg_combine<WITH_T>(m, S, t, sc, lds);
+}
+
 // Merge of up to MAX_SLICES slice partials by one wave (lane s holds slice s; lanes >= ns
 // pass m = -inf).  Returns wave-uniform reference m, and per lane the slice mass M and its
 // t-term, both relative to m; all in fp64.
@@ -328,41 +334,151 @@ __device__ __forceinline__ Merged merge_lane(float ms, double Ss, double ts, con
 // ---- in-slice inverse CDF ---------------------------------------------------------
 //
 // Finds the smallest token index i inside tiles [tb, te) whose inclusive prefix of weights,
-// counted from the start of the slice, exceeds `target`.  Weights come from a functor wf:
-// wf.load(vi) / wf.load_checked(vi) fetch the raw vector(s) and wf.weights(pack, w) turns them
-// into the N weights of vector vi (fp32, >= 0).  Prefixes are fp64: per-vector group
-// sums in fp32, lanes -> waves -> tiles in fp64.  If rounding leaves no such index, the last
-// index of the slice with positive weight is returned (or -1 if the slice has no mass).
-// All threads of the workgroup must call; the result (token, its weight) is uniform.
+// counted from the start of the slice, exceeds `target`.  The search works on batches of
+// LOCATE_UNROLL tiles: per-vector group sums in fp32, then lanes -> waves -> tiles in fp64.
+// The first crossing is found without LDS atomics: each wave ballots "my prefix exceeds the
+// target" per tile, posts its first hit, and the workgroup takes the smallest post.  If
+// rounding leaves no crossing, the last index of the slice with positive weight is returned
+// (or -1 if the slice has no mass).  All threads of the workgroup must call; the result
+// (token, its weight) is uniform.
 struct LocateLds {
     double wtot[NWAVE][LOCATE_UNROLL];
-    int key;
+    int wkey[NWAVE];
+    int wlast[NWAVE];
     int tok;
-    int last;
     float w;
 };
+constexpr int NOKEY = 0x7FFFFFFF;
 
+// One batch: w[u] holds the weights of vector (t0 + u) * WG + tid, all zero for absent tiles.
+// Returns true (uniform) if the crossing lies in this batch (L.tok / L.w are then set);
+// otherwise adds the batch mass to `run`.
+template <int N>
+__device__ __forceinline__ bool locate_batch(const float (&w)[LOCATE_UNROLL][N], int t0, int ntile,
+                                             double target, double &run, int &last, LocateLds &L)
+{
+    constexpr int LU = LOCATE_UNROLL;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    float g[LU];
+    double incl[LU];
+#pragma unroll
+    for (int u = 0; u < LU; ++u) {
+        g[u] = tree_sum<N>(w[u]);
+        incl[u] = 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < LU; ++u)
+        if (u < ntile) incl[u] = wave_inclusive_sum((double)g[u]);
+    __syncthreads();                      // LDS of an earlier batch / caller is free again
+    if (lane == 63) {
+#pragma unroll
+        for (int u = 0; u < LU; ++u) L.wtot[wave][u] = incl[u];
+    }
+    __syncthreads();
+    double base = run;
+    double excl[LU];
+    int wkey = NOKEY;
+#pragma unroll
+    for (int u = 0; u < LU; ++u) {
+        double before = 0.0, tot = 0.0;
+#pragma unroll
+        for (int w2 = 0; w2 < NWAVE; ++w2) {
+            const double x = L.wtot[w2][u];
+            if (w2 < wave) before += x;
+            tot += x;
+        }
+        const double P = base + before + incl[u];
+        excl[u] = base + before + (incl[u] - (double)g[u]);
+        const unsigned long long hit = __ballot(g[u] > 0.f && P > target);
+        if (wkey == NOKEY && hit) wkey = u * WG + wave * 64 + (__ffsll((long long)hit) - 1);
+        base += tot;
+    }
+    if (lane == 0) L.wkey[wave] = wkey;
+    __syncthreads();
+    int key = L.wkey[0];
+#pragma unroll
+    for (int w2 = 1; w2 < NWAVE; ++w2) key = min(key, L.wkey[w2]);
+    if (key == NOKEY) {
+#pragma unroll
+        for (int u = 0; u < LU; ++u) {
+#pragma unroll
+            for (int e = 0; e < N; ++e)
+                if (w[u][e] > 0.f) last = max(last, ((t0 + u) * WG + tid) * N + e);
+        }
+        run = base;
+        return false;
+    }
+    if ((key & (WG - 1)) == tid) {
+        const int ku = key / WG;
+#pragma unroll
+        for (int u = 0; u < LU; ++u) {
+            if (u == ku) {
+                double C = excl[u];
+                int pick = -1, lastpos = -1;
+#pragma unroll
+                for (int e = 0; e < N; ++e) {
+                    C += (double)w[u][e];
+                    if (w[u][e] > 0.f) {
+                        lastpos = e;
+                        if (pick < 0 && C > target) pick = e;
+                    }
+                }
+                if (pick < 0) pick = lastpos;
+                float wv = 0.f;
+#pragma unroll
+                for (int e = 0; e < N; ++e)
+                    if (e == pick) wv = w[u][e];
+                L.tok = ((t0 + u) * WG + tid) * N + pick;
+                L.w = wv;
+            }
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
+// No crossing anywhere: the last index with positive weight (-1 if none), uniform.
+template <int N, typename WF>
+__device__ __forceinline__ void locate_fallback(WF &wf, int last, LocateLds &L)
+{
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wl = wave_reduce(last, OpMax{});
+    __syncthreads();
+    if (lane == 0) L.wlast[wave] = wl;
+    __syncthreads();
+    int best = L.wlast[0];
+#pragma unroll
+    for (int w2 = 1; w2 < NWAVE; ++w2) best = max(best, L.wlast[w2]);
+    if (tid == 0) {
+        float wv = 0.f;
+        if (best >= 0) {
+            float one[N];
+            wf.weights(wf.load_checked(best / N), one);
+#pragma unroll
+            for (int e = 0; e < N; ++e)
+                if (e == best % N) wv = one[e];
+        }
+        L.tok = best;
+        L.w = wv;
+    }
+    __syncthreads();
+}
+
+// Search over tiles [tb, te) with the weights fetched by the functor wf:
+// wf.load(vi) / wf.load_checked(vi) fetch the raw vector(s) and wf.weights(pack, w) turns them
+// into the N weights of vector vi (fp32, >= 0).
 template <int N, typename WF>
 __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double target, LocateLds &L,
                                                float *weight_out)
 {
     constexpr int LU = LOCATE_UNROLL;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    constexpr int NOKEY = 0x7FFFFFFF;
-    if (tid == 0) {
-        L.key = NOKEY;
-        L.tok = -1;
-        L.last = -1;
-        L.w = 0.f;
-    }
-    __syncthreads();
+    const int tid = threadIdx.x;
     const int fe = min(te, wf.V / (WG * N));   // end of the tiles wholly inside the row
     double run = 0.0;
     int last = -1;
-    for (int t0 = tb; t0 < te; t0 += LU) {
+    bool found = false;
+    for (int t0 = tb; t0 < te && !found; t0 += LU) {
         float w[LU][N];
-        float g[LU];
-        double incl[LU];
         typename WF::Pack pk[LU];
 #pragma unroll
         for (int u = 0; u < LU; ++u)
@@ -377,153 +493,12 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
 #pragma unroll
                 for (int e = 0; e < N; ++e) w[u][e] = 0.f;
             }
-            g[u] = tree_sum<N>(w[u]);
-            incl[u] = 0.0;
         }
-#pragma unroll
-        for (int u = 0; u < LU; ++u)
-            if (t0 + u < te) incl[u] = wave_inclusive_sum((double)g[u]);
-        if (lane == 63) {
-#pragma unroll
-            for (int u = 0; u < LU; ++u) L.wtot[wave][u] = incl[u];
-        }
-        __syncthreads();
-        double base = run;
-        int mykey = NOKEY, myu = 0;
-        double myexcl = 0.0;
-#pragma unroll
-        for (int u = 0; u < LU; ++u) {
-            double before = 0.0, tot = 0.0;
-#pragma unroll
-            for (int w2 = 0; w2 < NWAVE; ++w2) {
-                const double x = L.wtot[w2][u];
-                if (w2 < wave) before += x;
-                tot += x;
-            }
-            const double P = base + before + incl[u];
-            if (mykey == NOKEY && g[u] > 0.f && P > target) {
-                mykey = u * WG + tid;
-                myu = u;
-                myexcl = base + before + (incl[u] - (double)g[u]);
-            }
-            base += tot;
-        }
-        if (mykey != NOKEY) atomicMin(&L.key, mykey);
-        __syncthreads();
-        const int key = L.key;
-        if (key != NOKEY) {
-            if (key == mykey) {
-                double C = myexcl;
-                int pick = -1;
-#pragma unroll
-                for (int u = 0; u < LU; ++u) {
-                    if (u == myu) {
-                        int lastpos = -1;
-#pragma unroll
-                        for (int e = 0; e < N; ++e) {
-                            C += (double)w[u][e];
-                            if (w[u][e] > 0.f) {
-                                lastpos = e;
-                                if (pick < 0 && C > target) pick = e;
-                            }
-                        }
-                        if (pick < 0) pick = lastpos;
-                        L.tok = ((t0 + u) * WG + tid) * N + pick;
-                        float wv = 0.f;
-#pragma unroll
-                        for (int e = 0; e < N; ++e)
-                            if (e == pick) wv = w[u][e];
-                        L.w = wv;
-                    }
-                }
-            }
-            break;
-        }
-#pragma unroll
-        for (int u = 0; u < LU; ++u) {
-#pragma unroll
-            for (int e = 0; e < N; ++e)
-                if (w[u][e] > 0.f) last = max(last, ((t0 + u) * WG + tid) * N + e);
-        }
-        run = base;
-        __syncthreads();
+        found = locate_batch<N>(w, t0, min(LU, te - t0), target, run, last, L);
     }
-    if (L.key == NOKEY) {      // uniform: nobody found a crossing
-        if (last >= 0) atomicMax(&L.last, last);
-        __syncthreads();
-        if (tid == 0 && L.last >= 0) {
-            float one[N];
-            wf.weights(wf.load_checked(L.last / N), one);
-            float wv = 0.f;
-#pragma unroll
-            for (int e = 0; e < N; ++e)
-                if (e == L.last % N) wv = one[e];
-            L.tok = L.last;
-            L.w = wv;
-        }
-    }
-    __syncthreads();
+    if (!found) locate_fallback<N>(wf, last, L);
     *weight_out = L.w;
     return L.tok;
-}
-
-// ---- "last workgroup finishes" -------------------------------------------------------
-//
-// Every workgroup of a group (the slices of a row, or all statistics workgroups of a
-// sequence) publishes its result, then calls arrive_last(); exactly one call per group -- the
-// one that arrives last -- returns true, after which that workgroup may fetch what the others
-// published.  The counter is left at zero for the next launch.
-//
-// Coherence across the XCDs' L2 caches without cache-wide write-backs: results are published
-// with device-scope atomic exchanges whose return values are awaited (so they have been
-// performed at the device's coherence point before the arrival counter is bumped), the
-// counter is a device-scope atomic, and the last workgroup fetches with device-scope atomic
-// loads, which do not hit in a non-coherent cache.
-__device__ __forceinline__ void publish64(unsigned long long *p, unsigned long long v)
-{
-    const unsigned long long old = __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    asm volatile("" : : "v"((unsigned)old));     // keep the returning form of the atomic
-}
-__device__ __forceinline__ unsigned long long fetch64(const unsigned long long *p)
-{
-    return __hip_atomic_load(const_cast<unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void publish_f64(double *p, double v)
-{
-    publish64(reinterpret_cast<unsigned long long *>(p), (unsigned long long)__double_as_longlong(v));
-}
-__device__ __forceinline__ double fetch_f64(const double *p)
-{
-    return __longlong_as_double((long long)fetch64(reinterpret_cast<const unsigned long long *>(p)));
-}
-__device__ __forceinline__ void publish_partial(Partial *slot, const Partial &p)
-{
-    publish64(reinterpret_cast<unsigned long long *>(&slot->m), (unsigned long long)__float_as_uint(p.m));
-    publish_f64(&slot->S, p.S);
-    publish_f64(&slot->t, p.t);
-}
-__device__ __forceinline__ Partial fetch_partial(const Partial *slot)
-{
-    Partial p;
-    p.m = __uint_as_float((unsigned)fetch64(reinterpret_cast<const unsigned long long *>(&slot->m)));
-    p.pad = 0.f;
-    p.S = fetch_f64(&slot->S);
-    p.t = fetch_f64(&slot->t);
-    return p;
-}
-
-// To be called by all threads after thread 0 has published the workgroup's result.
-__device__ __forceinline__ bool arrive_last(unsigned *counter, unsigned expected, int *lds_flag)
-{
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the exchanges above have returned
-        const unsigned old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool last = (old + 1u == expected);
-        if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *lds_flag = last ? 1 : 0;
-    }
-    __syncthreads();
-    return *lds_flag != 0;
 }
 
 }  // namespace svip

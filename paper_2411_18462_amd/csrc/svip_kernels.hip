@@ -1,15 +1,16 @@
 // SVIP hot path for MI355X (gfx950): kernels and the C ABI declared in include/svip.h.
 //
-// svip_draft_step  =  k_draft   (grid: slices x rows)  per-slice (m, S, t); the workgroup that
-//                               finishes a row last merges its slices, applies the stop test
-//                               and locates the sampled token (inverse CDF)
-// svip_verify      =  k_verify  (grid: slices x target rows [+ draft rows])  per-slice (m, S);
-//                               the workgroup that finishes a sequence last runs the p/q
-//                               acceptance test and the ballot scan for the first rejection
-//                     k_resid   (grid: slices x sequences)  slice masses of the residual (or of
-//                               the bonus row); the last workgroup of a sequence locates the token
+// svip_draft_step  =  k_draft_stats    grid (slices, rows)       per-slice (m, S, t) of every active row
+//                     k_draft_finish   grid (rows)               merge, entropy, stop test, inverse CDF
+// svip_verify      =  k_verify_stats   grid (slices, stat rows)  per-slice (m, S) of every needed row
+//                     k_accept         grid (sequences), 1 wave  p/q test, ballot scan for the first rejection
+//                     k_resid_mass     grid (slices, sequences)  slice masses of the residual / bonus row
+//                     k_resid_finish   grid (sequences)          inverse CDF of the residual / bonus row
 //
 // The passes are bound by HBM reads of the logits; there is no dense contraction, hence no MFMA.
+// Kernels of one call are ordered by the stream only (no spinning, no device-side waits), and
+// each small kernel issues all of its independent loads before the first dependent one, because
+// at small batches a step is bound by round trips to memory rather than by bandwidth.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -22,7 +23,7 @@ namespace svip {
 
 // ---- workspace layout ----------------------------------------------------------------
 
-struct SeqRec {          // what the acceptance scan hands to the residual pass, one per sequence
+struct SeqRec {          // what k_accept hands to the residual kernels, one per sequence
     double Lp;           // logsumexp(target row r) * log2(e)
     double Lq;           // logsumexp(draft row r) * log2(e) (residual mode only)
     int r;               // target row to sample from (first rejection, or draft_len for a bonus)
@@ -31,37 +32,29 @@ struct SeqRec {          // what the acceptance scan hands to the residual pass,
 
 struct Workspace {
     unsigned *flags;     // sticky device-data flags
-    unsigned *cnt_a;     // [B] arrival counters: draft rows / verify sequences (zero between launches)
-    unsigned *cnt_b;     // [B] arrival counters of the residual pass
-    Partial *part;       // [rows][ns] slice statistics
     SeqRec *rec;         // [B]
     double *mass;        // [B][MAX_SLICES][2] residual mass, target mass per slice
+    Partial *part;       // [stat rows][ns] slice statistics
 };
 
-// Fixed header, independent of the batch: the flag word, then two arrays of MAX_BATCH arrival
-// counters.  svip_workspace_reset zeroes it; every launch leaves the counters at zero again.
-constexpr int MAX_BATCH = 65535;                 // also the grid.y limit of a launch
-constexpr size_t FLAG_BYTES = 256;
-constexpr size_t HEADER_BYTES = FLAG_BYTES + 2 * 65536 * sizeof(unsigned);
+constexpr int MAX_BATCH = 65535;                 // grid.y limit of a launch
+constexpr size_t HEADER_BYTES = 256;
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static size_t ws_part_bytes(int B, int k) { return align256((size_t)B * (2 * (size_t)k + 1) * MAX_SLICES * sizeof(Partial)); }
 static size_t ws_rec_bytes(int B) { return align256((size_t)B * sizeof(SeqRec)); }
 static size_t ws_mass_bytes(int B) { return align256((size_t)B * MAX_SLICES * 2 * sizeof(double)); }
 
-static Workspace carve(void *ws, int B, int k)
+static Workspace carve(void *ws, int B)
 {
     char *p = static_cast<char *>(ws);
     Workspace w;
     w.flags = reinterpret_cast<unsigned *>(p);
-    w.cnt_a = reinterpret_cast<unsigned *>(p + FLAG_BYTES);
-    w.cnt_b = w.cnt_a + 65536;
     p += HEADER_BYTES;
-    w.part = reinterpret_cast<Partial *>(p);
-    p += ws_part_bytes(B, k);
     w.rec = reinterpret_cast<SeqRec *>(p);
     p += ws_rec_bytes(B);
     w.mass = reinterpret_cast<double *>(p);
+    p += ws_mass_bytes(B);
+    w.part = reinterpret_cast<Partial *>(p);
     return w;
 }
 
@@ -85,7 +78,6 @@ struct DraftArgs {
     int *draft_len;
     long long io_stride;
     Partial *part;
-    unsigned *cnt;
 };
 
 struct VerifyArgs {
@@ -93,6 +85,7 @@ struct VerifyArgs {
     const void *draft;
     long long seq_t, seq_d, row_stride;
     int B, k;
+    int kd;        // draft rows per sequence in the statistics pass: k if the draft logsumexps are recomputed, else 0
     Geo geo;       // slicing of the statistics pass
     Geo geo_s;     // slicing of the sampling pass (slices of at most LOCATE_UNROLL tiles when possible)
     Scale sc;
@@ -107,14 +100,7 @@ struct VerifyArgs {
     Workspace ws;
 };
 
-__device__ __forceinline__ int clamp_len(int g, int k, unsigned *flags)
-{
-    if (g < 0 || g > k) {
-        atomicOr(flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
-        g = g < 0 ? 0 : k;
-    }
-    return g;
-}
+__device__ __forceinline__ int clamp_len(int g, int k) { return g < 0 ? 0 : (g > k ? k : g); }
 
 // ---- weights for the inverse CDF ---------------------------------------------------------
 
@@ -165,220 +151,6 @@ struct ResidualWeights {       // w_i = max(0, p_i - q_i), normalised p and q
     }
 };
 
-// Choice of the slice that contains `target` among per-lane slice masses M (lane order =
-// slice order).  Returns (uniform) the slice and the target relative to the slice start.
-__device__ __forceinline__ int pick_slice(double M, double target, double incl, double *local_target)
-{
-    const unsigned long long cross = __ballot(M > 0.0 && incl > target);
-    const unsigned long long mass = __ballot(M > 0.0);
-    int s;
-    if (cross) s = __ffsll((long long)cross) - 1;
-    else if (mass) s = 63 - __clzll((long long)mass);
-    else s = 0;
-    const double excl = read_lane(incl - M, s);
-    *local_target = target - excl;
-    return s;
-}
-
-// ---- draft step -------------------------------------------------------------------------------
-
-struct FinishLds {
-    LocateLds loc;
-    double target, L, S;
-    int slice;
-};
-
-// Merge of a row's slices, entropy and stop test, inverse CDF; run by the workgroup that
-// finished the row last.
-template <typename DT>
-__device__ __forceinline__ void draft_finish(const DraftArgs &a, int b, const DT *row, FinishLds &sh)
-{
-    constexpr int N = VecOf<DT>::N;
-    const int tid = threadIdx.x;
-    const long long o = (long long)b * a.io_stride;
-    double H = 0.0, lse = 0.0;
-    if (tid < 64) {
-        float ms = neg_inf();
-        double Ss = 0.0, ts = 0.0;
-        if (tid < a.geo.ns) {
-            const Partial p = fetch_partial(&a.part[(size_t)b * a.geo.ns + tid]);
-            ms = p.m;
-            Ss = p.S;
-            ts = p.t;
-        }
-        const Merged mg = merge_lane(ms, Ss, ts, a.sc);
-        const double incl = wave_inclusive_sum(mg.M);
-        const double S = read_lane(incl, 63);
-        const double tt = wave_sum(mg.tt);
-        // H = ln S - (sum e x ln2) / S  for weights e = exp2(x): the entropy of e / S
-        const double lnS = log(S);
-        H = lnS - 0.6931471805599453 * tt / S;
-        H = H > 0.0 ? H : 0.0;
-        lse = (double)mg.m * a.sc.inv_T + lnS;
-        const double target = (double)a.u[o] * S;
-        double local;
-        const int s = pick_slice(mg.M, target, incl, &local);
-        if (tid == 0) {
-            sh.target = local;
-            sh.L = (double)mg.m * a.sc.c;
-            sh.S = S;
-            sh.slice = s;
-        }
-    }
-    __syncthreads();
-    SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, sh.L)};
-    const int tb = sh.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    float wtok;
-    const int tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
-    if (tid == 0) {
-        a.token[o] = tok;
-        if (a.entropy) a.entropy[o] = (float)H;
-        if (a.q_tok) a.q_tok[o] = (float)((double)wtok / sh.S);
-        a.lse[o] = lse;
-        const bool stop = (sqrt(H) > (double)a.h) || (a.step_j + 1 >= a.k_max);
-        a.stop[b] = stop ? 1 : 0;
-        if (a.draft_len) a.draft_len[b] = a.step_j + 1;
-    }
-}
-
-// grid (slices, rows): workgroup (s, b) streams slice s of row b.
-template <typename DT>
-__global__ __launch_bounds__(WG) void k_draft(DraftArgs a)
-{
-    __shared__ double lds[2 * NWAVE];
-    __shared__ FinishLds sh;
-    __shared__ int last_flag;
-    const int s = blockIdx.x, b = blockIdx.y;
-    if (a.stop_in && a.stop_in[b]) {
-        if (s == 0 && threadIdx.x == 0) {
-            a.token[(long long)b * a.io_stride] = -1;
-            a.stop[b] = 1;
-        }
-        return;
-    }
-    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
-    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    const Partial p = slice_stats<DT, true>(row, a.geo.V, tb, te, a.sc, lds);
-    if (threadIdx.x == 0) publish_partial(&a.part[(size_t)b * a.geo.ns + s], p);
-    if (!arrive_last(a.cnt + b, (unsigned)a.geo.ns, &last_flag)) return;
-    draft_finish<DT>(a, b, row, sh);
-}
-
-// ---- verify: acceptance test and first rejection -------------------------------------------
-
-// logsumexp * log2(e) of statistics row y, merged serially over its slices in fp64.
-__device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns, const Scale &sc)
-{
-    float m = neg_inf();
-    for (int s = 0; s < ns; ++s) m = fmaxf(m, fetch_partial(&part[y * ns + s]).m);
-    double S = 0.0;
-    for (int s = 0; s < ns; ++s) {
-        const Partial p = fetch_partial(&part[y * ns + s]);
-        if (p.m != neg_inf() && p.S > 0.0) S += p.S * exp2(((double)p.m - (double)m) * sc.c);
-    }
-    return (double)m * sc.c + log2(S);
-}
-
-// Acceptance test at every drafted position of sequence b and first-rejection scan, by one
-// wave (lane = position, 64 positions per pass); run by the workgroup that finished the
-// sequence's statistics last.
-template <typename DT>
-__device__ __forceinline__ void accept_scan(const VerifyArgs &a, int b, int g)
-{
-    const int lane = threadIdx.x;
-    const DT *tgt = static_cast<const DT *>(a.target) + (long long)b * a.seq_t;
-    const DT *drf = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d;
-    const size_t yt = (size_t)b * (a.k + 1);
-    const size_t yd = (size_t)a.B * (a.k + 1) + (size_t)b * a.k;
-    constexpr double LOG2E = 1.4426950408889634;
-    int r = g;
-    double Lq_r = 0.0;
-    for (int j0 = 0; j0 < g; j0 += 64) {
-        const int j = j0 + lane;
-        bool reject = false;
-        double Lq = 0.0;
-        if (j < g) {
-            int x = a.tokens[(size_t)b * a.k + j];
-            if (x < 0 || x >= a.geo.V) {
-                atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_TOKEN);
-                x = x < 0 ? 0 : a.geo.V - 1;
-            }
-            const double Lp = row_L(a.ws.part, yt + j, a.geo.ns, a.sc);
-            Lq = a.draft_lse ? a.draft_lse[(size_t)b * a.k + j] * LOG2E
-                             : row_L(a.ws.part, yd + j, a.geo.ns, a.sc);
-            const double zp = (double)load_one<DT>(tgt + (long long)j * a.row_stride, x);
-            const double zq = (double)load_one<DT>(drf + (long long)j * a.row_stride, x);
-            const double p = exp2(zp * a.sc.c - Lp);
-            const double q = exp2(zq * a.sc.c - Lq);
-            const double u = (double)a.u_accept[(size_t)b * a.k + j];
-            reject = !(u * q < p);
-            if (a.accept_prob) {
-                const double ratio = q > 0.0 ? p / q : (p > 0.0 ? 1.0 : 0.0);
-                a.accept_prob[(size_t)b * a.k + j] = (float)(ratio < 1.0 ? ratio : 1.0);
-            }
-        }
-        const unsigned long long rej = __ballot(reject);
-        if (rej && r == g) {
-            const int first = __ffsll((long long)rej) - 1;
-            r = j0 + first;
-            Lq_r = read_lane(Lq, first);
-            if (!a.accept_prob) break;     // later positions cannot change the outputs
-        }
-    }
-    if (lane == 0) {
-        a.n_accepted[b] = r;
-        SeqRec rec;
-        rec.r = r;
-        rec.resid = r < g ? 1 : 0;
-        rec.Lp = row_L(a.ws.part, yt + r, a.geo.ns, a.sc);
-        rec.Lq = Lq_r;
-        a.ws.rec[b] = rec;
-    }
-}
-
-// grid (slices, rows).  Rows y < B (k+1) are target rows (b, j), needed for j <= draft_len[b];
-// when the draft logsumexps must be recomputed, rows y >= B (k+1) are draft rows (b, j),
-// needed for j < draft_len[b].  Workgroups of rows that are not needed exit at once.
-template <typename DT>
-__global__ __launch_bounds__(WG) void k_verify(VerifyArgs a)
-{
-    __shared__ double lds[2 * NWAVE];
-    __shared__ int last_flag;
-    const int s = blockIdx.x;
-    const int y = blockIdx.y;
-    const int nt = a.B * (a.k + 1);
-    const bool recompute = a.draft_lse == nullptr;
-    const DT *row;
-    int b, g;
-    if (y < nt) {
-        b = y / (a.k + 1);
-        const int j = y - b * (a.k + 1);
-        g = a.draft_len[b];
-        g = g < 0 ? 0 : (g > a.k ? a.k : g);
-        if (j > g) return;
-        row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
-    } else {
-        const int yd = y - nt;
-        b = yd / a.k;
-        const int j = yd - b * a.k;
-        g = a.draft_len[b];
-        g = g < 0 ? 0 : (g > a.k ? a.k : g);
-        if (j >= g) return;
-        row = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)j * a.row_stride;
-    }
-    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    const Partial p = slice_stats<DT, false>(row, a.geo.V, tb, te, a.sc, lds);
-    if (threadIdx.x == 0) publish_partial(&a.ws.part[(size_t)y * a.geo.ns + s], p);
-    const unsigned expected = (unsigned)a.geo.ns * (unsigned)(g + 1 + (recompute ? g : 0));
-    if (!arrive_last(a.ws.cnt_a + b, expected, &last_flag)) return;
-    if (threadIdx.x < 64) {
-        clamp_len(a.draft_len[b], a.k, a.ws.flags);      // records an out-of-range draft length
-        accept_scan<DT>(a, b, g);
-    }
-}
-
-// ---- verify: residual / bonus sampling ------------------------------------------------------
-
 // One batch of NU vectors per thread of the rejected position's rows: adds the residual
 // mass max(0, p - q) (if RESID) and the target mass p of the batch.
 template <typename DT, int NU, bool RESID, bool CHECKED>
@@ -414,6 +186,8 @@ __device__ __forceinline__ void mass_batch(const DT *prow, const DT *qrow, int V
     Pacc += Pb;
 }
 
+// Per-thread residual and target masses of tiles [tb, te) in batches of LOCATE_UNROLL vectors
+// (the same grouping of additions as the in-register path of k_resid).
 template <typename DT, bool RESID>
 __device__ __forceinline__ void slice_mass(const DT *prow, const DT *qrow, int V, int tb, int te,
                                            const ExpRef &ep, const ExpRef &eq, float &Wacc, float &Pacc)
@@ -427,57 +201,234 @@ __device__ __forceinline__ void slice_mass(const DT *prow, const DT *qrow, int V
     if (t0 < te) mass_batch<DT, 1, RESID, true>(prow, qrow, V, t0, ep, eq, Wacc, Pacc);
 }
 
-// Choice between residual and target weights, slice selection and inverse CDF for
-// sequence b; run by the workgroup that finished the sequence's slice masses last.
+// Choice of the slice that contains `target` among per-lane slice masses M (lane order =
+// slice order).  Returns (uniform) the slice and the target relative to the slice start.
+__device__ __forceinline__ int pick_slice(double M, double target, double incl, double *local_target)
+{
+    const unsigned long long cross = __ballot(M > 0.0 && incl > target);
+    const unsigned long long mass = __ballot(M > 0.0);
+    int s;
+    if (cross) s = __ffsll((long long)cross) - 1;
+    else if (mass) s = 63 - __clzll((long long)mass);
+    else s = 0;
+    const double excl = read_lane(incl - M, s);
+    *local_target = target - excl;
+    return s;
+}
+
+// ---- draft step -------------------------------------------------------------------------------
+
+// grid (slices, rows): statistics of slice s of row b.
 template <typename DT>
-__device__ __forceinline__ void resid_finish(const VerifyArgs &a, int b, const SeqRec &rec, const DT *prow,
-                                             const DT *qrow, FinishLds &sh, int *use_resid)
+__global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
+{
+    __shared__ double lds[2 * NWAVE];
+    const int s = blockIdx.x, b = blockIdx.y;
+    if (a.stop_in && a.stop_in[b]) return;
+    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
+    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const Partial p = slice_stats<DT, true>(row, a.geo.V, tb, te, a.sc, lds);
+    if (threadIdx.x == 0) a.part[(size_t)b * a.geo.ns + s] = p;
+}
+
+struct FinishLds {
+    LocateLds loc;
+    double target, L, S, tt;
+    float m;
+    int slice;
+    int use_resid;
+};
+
+// grid (rows): merge of the row's slices, entropy and stop test, inverse CDF.
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_draft_finish(DraftArgs a)
 {
     constexpr int N = VecOf<DT>::N;
-    const int tid = threadIdx.x;
-    if (tid < 64) {
-        double W = 0.0, P = 0.0;
-        if (tid < a.geo_s.ns) {
-            const double *in = a.ws.mass + ((size_t)b * MAX_SLICES + tid) * 2;
-            W = fetch_f64(in);
-            P = fetch_f64(in + 1);
+    __shared__ FinishLds sh;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const long long o = (long long)b * a.io_stride;
+    // independent loads first: the row's flag, its uniform and its slice statistics
+    const unsigned char stopped = a.stop_in ? a.stop_in[b] : (unsigned char)0;
+    const float u = a.u[o];
+    Partial p;
+    p.m = neg_inf();
+    p.S = 0.0;
+    p.t = 0.0;
+    if (tid < a.geo.ns) p = a.part[(size_t)b * a.geo.ns + tid];
+    if (stopped) {
+        if (tid == 0) {
+            a.token[o] = -1;
+            a.stop[b] = 1;
         }
-        const double inclW = wave_inclusive_sum(W), inclP = wave_inclusive_sum(P);
-        const double totW = read_lane(inclW, 63), totP = read_lane(inclP, 63);
-        const bool resid = rec.resid && totW > 0.0;   // no residual mass: draw from the target row
-        const double M = resid ? W : P, incl = resid ? inclW : inclP, tot = resid ? totW : totP;
-        const double target = (double)a.u_resample[b] * tot;
+        return;
+    }
+    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
+    if (tid < 64) {
+        const Merged mg = merge_lane(tid < a.geo.ns ? p.m : neg_inf(), p.S, p.t, a.sc);
+        const double incl = wave_inclusive_sum(mg.M);
+        const double S = read_lane(incl, 63);
+        const double tt = wave_sum(mg.tt);
         double local;
-        const int s = pick_slice(M, target, incl, &local);
+        const int s = pick_slice(mg.M, (double)u * S, incl, &local);
         if (tid == 0) {
             sh.target = local;
+            sh.L = (double)mg.m * a.sc.c;
+            sh.S = S;
+            sh.tt = tt;
+            sh.m = mg.m;
             sh.slice = s;
-            *use_resid = resid ? 1 : 0;
         }
     }
     __syncthreads();
-    const int tb = sh.slice * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
+    SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, sh.L)};
+    const int tb = sh.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
     float wtok;
-    int tok;
-    if (*use_resid) {
-        ResidualWeights<DT> wf{prow, qrow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp), make_exp_ref(a.sc, rec.Lq)};
-        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
-    } else {
-        SoftmaxWeights<DT> wf{prow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp)};
-        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    const int tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    if (tid == 0) {
+        // H = ln S - (sum e x ln2) / S  for weights e = exp2(x): the entropy of e / S
+        const double S = sh.S, lnS = log(S);
+        double H = lnS - 0.6931471805599453 * sh.tt / S;
+        H = H > 0.0 ? H : 0.0;
+        a.token[o] = tok;
+        if (a.entropy) a.entropy[o] = (float)H;
+        if (a.q_tok) a.q_tok[o] = (float)((double)wtok / S);
+        a.lse[o] = (double)sh.m * a.sc.inv_T + lnS;
+        const bool stop = (sqrt(H) > (double)a.h) || (a.step_j + 1 >= a.k_max);
+        a.stop[b] = stop ? 1 : 0;
+        if (a.draft_len) a.draft_len[b] = a.step_j + 1;
     }
-    if (tid == 0) a.next_token[b] = tok;
 }
 
-// grid (slices, sequences): slice masses of the weights to sample from -- [0] residual
-// max(0, p - q) at the rejected position, [1] target p of the row to sample -- then the last
-// workgroup of the sequence draws the token.
+// ---- verify: statistics ------------------------------------------------------------------------
+
+// Statistics rows of sequence b are numbered jj = 0 .. kd + k: first the kd draft rows (only
+// when the draft logsumexps are recomputed), then the k + 1 target rows.
+__device__ __forceinline__ size_t stat_row(const VerifyArgs &a, int b, int jj)
+{
+    return (size_t)b * (a.kd + a.k + 1) + jj;
+}
+
+// grid (slices, sequences * rows per sequence).  Draft rows are needed for j < draft_len[b],
+// target rows for j <= draft_len[b]; workgroups of other rows exit at once.
 template <typename DT>
-__global__ __launch_bounds__(WG) void k_resid(VerifyArgs a)
+__global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
 {
     __shared__ double lds[2 * NWAVE];
-    __shared__ FinishLds sh;
-    __shared__ int last_flag, use_resid;
+    const int s = blockIdx.x;
+    const int rps = a.kd + a.k + 1;
+    const int b = blockIdx.y / rps, jj = blockIdx.y - b * rps;
+    const int g = clamp_len(a.draft_len[b], a.k);
+    const DT *row;
+    if (jj < a.kd) {
+        if (jj >= g) return;
+        row = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)jj * a.row_stride;
+    } else {
+        const int j = jj - a.kd;
+        if (j > g) return;
+        row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
+    }
+    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const Partial p = slice_stats<DT, false>(row, a.geo.V, tb, te, a.sc, lds);
+    if (threadIdx.x == 0) a.ws.part[stat_row(a, b, jj) * a.geo.ns + s] = p;
+}
+
+// ---- verify: acceptance test and first rejection -------------------------------------------
+
+// logsumexp * log2(e) of statistics row y, merged over its slices in fp64.
+__device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns, const Scale &sc)
+{
+    float m = neg_inf();
+    double S = 0.0;
+    for (int s = 0; s < ns; ++s) {
+        const Partial p = part[y * ns + s];
+        if (p.m == neg_inf() || !(p.S > 0.0)) continue;
+        if (p.m > m) {
+            S *= exp2(((double)m - (double)p.m) * sc.c);     // exp2(-inf) = 0 on the first slice
+            m = p.m;
+        }
+        S += p.S * exp2(((double)p.m - (double)m) * sc.c);
+    }
+    return (double)m * sc.c + log2(S);
+}
+
+// grid (sequences), one wave: lane = position, 64 positions per pass.  Lanes j <= draft_len merge
+// the statistics of target row j; lanes j < draft_len run the acceptance test; a ballot finds
+// the first rejection.
+template <typename DT>
+__global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int graw = a.draft_len[b];
+    const int g = clamp_len(graw, a.k);
+    if (graw != g && lane == 0) atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
+    const DT *tgt = static_cast<const DT *>(a.target) + (long long)b * a.seq_t;
+    const DT *drf = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d;
+    constexpr double LOG2E = 1.4426950408889634;
+    int r = -1;                 // first rejection, once known
+    double Lp_r = 0.0, Lq_r = 0.0;
+    for (int j0 = 0; j0 <= g && (r < 0 || a.accept_prob); j0 += 64) {
+        const int j = j0 + lane;
+        bool reject = false;
+        double Lp = 0.0, Lq = 0.0;
+        if (j <= g) {
+            // loads that do not depend on each other: token, uniform, draft logsumexp, slot statistics
+            int x = 0;
+            double u = 0.0, lse_q = 0.0;
+            if (j < g) {
+                x = a.tokens[(size_t)b * a.k + j];
+                u = (double)a.u_accept[(size_t)b * a.k + j];
+                if (a.draft_lse) lse_q = a.draft_lse[(size_t)b * a.k + j];
+            }
+            Lp = row_L(a.ws.part, stat_row(a, b, a.kd + j), a.geo.ns, a.sc);
+            if (j < g) {
+                Lq = a.draft_lse ? lse_q * LOG2E : row_L(a.ws.part, stat_row(a, b, j), a.geo.ns, a.sc);
+                if (x < 0 || x >= a.geo.V) {
+                    atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_TOKEN);
+                    x = x < 0 ? 0 : a.geo.V - 1;
+                }
+                const double zp = (double)load_one<DT>(tgt + (long long)j * a.row_stride, x);
+                const double zq = (double)load_one<DT>(drf + (long long)j * a.row_stride, x);
+                const double p = exp2(zp * a.sc.c - Lp);
+                const double q = exp2(zq * a.sc.c - Lq);
+                reject = !(u * q < p);
+                if (a.accept_prob) {
+                    const double ratio = q > 0.0 ? p / q : (p > 0.0 ? 1.0 : 0.0);
+                    a.accept_prob[(size_t)b * a.k + j] = (float)(ratio < 1.0 ? ratio : 1.0);
+                }
+            }
+        }
+        if (r < 0) {
+            const unsigned long long rej = __ballot(reject);
+            if (rej) {
+                const int first = __ffsll((long long)rej) - 1;
+                r = j0 + first;
+                Lp_r = read_lane(Lp, first);
+                Lq_r = read_lane(Lq, first);
+            } else if (g - j0 < 64) {      // row g (the bonus row) was merged in this pass
+                r = g;
+                Lp_r = read_lane(Lp, g - j0);
+            }
+        }
+    }
+    if (lane == 0) {
+        a.n_accepted[b] = r;
+        SeqRec rec;
+        rec.r = r;
+        rec.resid = r < g ? 1 : 0;
+        rec.Lp = Lp_r;
+        rec.Lq = Lq_r;
+        a.ws.rec[b] = rec;
+    }
+}
+
+// ---- verify: residual / bonus sampling ------------------------------------------------------
+
+// grid (slices, sequences): slice masses of the weights to sample from -- [0] residual
+// max(0, p - q) at the rejected position, [1] target p of the row to sample.
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_resid_mass(VerifyArgs a)
+{
+    __shared__ double lds[2 * NWAVE];
     const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const SeqRec rec = a.ws.rec[b];
     const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
@@ -502,19 +453,57 @@ __global__ __launch_bounds__(WG) void k_resid(VerifyArgs a)
             P += lds[NWAVE + w];
         }
         double *out = a.ws.mass + ((size_t)b * MAX_SLICES + s) * 2;
-        publish_f64(out, W);
-        publish_f64(out + 1, P);
+        out[0] = W;
+        out[1] = P;
     }
-    if (!arrive_last(a.ws.cnt_b + b, (unsigned)a.geo_s.ns, &last_flag)) return;
-    resid_finish<DT>(a, b, rec, prow, qrow, sh, &use_resid);
 }
 
-__global__ void k_zero_header(unsigned *flags, unsigned *cnt, int n)
+// grid (sequences): choice between residual and target weights, slice selection, inverse CDF.
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_resid_finish(VerifyArgs a)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) *flags = 0u;
-    if (i < n) cnt[i] = 0u;
+    constexpr int N = VecOf<DT>::N;
+    __shared__ FinishLds sh;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    // independent loads first
+    const SeqRec rec = a.ws.rec[b];
+    const float u = a.u_resample[b];
+    double W = 0.0, P = 0.0;
+    if (tid < a.geo_s.ns) {
+        const double *in = a.ws.mass + ((size_t)b * MAX_SLICES + tid) * 2;
+        W = in[0];
+        P = in[1];
+    }
+    if (tid < 64) {
+        const double inclW = wave_inclusive_sum(W), inclP = wave_inclusive_sum(P);
+        const double totW = read_lane(inclW, 63), totP = read_lane(inclP, 63);
+        const bool resid = rec.resid && totW > 0.0;   // no residual mass: draw from the target row
+        const double M = resid ? W : P, incl = resid ? inclW : inclP, tot = resid ? totW : totP;
+        double local;
+        const int s = pick_slice(M, (double)u * tot, incl, &local);
+        if (tid == 0) {
+            sh.target = local;
+            sh.slice = s;
+            sh.use_resid = resid ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
+    const DT *qrow = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)rec.r * a.row_stride;
+    const int tb = sh.slice * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
+    float wtok;
+    int tok;
+    if (sh.use_resid) {
+        ResidualWeights<DT> wf{prow, qrow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp), make_exp_ref(a.sc, rec.Lq)};
+        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    } else {
+        SoftmaxWeights<DT> wf{prow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp)};
+        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    }
+    if (tid == 0) a.next_token[b] = tok;
 }
+
+__global__ void k_zero(unsigned *p) { *p = 0u; }
 
 // ---- host side -------------------------------------------------------------------------------
 
@@ -594,18 +583,22 @@ const char *svip_status_string(int status)
 
 size_t svip_workspace_bytes(int B, int k_max, int V)
 {
-    if (B <= 0 || k_max < 1 || k_max > SVIP_MAX_K || V <= 0) return 0;
-    return HEADER_BYTES + ws_part_bytes(B, k_max) + ws_rec_bytes(B) + ws_mass_bytes(B);
+    if (B <= 0 || B > MAX_BATCH || k_max < 1 || k_max > SVIP_MAX_K || V <= 0) return 0;
+    // slice statistics: the draft step slices its B rows finely (at most MAX_SLICES each); the
+    // statistics pass of verify has up to B (2 k + 1) rows, of which make_geo cuts at most
+    // ceil(2048 / rows) + 1 slices each
+    const size_t vrows = (size_t)B * (2 * (size_t)k_max + 1);
+    size_t parts = (size_t)B * MAX_SLICES;
+    if (2 * vrows + 2048 > parts) parts = 2 * vrows + 2048;
+    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + align256(parts * sizeof(Partial));
 }
 
 svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!workspace || workspace_bytes < HEADER_BYTES || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return SVIP_ERR_WORKSPACE;
-    unsigned *flags = static_cast<unsigned *>(workspace);
-    unsigned *cnt = reinterpret_cast<unsigned *>(static_cast<char *>(workspace) + FLAG_BYTES);
-    hipLaunchKernelGGL(k_zero_header, dim3(2 * 65536 / 256), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                       flags, cnt, 2 * 65536);
+    hipLaunchKernelGGL(k_zero, dim3(1), dim3(1), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<unsigned *>(workspace));
     return check_launch();
 }
 
@@ -634,16 +627,16 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
     const int vec = dtype == SVIP_BF16 ? 8 : 4;
     if (!aligned16(draft_logits) || row_stride % vec != 0) return SVIP_ERR_ALIGN;
     if (!(temperature > 0.f) || !isfinite(temperature) || !(h >= 0.f)) return SVIP_ERR_PARAM;
-    // the workspace only has to hold this call's partials: B rows
-    const size_t need = HEADER_BYTES + align256((size_t)B * MAX_SLICES * sizeof(Partial));
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
-        return SVIP_ERR_WORKSPACE;
 
     DraftArgs a;
+    a.geo = make_geo(V, vec, B, true, env_int("SVIP_DRAFT_SLICES", 0));
+    const size_t need = HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + (size_t)B * a.geo.ns * sizeof(Partial);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+        return SVIP_ERR_WORKSPACE;
+    const Workspace w = carve(workspace, B);
     a.logits = draft_logits;
     a.row_stride = row_stride;
     a.B = B;
-    a.geo = make_geo(V, vec, B, true, env_int("SVIP_DRAFT_SLICES", 0));
     a.sc = make_scale(temperature);
     a.h = h;
     a.step_j = step_j;
@@ -657,12 +650,16 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
     a.stop = stop_out;
     a.draft_len = draft_len_out;
     a.io_stride = io_stride;
-    a.part = reinterpret_cast<Partial *>(static_cast<char *>(workspace) + HEADER_BYTES);
-    a.cnt = reinterpret_cast<unsigned *>(static_cast<char *>(workspace) + FLAG_BYTES);
+    a.part = w.part;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 grid(a.geo.ns, B);
-    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_draft<bf16>, grid, dim3(WG), 0, st, a);
-    else hipLaunchKernelGGL(k_draft<float>, grid, dim3(WG), 0, st, a);
+    if (dtype == SVIP_BF16) {
+        hipLaunchKernelGGL(k_draft_stats<bf16>, grid, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_draft_finish<bf16>, dim3(B), dim3(WG), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(k_draft_stats<float>, grid, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_draft_finish<float>, dim3(B), dim3(WG), 0, st, a);
+    }
     return check_launch();
 }
 
@@ -678,21 +675,25 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
         !n_accepted_out || !next_token_out)
         return SVIP_ERR_NULL;
     if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
-    if (B <= 0 || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || row_stride < V ||
+    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || row_stride < V ||
         seq_stride_t < (long long)k_max * row_stride + V || seq_stride_d < (long long)(k_max - 1) * row_stride + V)
         return SVIP_ERR_SHAPE;
-    const long long nrows = (long long)B * (2LL * k_max + 1);
-    if (nrows > 65535) return SVIP_ERR_SHAPE;          // grid.y limit of the statistics pass
+    const int kd = draft_lse ? 0 : k_max;
+    const long long stat_rows = (long long)B * (kd + k_max + 1);
+    if (stat_rows > MAX_BATCH) return SVIP_ERR_SHAPE;          // grid.y limit of the statistics pass
     const int vec = dtype == SVIP_BF16 ? 8 : 4;
     if (!aligned16(target_logits) || !aligned16(draft_logits) || row_stride % vec != 0 ||
         seq_stride_t % vec != 0 || seq_stride_d % vec != 0)
         return SVIP_ERR_ALIGN;
     if (!(temperature > 0.f) || !isfinite(temperature)) return SVIP_ERR_PARAM;
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
-        workspace_bytes < svip_workspace_bytes(B, k_max, V))
-        return SVIP_ERR_WORKSPACE;
 
     VerifyArgs a;
+    a.geo = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    a.geo_s = make_geo(V, vec, B, true, env_int("SVIP_SAMPLE_SLICES", 0));
+    const size_t need = HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) +
+                        (size_t)stat_rows * a.geo.ns * sizeof(Partial);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+        return SVIP_ERR_WORKSPACE;
     a.target = target_logits;
     a.draft = draft_logits;
     a.seq_t = seq_stride_t;
@@ -700,9 +701,7 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
     a.row_stride = row_stride;
     a.B = B;
     a.k = k_max;
-    const int stat_rows = B * (k_max + 1) + (draft_lse ? 0 : B * k_max);
-    a.geo = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    a.geo_s = make_geo(V, vec, B, true, env_int("SVIP_SAMPLE_SLICES", 0));
+    a.kd = kd;
     a.sc = make_scale(temperature);
     a.tokens = draft_tokens;
     a.draft_len = draft_len;
@@ -712,19 +711,26 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
     a.n_accepted = n_accepted_out;
     a.next_token = next_token_out;
     a.accept_prob = accept_prob_out;
-    a.ws = carve(workspace, B, k_max);
+    a.ws = carve(workspace, B);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 g_stats(a.geo.ns, stat_rows), g_mass(a.geo_s.ns, B);
+    const dim3 g_stats(a.geo.ns, (unsigned)stat_rows), g_mass(a.geo_s.ns, B);
     const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
     if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], st);
-    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify<bf16>, g_stats, dim3(WG), 0, st, a);
-    else hipLaunchKernelGGL(k_verify<float>, g_stats, dim3(WG), 0, st, a);
+    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a);
+    else hipLaunchKernelGGL(k_verify_stats<float>, g_stats, dim3(WG), 0, st, a);
     if (timed) {
         (void)hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st);
         ++g_prof.used;
     }
-    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_resid<bf16>, g_mass, dim3(WG), 0, st, a);
-    else hipLaunchKernelGGL(k_resid<float>, g_mass, dim3(WG), 0, st, a);
+    if (dtype == SVIP_BF16) {
+        hipLaunchKernelGGL(k_accept<bf16>, dim3(B), dim3(64), 0, st, a);
+        hipLaunchKernelGGL(k_resid_mass<bf16>, g_mass, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_resid_finish<bf16>, dim3(B), dim3(WG), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(k_accept<float>, dim3(B), dim3(64), 0, st, a);
+        hipLaunchKernelGGL(k_resid_mass<float>, g_mass, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_resid_finish<float>, dim3(B), dim3(WG), 0, st, a);
+    }
     return check_launch();
 }
 
