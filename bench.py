@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch the draft steps eagerly")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences in the oracle sample (0 = auto)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain device copies of 256 MiB (reference for rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -187,6 +189,13 @@ def main():
         if not a.no_graph:
             for s in sets:
                 s.capture(h)
+        torch.cuda.synchronize()
+
+    if a.calibrate_copy:       # known traffic for scaling FETCH_SIZE / WRITE_SIZE: 256 MiB read + 256 MiB written
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
         torch.cuda.synchronize()
 
     # ---- headline: every sequence drafts k_max positions ---------------------------------

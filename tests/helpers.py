@@ -70,6 +70,11 @@ class Round:
         torch.cuda.synchronize()
 
 
+def f32(x):
+    """The value the C ABI receives for a float argument, as a Python float."""
+    return float(np.float32(x))
+
+
 def cell_is_valid(prob, tok, u, tol):
     """True if token `tok` is a legitimate draw for uniform u up to `tol` of cumulative mass."""
     if tok < 0 or tok >= prob.size or not prob[tok] > 0:
@@ -84,6 +89,7 @@ def check_draft_rows(draft_cpu, T, h, k_max, u_sample, gpu, rows=None, steps=Non
     """Compare unchained draft-step outputs of `gpu` (a Round after draft_all(chain=False))
     with the oracle for rows x steps.  Returns a dict of counts."""
     B, k, V = draft_cpu.shape
+    T, h = f32(T), f32(h)
     rows = range(B) if rows is None else rows
     steps = range(k) if steps is None else steps
     tok = gpu.tokens.cpu().numpy()
@@ -126,13 +132,16 @@ def check_draft_rows(draft_cpu, T, h, k_max, u_sample, gpu, rows=None, steps=Non
 
 
 def oracle_chain(draft_cpu, T, h, u_sample):
-    """Algorithm 1's drafting loop through the oracle: tokens [B, k] (-1 where not drafted),
-    draft_len [B], lse [B, k], min decision margin per row over its drafted steps."""
+    """Algorithm 1's drafting loop through the oracle.  Returns tokens [B, k] (-1 where not
+    drafted), draft_len [B], lse [B, k], and per (row, step) the stop-test margin and the
+    sampler margin (inf where the row was no longer drafting)."""
     B, k, V = draft_cpu.shape
+    T, h = f32(T), f32(h)
     tokens = np.full((B, k), -1, np.int64)
     lse = np.zeros((B, k))
     dl = np.zeros(B, np.int64)
-    margin = np.full(B, np.inf)
+    mh = np.full((B, k), np.inf)
+    ms = np.full((B, k), np.inf)
     stop = np.zeros(B, np.uint8)
     for j in range(k):
         o = oracle.draft_step(draft_cpu[:, j].double().numpy(), T, h, j, k, u_sample[:, j].double().numpy(),
@@ -141,15 +150,44 @@ def oracle_chain(draft_cpu, T, h, u_sample):
         tokens[act, j] = o.token[act]
         lse[act, j] = o.lse[act]
         dl[act] = j + 1
-        margin[act] = np.minimum(margin[act], np.minimum(o.margin_h[act], o.margin_s[act]))
+        mh[act, j] = o.margin_h[act]
+        ms[act, j] = o.margin_s[act]
         stop = o.stop.copy()
-    return tokens, dl, lse, margin
+    return tokens, dl, lse, mh, ms
+
+
+def check_chain(gpu_tokens, gpu_len, tokens, dl, mh, ms, rows=None):
+    """Chained draft outputs against oracle_chain, decision by decision: a row's draft length is
+    compared when every stop test it went through was outside the margin, each token when its
+    own draw (and the stop tests before it) were.  Returns counts."""
+    B, k = tokens.shape
+    rows = range(B) if rows is None else rows
+    st = dict(rows=0, len_checked=0, tok_checked=0, tok_excluded=0, tok_excluded_diff=0)
+    for n, b in enumerate(rows):
+        st["rows"] += 1
+        g = int(dl[n])
+        stops_ok = np.concatenate([[True], np.cumprod(mh[n, :g] >= MARGIN).astype(bool)])   # [j]: tests before j
+        if stops_ok[g]:
+            st["len_checked"] += 1
+            assert gpu_len[b] == g, f"row {b}: draft_len {gpu_len[b]} != {g}"
+            assert (gpu_tokens[b, g:] == -1).all(), f"row {b}: steps after the stop must hold -1"
+        for j in range(g):
+            if not stops_ok[j]:
+                break
+            if ms[n, j] >= MARGIN:
+                st["tok_checked"] += 1
+                assert gpu_tokens[b, j] == tokens[n, j], f"row {b} step {j}: token {gpu_tokens[b, j]} != {tokens[n, j]}"
+            else:
+                st["tok_excluded"] += 1
+                st["tok_excluded_diff"] += int(gpu_tokens[b, j] != tokens[n, j])
+    return st
 
 
 def check_verify(draft_cpu, target_cpu, T, tokens, draft_len, u_accept, u_resample, gpu, rows=None,
                  stats=None):
     """Compare verify outputs of `gpu` with the oracle for sequences `rows`."""
     B, k, V = draft_cpu.shape
+    T = f32(T)
     rows = list(range(B)) if rows is None else list(rows)
     nacc = gpu.n_accepted.cpu().numpy()
     nxt = gpu.next_token.cpu().numpy()
@@ -178,4 +216,7 @@ def check_verify(draft_cpu, target_cpu, T, tokens, draft_len, u_accept, u_resamp
             st["excluded"] += 1
             if nacc[b] != o.n_accepted[0] or nxt[b] != o.next_token[0]:
                 st["excluded_diff"] += 1
+                # inside the margin the accepted count may move by the one borderline position,
+                # and a differing token must still be a neighbouring cell of the same draw
+                assert abs(int(nacc[b]) - int(o.n_accepted[0])) <= g, where
     return st

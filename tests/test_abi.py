@@ -1,0 +1,92 @@
+"""The C-ABI library without a GPU: it loads, exports every declared symbol, and rejects bad
+arguments on the host before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import paper_2411_18462_amd as svip
+from paper_2411_18462_amd.binding import EXPORTS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = svip.load()
+    header = open(os.path.join(ROOT, "include", "svip.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(svip_[a-z_]+)\s*\(", header))
+    assert declared == set(EXPORTS), declared ^ set(EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    lib = svip.load()
+    seen = set()
+    for code in range(8):
+        s = lib.svip_status_string(code).decode()
+        assert s.startswith("SVIP_") and s not in seen
+        seen.add(s)
+    assert b"unknown" in lib.svip_status_string(99)
+
+
+def test_workspace_bytes_is_a_pure_host_function():
+    assert svip.workspace_bytes(0, 16, 128256) == 0
+    assert svip.workspace_bytes(64, 0, 128256) == 0
+    assert svip.workspace_bytes(64, svip.MAX_K + 1, 128256) == 0
+    assert svip.workspace_bytes(64, 16, 0) == 0
+    small, big = svip.workspace_bytes(1, 8, 32000), svip.workspace_bytes(64, 16, 128256)
+    assert 0 < small <= big < (1 << 30) and small % 256 == 0 and big % 256 == 0
+    assert svip.workspace_bytes(256, 64, 151936) >= big
+
+
+def test_host_checks_reject_before_any_gpu_call():
+    """No GPU here: every call below must fail on its argument checks (a launch would give
+    SVIP_ERR_HIP instead)."""
+    lib = svip.load()
+    buf = ctypes.create_string_buffer(1 << 16)
+    p = (ctypes.addressof(buf) + 255) & ~255          # fake, aligned "device" pointers, never dereferenced
+    ws_bytes = svip.workspace_bytes(2, 4, 64)
+    V = 64
+
+    def draft(**kw):
+        a = dict(logits=p, dtype=1, B=2, V=V, row_stride=V, T=1.0, h=0.3, j=0, k=4, u=p, stop_in=None, tok=p,
+                 ent=None, q=None, lse=p, stop=p, dl=None, ios=1, ws=p, wsb=ws_bytes, st=None)
+        a.update(kw)
+        return lib.svip_draft_step(a["logits"], a["dtype"], a["B"], a["V"], a["row_stride"], a["T"], a["h"], a["j"],
+                                   a["k"], a["u"], a["stop_in"], a["tok"], a["ent"], a["q"], a["lse"], a["stop"],
+                                   a["dl"], a["ios"], a["ws"], a["wsb"], a["st"])
+
+    assert draft(logits=None) == 1 and draft(u=None) == 1 and draft(tok=None) == 1 and draft(lse=None) == 1
+    assert draft(dtype=7) == 3
+    assert draft(B=0) == 2 and draft(V=0) == 2 and draft(k=0) == 2 and draft(j=4) == 2 and draft(j=-1) == 2
+    assert draft(ios=0) == 2 and draft(row_stride=V - 8) == 2 and draft(B=70000) == 2
+    assert draft(logits=p + 2) == 4 and draft(row_stride=V + 4) == 4 and draft(dtype=0, row_stride=V + 2) == 4
+    assert draft(T=0.0) == 6 and draft(T=-1.0) == 6 and draft(T=float("inf")) == 6 and draft(h=-0.1) == 6
+    assert draft(h=float("nan")) == 6 and draft(T=float("nan")) == 6
+    assert draft(ws=None) == 5 and draft(ws=p + 16) == 5 and draft(wsb=1024) == 5
+
+    def verify(**kw):
+        a = dict(t=p, d=p, dtype=1, B=2, k=4, V=V, st_t=5 * V, st_d=4 * V, rs=V, T=1.0, tok=p, dl=p, lse=None,
+                 ua=p, ur=p, na=p, nt=p, ap=None, ws=p, wsb=ws_bytes, st=None)
+        a.update(kw)
+        return lib.svip_verify(a["t"], a["d"], a["dtype"], a["B"], a["k"], a["V"], a["st_t"], a["st_d"], a["rs"],
+                               a["T"], a["tok"], a["dl"], a["lse"], a["ua"], a["ur"], a["na"], a["nt"], a["ap"],
+                               a["ws"], a["wsb"], a["st"])
+
+    assert verify(t=None) == 1 and verify(d=None) == 1 and verify(tok=None) == 1 and verify(dl=None) == 1
+    assert verify(ua=None) == 1 and verify(ur=None) == 1 and verify(na=None) == 1 and verify(nt=None) == 1
+    assert verify(dtype=2) == 3
+    assert verify(B=0) == 2 and verify(k=0) == 2 and verify(V=0) == 2 and verify(st_t=4 * V) == 2
+    assert verify(st_d=2 * V) == 2 and verify(rs=V - 8) == 2 and verify(B=40000, k=svip.MAX_K) == 2
+    assert verify(t=p + 8) == 4 and verify(rs=V + 4, st_t=5 * (V + 4), st_d=4 * (V + 4)) == 4
+    assert verify(T=0.0) == 6
+    assert verify(ws=None) == 5 and verify(wsb=512) == 5
+    assert lib.svip_workspace_reset(None, 1 << 20, None) == 5
+    assert lib.svip_workspace_reset(p + 8, 1 << 20, None) == 5
+    out = ctypes.c_uint(0)
+    assert lib.svip_workspace_flags(None, None, ctypes.byref(out)) == 5
+    assert lib.svip_workspace_flags(p, None, None) == 1
+    ms, n = ctypes.c_double(0), ctypes.c_int(0)
+    assert lib.svip_profile_end(ctypes.byref(ms), ctypes.byref(n)) == 6      # not begun
+    assert lib.svip_profile_begin(0) == 6
