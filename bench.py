@@ -39,7 +39,10 @@ def parse():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch the draft steps eagerly")
-    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences in the oracle sample (0 = auto)")
+    ap.add_argument("--cpu-seqs", type=int, default=0,
+                    help="sequences in the oracle sample (0 = four batches of the workload, ~15 s of CPU work)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="only the timed headline region (used for the rocprofv3 summaries under profiles/)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain device copies of 256 MiB (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -124,8 +127,8 @@ def cpu_baseline(w, h, nseq, threads):
     oracle.build()
     T, hh = float(np.float32(w.T)), float(np.float32(h))
 
-    def one(b):
-        s = si.gen_sequence(w, b, seed=0)
+    def one(i):
+        s = si.gen_sequence(w, i % w.B, seed=i // w.B)      # further batches of the workload: other seeds
         zq = s["draft"].double().numpy()
         zp = s["target"].double().numpy()
         stop = np.zeros(1, np.uint8)
@@ -150,6 +153,19 @@ def cpu_baseline(w, h, nseq, threads):
     rows = sum(r[1] for r in res)
     busy = sum(r[0] for r in res)
     return rows, wall, busy
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the statistics kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE scaled by a plain copy of known size), or None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"k_verify_stats_{workload}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(float(line.split("=")[1].split()[0]))
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -221,16 +237,32 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / n
 
-    n_ph = max(10, a.steps // 2)
-    t_draft = phase(lambda s: s.graph.replay() if s.graph is not None else s.draft_round(H_FULL), n_ph)
-    t_verify = phase(lambda s: s.verify(), n_ph)
-
-    # ---- the same round under the separating threshold (variable draft lengths) ----------
-    prepare(w.h)
-    dt_h, _ = timed(sets, w.h, max(10, a.steps // 2), 3, svip, False)
-    dl_h = sets[0].draft_len.cpu().numpy().astype(np.int64)
-    rows_h = int(dl_h.sum() + (dl_h + 1).sum())
-    steps_h = max(10, a.steps // 2)
+    extra = {}
+    if not a.headline_only:
+        n_ph = max(10, a.steps // 2)
+        t_draft = phase(lambda s: s.graph.replay() if s.graph is not None else s.draft_round(H_FULL), n_ph)
+        t_verify = phase(lambda s: s.verify(), n_ph)
+        extra["phases"] = {
+            "draft_round_us": 1e6 * t_draft,
+            "draft_step_us": 1e6 * t_draft / k,
+            "draft_GBps": draft_bytes / t_draft / 1e9,
+            "verify_us": 1e6 * t_verify,
+            "verify_GBps": verify_bytes / t_verify / 1e9,
+            "whole_round_GBps": (draft_bytes + verify_bytes) * a.steps / dt / 1e9,
+        }
+        # the same round under the threshold that separates the mixture (variable draft lengths)
+        prepare(w.h)
+        steps_h = max(10, a.steps // 2)
+        dt_h, _ = timed(sets, w.h, steps_h, 3, svip, False)
+        dl_h = sets[0].draft_len.cpu().numpy().astype(np.int64)
+        rows_h = int(dl_h.sum() + (dl_h + 1).sum())
+        extra["svip_policy_h3"] = {
+            "h": w.h,
+            "rows_per_step": rows_h,
+            "mean_draft_len": float(dl_h.mean()),
+            "rows_per_s": rows_h * steps_h / dt_h,
+            "ms_per_step": 1e3 * dt_h / steps_h,
+        }
 
     out = {
         "metric": "draft+verify rows/sec and achieved HBM GB/s (% peak) at V=128K bf16, B=64",
@@ -260,38 +292,26 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": measured_traffic(w.name),
             "bytes_per_launch": stats_bytes,
             "avg_kernel_us": kern_us,
             "launches_timed": kern_n,
         },
-        "phases": {
-            "draft_round_us": 1e6 * t_draft,
-            "draft_GBps": draft_bytes / t_draft / 1e9,
-            "verify_us": 1e6 * t_verify,
-            "verify_GBps": verify_bytes / t_verify / 1e9,
-            "whole_round_GBps": (draft_bytes + verify_bytes) * a.steps / dt / 1e9,
-        },
-        "svip_policy_h3": {
-            "h": w.h,
-            "rows_per_step": rows_h,
-            "mean_draft_len": float(dl_h.mean()),
-            "rows_per_s": rows_h * steps_h / dt_h,
-            "ms_per_step": 1e3 * dt_h / steps_h,
-        },
     }
+    out.update(extra)
 
     if not a.no_cpu_baseline:
         threads = min(16, os.cpu_count() or 1)
-        nseq = a.cpu_seqs or B
+        nseq = a.cpu_seqs or 4 * B
         rows, wall, busy = cpu_baseline(w, H_FULL, nseq, threads)
         out["cpu_baseline"] = {
             "value": rows / wall,
             "unit": "rows/s",
             "cores": threads,
             "kind": "oracle",
-            "sample": f"{nseq} of {B} sequences of the same round (chained draft steps + verify), "
-                      f"{rows} rows, {wall:.1f} s wall, {busy:.1f} s summed thread time",
+            "sample": f"{nseq} sequences ({nseq / B:g} batches of the workload, seeds 0..) through the same round "
+                      f"(chained draft steps + verify), {rows} rows, {wall:.1f} s wall, "
+                      f"{busy:.1f} s summed thread time",
         }
     print(json.dumps(out))
 

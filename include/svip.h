@@ -18,7 +18,8 @@
  * General rules
  *   - Every pointer marked "device" is GPU memory of the current HIP device; "host" is CPU
  *     memory.  The caller owns every buffer; the library allocates nothing, frees nothing
- *     and keeps no pointer after a call returns.
+ *     and keeps no pointer after a call returns (the benchmark timing hook at the end of
+ *     this header, which creates HIP events, is the one exception).
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without synchronising.  Outputs are valid once the stream
  *     has reached that point.
