@@ -37,7 +37,7 @@ struct Workspace {
     Partial *part;       // [stat rows][ns] slice statistics
 };
 
-constexpr int MAX_BATCH = 65535;                 // grid.y limit of a launch
+constexpr int MAX_BATCH = 1 << 20;               // sequences per call (grids are one-dimensional)
 constexpr size_t HEADER_BYTES = 256;
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -218,12 +218,12 @@ __device__ __forceinline__ int pick_slice(double M, double target, double incl, 
 
 // ---- draft step -------------------------------------------------------------------------------
 
-// grid (slices, rows): statistics of slice s of row b.
+// grid (rows * slices): statistics of slice s of row b.
 template <typename DT>
 __global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
 {
     __shared__ double lds[2 * NWAVE];
-    const int s = blockIdx.x, b = blockIdx.y;
+    const int b = blockIdx.x / a.geo.ns, s = blockIdx.x - b * a.geo.ns;
     if (a.stop_in && a.stop_in[b]) return;
     const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
     const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
@@ -308,15 +308,15 @@ __device__ __forceinline__ size_t stat_row(const VerifyArgs &a, int b, int jj)
     return (size_t)b * (a.kd + a.k + 1) + jj;
 }
 
-// grid (slices, sequences * rows per sequence).  Draft rows are needed for j < draft_len[b],
+// grid (sequences * rows per sequence * slices).  Draft rows are needed for j < draft_len[b],
 // target rows for j <= draft_len[b]; workgroups of other rows exit at once.
 template <typename DT>
 __global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
 {
     __shared__ double lds[2 * NWAVE];
-    const int s = blockIdx.x;
+    const int y = blockIdx.x / a.geo.ns, s = blockIdx.x - y * a.geo.ns;
     const int rps = a.kd + a.k + 1;
-    const int b = blockIdx.y / rps, jj = blockIdx.y - b * rps;
+    const int b = y / rps, jj = y - b * rps;
     const int g = clamp_len(a.draft_len[b], a.k);
     const DT *row;
     if (jj < a.kd) {
@@ -423,13 +423,13 @@ __global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
 
 // ---- verify: residual / bonus sampling ------------------------------------------------------
 
-// grid (slices, sequences): slice masses of the weights to sample from -- [0] residual
+// grid (sequences * slices): slice masses of the weights to sample from -- [0] residual
 // max(0, p - q) at the rejected position, [1] target p of the row to sample.
 template <typename DT>
 __global__ __launch_bounds__(WG) void k_resid_mass(VerifyArgs a)
 {
     __shared__ double lds[2 * NWAVE];
-    const int s = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int b = blockIdx.x / a.geo_s.ns, s = blockIdx.x - b * a.geo_s.ns, tid = threadIdx.x;
     const SeqRec rec = a.ws.rec[b];
     const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
     const DT *qrow = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)rec.r * a.row_stride;
@@ -652,7 +652,7 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
     a.io_stride = io_stride;
     a.part = w.part;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid(a.geo.ns, B);
+    const dim3 grid((unsigned)a.geo.ns * (unsigned)B);
     if (dtype == SVIP_BF16) {
         hipLaunchKernelGGL(k_draft_stats<bf16>, grid, dim3(WG), 0, st, a);
         hipLaunchKernelGGL(k_draft_finish<bf16>, dim3(B), dim3(WG), 0, st, a);
@@ -680,7 +680,7 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
         return SVIP_ERR_SHAPE;
     const int kd = draft_lse ? 0 : k_max;
     const long long stat_rows = (long long)B * (kd + k_max + 1);
-    if (stat_rows > MAX_BATCH) return SVIP_ERR_SHAPE;          // grid.y limit of the statistics pass
+    if (stat_rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;          // workgroups of the statistics pass
     const int vec = dtype == SVIP_BF16 ? 8 : 4;
     if (!aligned16(target_logits) || !aligned16(draft_logits) || row_stride % vec != 0 ||
         seq_stride_t % vec != 0 || seq_stride_d % vec != 0)
@@ -713,7 +713,7 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
     a.accept_prob = accept_prob_out;
     a.ws = carve(workspace, B);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 g_stats(a.geo.ns, (unsigned)stat_rows), g_mass(a.geo_s.ns, B);
+    const dim3 g_stats((unsigned)(stat_rows * a.geo.ns)), g_mass((unsigned)a.geo_s.ns * (unsigned)B);
     const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
     if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], st);
     if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a);

@@ -60,7 +60,7 @@ def test_host_checks_reject_before_any_gpu_call():
     assert draft(logits=None) == 1 and draft(u=None) == 1 and draft(tok=None) == 1 and draft(lse=None) == 1
     assert draft(dtype=7) == 3
     assert draft(B=0) == 2 and draft(V=0) == 2 and draft(k=0) == 2 and draft(j=4) == 2 and draft(j=-1) == 2
-    assert draft(ios=0) == 2 and draft(row_stride=V - 8) == 2 and draft(B=70000) == 2
+    assert draft(ios=0) == 2 and draft(row_stride=V - 8) == 2 and draft(B=(1 << 20) + 1) == 2
     assert draft(logits=p + 2) == 4 and draft(row_stride=V + 4) == 4 and draft(dtype=0, row_stride=V + 2) == 4
     assert draft(T=0.0) == 6 and draft(T=-1.0) == 6 and draft(T=float("inf")) == 6 and draft(h=-0.1) == 6
     assert draft(h=float("nan")) == 6 and draft(T=float("nan")) == 6
@@ -78,7 +78,7 @@ def test_host_checks_reject_before_any_gpu_call():
     assert verify(ua=None) == 1 and verify(ur=None) == 1 and verify(na=None) == 1 and verify(nt=None) == 1
     assert verify(dtype=2) == 3
     assert verify(B=0) == 2 and verify(k=0) == 2 and verify(V=0) == 2 and verify(st_t=4 * V) == 2
-    assert verify(st_d=2 * V) == 2 and verify(rs=V - 8) == 2 and verify(B=40000, k=svip.MAX_K) == 2
+    assert verify(st_d=2 * V) == 2 and verify(rs=V - 8) == 2 and verify(B=(1 << 20) + 1) == 2
     assert verify(t=p + 8) == 4 and verify(rs=V + 4, st_t=5 * (V + 4), st_d=4 * (V + 4)) == 4
     assert verify(T=0.0) == 6
     assert verify(ws=None) == 5 and verify(wsb=512) == 5

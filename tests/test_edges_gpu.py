@@ -204,3 +204,21 @@ def test_host_errors_enqueue_nothing(svip):
     assert e.value.status == 4
     torch.cuda.synchronize()
     assert (r.tokens.cpu().numpy() == -7).all()              # nothing ran
+
+
+def test_large_batch_of_short_rows(svip):
+    """B = 6000 sequences (more statistics rows than a 16-bit grid dimension), tiny vocabulary."""
+    B, k, V = 6000, 5, 96
+    draft, target, us, ua, ur = _make(B, k, V, torch.float32, seed=23, scale=1.5, noise=0.7)
+    r = Round(svip, draft, target, us, ua, ur, 1.0, 1.9)
+    r.draft_all(chain=True)
+    from helpers import check_chain, oracle_chain
+    rows = list(range(0, B, 97))
+    tokens, dl, lse, mh, ms = oracle_chain(draft[rows], 1.0, 1.9, us[rows])
+    st = check_chain(r.tokens.cpu().numpy(), r.draft_len.cpu().numpy(), tokens, dl, mh, ms, rows=rows)
+    for mode in ("given", None):
+        r.verify(lse=mode)
+        sv = check_verify(draft, target, 1.0, r.tokens.cpu().numpy().astype(np.int64),
+                          r.draft_len.cpu().numpy().astype(np.int64), ua, ur, r, rows=rows)
+    assert svip.workspace_flags(r.ws) == 0
+    _say(f"B={B}: chain {st} verify {sv}")
