@@ -56,6 +56,14 @@ def _load():
         lib.oracle_verify.argtypes = [
             _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
             _L, _L, _D, _D, _L, _L, _D, _D, _D]
+        lib.oracle_argmax_row.restype = ctypes.c_long
+        lib.oracle_argmax_row.argtypes = [_D, ctypes.c_long]
+        lib.oracle_draft_step_greedy.restype = None
+        lib.oracle_draft_step_greedy.argtypes = [
+            _D, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_double,
+            ctypes.c_long, ctypes.c_long, _U8, _L, _D, _D, _D, _U8, _D]
+        lib.oracle_verify_greedy.restype = None
+        lib.oracle_verify_greedy.argtypes = [_D, ctypes.c_long, ctypes.c_long, ctypes.c_long, _L, _L, _L, _L]
         lib.oracle_pair_stats.restype = None
         lib.oracle_pair_stats.argtypes = [_D, _D, ctypes.c_long, ctypes.c_double, _D]
         lib.oracle_sd_position_trials.restype = None
@@ -168,6 +176,44 @@ def verify(zp, zq, T, tok, gamma, ua, ur) -> VerifyResult:
         _p(ua, _D), _p(ur, _D), _p(out.n_accepted, _L), _p(out.next_token, _L),
         _p(out.accept_prob, _D), _p(out.margin, _D), _p(out.resid_mass, _D))
     return out
+
+
+def argmax_row(z) -> int:
+    z = _f64(z).ravel()
+    return int(_load().oracle_argmax_row(_p(z, _D), z.size))
+
+
+def draft_step_greedy(z, T, h, step_j, k_max, stop_in=None) -> DraftStepResult:
+    """Greedy draft-side pass over z[B, V]: token = argmax; margin_s is inf (no draw)."""
+    z = _f64(z)
+    assert z.ndim == 2
+    B, V = z.shape
+    si = None
+    if stop_in is not None:
+        si = np.ascontiguousarray(_i64(stop_in).ravel() != 0, dtype=np.uint8)
+        assert si.size == B
+    out = DraftStepResult(
+        np.empty(B, np.int64), np.empty(B), np.empty(B), np.empty(B),
+        np.empty(B, np.uint8), np.empty(B), np.full(B, np.inf))
+    _load().oracle_draft_step_greedy(
+        _p(z, _D), B, V, V, float(T), float(h), int(step_j), int(k_max),
+        _p(si, _U8) if si is not None else None,
+        _p(out.token, _L), _p(out.entropy, _D), _p(out.q_tok, _D), _p(out.lse, _D),
+        _p(out.stop, _U8), _p(out.margin_h, _D))
+    return out
+
+
+def verify_greedy(zp, tok, gamma):
+    """(n_accepted[B], next_token[B]) of greedy verification; zp[B, k+1, V]."""
+    zp = _f64(zp)
+    B, kp1, V = zp.shape
+    k = kp1 - 1
+    tok = _i64(tok).reshape(B, k)
+    gamma = _i64(gamma).ravel()
+    assert gamma.size == B and (gamma >= 0).all() and (gamma <= k).all()
+    nacc, nxt = np.empty(B, np.int64), np.empty(B, np.int64)
+    _load().oracle_verify_greedy(_p(zp, _D), B, k, V, _p(tok, _L), _p(gamma, _L), _p(nacc, _L), _p(nxt, _L))
+    return nacc, nxt
 
 
 def pair_stats(zp_row, zq_row, T: float = 1.0) -> dict:

@@ -17,6 +17,7 @@
  *     the listing prints q - p, which cannot preserve the target law the paper
  *     claims in Section 1 -- the p - q direction is the one that does
  *   - bonus token x ~ p(.|all drafts) if nothing rejected  Algorithm 1, last "Sample" step
+ *   - greedy decoding: accept iff argmax p = x, correct with argmax p   Algorithms 3 and 5
  * plus the diagnostics of Section 2.2: beta = sum min(p,q) (Eq. beta), KL(q||p) and
  * the cross entropy H_{q,p} (Eq. pinsker / beta-bound).
  *
@@ -204,6 +205,70 @@ void oracle_verify(const double *zp, const double *zq, long B, long k_max, long 
         margin[b] = ms < mar ? ms : mar;
     }
     free(p); free(q); free(w);
+}
+
+/* ---- greedy decoding (Algorithm 3 Verify, Algorithm 5 Correct) ---------------------- */
+
+/* Index of the largest logit; among equal maxima the smallest index. */
+long oracle_argmax_row(const double *z, long V)
+{
+    long best = 0;
+    for (long i = 1; i < V; ++i)
+        if (z[i] > z[best]) best = i;
+    return best;
+}
+
+/*
+ * Draft step under greedy decoding: the draft token is argmax q instead of a draw; the
+ * entropy of softmax(z / T) still drives the stop test (Section 2.2) and the cap applies.
+ */
+void oracle_draft_step_greedy(const double *z, long B, long V, long row_stride,
+                              double T, double h, long step_j, long k_max,
+                              const unsigned char *stop_in,
+                              long *token, double *entropy, double *q_tok, double *lse,
+                              unsigned char *stop, double *margin_h)
+{
+    double *q = (double *)malloc(sizeof(double) * (size_t)V);
+    for (long b = 0; b < B; ++b) {
+        if (stop_in && stop_in[b]) {
+            token[b] = -1; entropy[b] = 0; q_tok[b] = 0; lse[b] = 0; stop[b] = 1;
+            margin_h[b] = INFINITY;
+            continue;
+        }
+        const double *zb = z + b * row_stride;
+        lse[b] = oracle_softmax_row(zb, V, T, q);
+        double H = oracle_entropy_row(q, V);
+        entropy[b] = H;
+        long x = oracle_argmax_row(zb, V);
+        token[b] = x;
+        q_tok[b] = q[x];
+        int by_entropy = sqrt(H) > h;
+        int by_cap = (step_j + 1 >= k_max);
+        stop[b] = (unsigned char)(by_entropy || by_cap);
+        margin_h[b] = by_cap ? INFINITY : fabs(sqrt(H) - h);
+    }
+    free(q);
+}
+
+/*
+ * Verification under greedy decoding: position j is accepted iff argmax p_j equals the draft
+ * token (Algorithm 3); at the first failure the correction is argmax p_j (Algorithm 5); if
+ * every draft is accepted the bonus token is argmax of the next target row.
+ * zp: [B][k_max+1][V], tok: [B][k_max], gamma[b] in 0..k_max.
+ */
+void oracle_verify_greedy(const double *zp, long B, long k_max, long V,
+                          const long *tok, const long *gamma,
+                          long *n_accepted, long *next_token)
+{
+    for (long b = 0; b < B; ++b) {
+        const double *zpb = zp + b * (k_max + 1) * V;
+        long g = gamma[b], r = g;
+        for (long j = 0; j < g; ++j) {
+            if (oracle_argmax_row(zpb + j * V, V) != tok[b * k_max + j]) { r = j; break; }
+        }
+        n_accepted[b] = r;
+        next_token[b] = oracle_argmax_row(zpb + r * V, V);
+    }
 }
 
 /* ---- diagnostics of Section 2.2 ------------------------------------------------ */

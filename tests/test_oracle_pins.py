@@ -359,3 +359,70 @@ def test_zero_residual_falls_back_to_target():
     r = oracle.verify(np.stack([z[0], z[0]])[None], z[None], 1.0, [[2]], [1], [[1.0]], [0.45])
     assert r.n_accepted[0] == 0 and r.resid_mass[0] == 0.0
     assert r.next_token[0] == 2 and r.margin[0] == 0.0
+
+
+# ---------------------------------------------------------------- greedy decoding (Algorithms 3 and 5)
+
+def test_argmax_first_maximum_and_numpy():
+    rng = _rng(41)
+    for V in (1, 2, 7, 1000):
+        z = rng.normal(0, 2, V)
+        assert oracle.argmax_row(z) == int(np.argmax(z))
+    z = np.array([0.5, 3.0, -1.0, 3.0, 3.0, 2.0])
+    assert oracle.argmax_row(z) == 1                       # smallest index among equal maxima
+    assert oracle.argmax_row(np.array([-np.inf, -np.inf, -5.0])) == 2
+    zq = np.round(rng.normal(0, 1, (4, 50)) * 4) / 4       # coarse values: ties are common
+    r = oracle.draft_step_greedy(zq, 1.0, 0.3, 0, 40)
+    assert np.array_equal(r.token, np.argmax(zq, axis=1))
+    s = oracle.draft_step(zq, 1.0, 0.3, 0, 40, rng.random(4))
+    assert np.allclose(r.entropy, s.entropy) and np.allclose(r.lse, s.lse) and np.array_equal(r.stop, s.stop)
+    p = scipy.special.softmax(zq, axis=1)
+    assert np.allclose(r.q_tok, p[np.arange(4), r.token], rtol=1e-12)
+
+
+def test_greedy_verify_all_prefix_lengths():
+    rng = _rng(42)
+    B, k, V = 9, 8, 30
+    zp = rng.normal(0, 2, (B, k + 1, V))
+    am = np.argmax(zp, axis=2)
+    tok = am[:, :k].copy()
+    gamma = np.array([8, 8, 5, 0, 1, 8, 3, 8, 8])
+    first_bad = [8, 0, 2, 0, 0, 7, 3, 4, 8]                # where the draft departs from argmax p
+    for b, j in enumerate(first_bad):
+        if j < k:
+            tok[b, j] = (am[b, j] + 1) % V
+    nacc, nxt = oracle.verify_greedy(zp, tok, gamma)
+    for b in range(B):
+        r = min(first_bad[b], gamma[b])
+        assert nacc[b] == r and nxt[b] == am[b, r]
+
+
+def test_greedy_is_the_zero_temperature_limit_of_sampling():
+    """At a tiny temperature the softmax of a tie-free row is one-hot at its argmax, so the
+    sampling oracle (already pinned) must reproduce the greedy one."""
+    rng = _rng(43)
+    B, k, V = 6, 5, 40
+    zq = rng.normal(0, 3, (B, k, V))
+    zp = np.concatenate([zq, rng.normal(0, 3, (B, 1, V))], 1) + rng.normal(0, 2.0, (B, k + 1, V))
+    T = 1e-3
+    tok = np.zeros((B, k), np.int64)
+    for j in range(k):
+        g = oracle.draft_step_greedy(zq[:, j], 1.0, 9.0, j, k + 1)
+        s = oracle.draft_step(zq[:, j], T, 9e9, j, k + 1, rng.random(B))
+        assert np.array_equal(g.token, s.token)
+        tok[:, j] = g.token
+    gamma = np.full(B, k)
+    nacc, nxt = oracle.verify_greedy(zp, tok, gamma)
+    s = oracle.verify(zp, zq, T, tok, gamma, rng.random((B, k)), rng.random(B))
+    assert np.array_equal(nacc, s.n_accepted) and np.array_equal(nxt, s.next_token)
+    assert (nacc < k).any()          # the perturbed target does reject somewhere
+
+
+def test_greedy_identical_models_accept_everything():
+    rng = _rng(44)
+    B, k, V = 4, 6, 25
+    z = rng.normal(0, 1, (B, k + 1, V))
+    tok = np.argmax(z[:, :k], axis=2)
+    nacc, nxt = oracle.verify_greedy(z, tok, np.array([6, 4, 0, 1]))
+    assert np.array_equal(nacc, [6, 4, 0, 1])
+    assert np.array_equal(nxt, [np.argmax(z[b, g]) for b, g in enumerate([6, 4, 0, 1])])
