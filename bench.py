@@ -68,23 +68,37 @@ class RoundBuffers:
         self.accept_prob = torch.zeros(B, k, dtype=torch.float32, device=dev)
         self.ws = svip.new_workspace(B, k, V)
         self.graph = None
+        self.graph_greedy = None
 
-    def draft_round(self, h):
+    def draft_round(self, h, greedy=False):
         """Algorithm 1's drafting loop, flags threaded on the device (no host sync)."""
         self.stop.zero_()
         for j in range(self.k):
             self.svip.draft_step(
-                self.draft[:, j], temperature=self.w.T, h=h, step_j=j, k_max=self.k,
+                self.draft[:, j], temperature=self.w.T, h=h, step_j=j, k_max=self.k, greedy=greedy,
                 u_sample=self.us[:, j], stop_in=self.stop, token_out=self.tokens[:, j],
                 entropy_out=self.entropy[:, j], q_tok_out=self.q_tok[:, j], lse_out=self.lse[:, j],
                 stop_out=self.stop, draft_len_out=self.draft_len, workspace=self.ws)
 
-    def capture(self, h):
+    def capture(self, h, greedy=False):
         import torch
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            self.draft_round(h)
-        self.graph = g
+            self.draft_round(h, greedy)
+        if greedy:
+            self.graph_greedy = g
+        else:
+            self.graph = g
+
+    def step_greedy(self, h):
+        """The same round under greedy decoding (Algorithms 3 and 5)."""
+        if self.graph_greedy is not None:
+            self.graph_greedy.replay()
+        else:
+            self.draft_round(h, True)
+        self.svip.verify_greedy(
+            self.target, draft_tokens=self.tokens, draft_len=self.draft_len,
+            n_accepted_out=self.n_accepted, next_token_out=self.next_token, workspace=self.ws)
 
     def verify(self):
         self.svip.verify(
@@ -262,6 +276,25 @@ def main():
             "mean_draft_len": float(dl_h.mean()),
             "rows_per_s": rows_h * steps_h / dt_h,
             "ms_per_step": 1e3 * dt_h / steps_h,
+        }
+
+        # greedy decoding over the same buffers: argmax drafting, argmax-only verification
+        for s in sets:
+            s.step_greedy(H_FULL)
+        torch.cuda.synchronize()
+        if not a.no_graph:
+            for s in sets:
+                s.capture(H_FULL, greedy=True)
+        t_g = phase(lambda s: s.step_greedy(H_FULL), steps_h)
+        t_gv = phase(lambda s: s.svip.verify_greedy(
+            s.target, draft_tokens=s.tokens, draft_len=s.draft_len, n_accepted_out=s.n_accepted,
+            next_token_out=s.next_token, workspace=s.ws), steps_h)
+        extra["greedy"] = {
+            "rows_per_s": rows_per_step / t_g,
+            "ms_per_step": 1e3 * t_g,
+            "verify_us": 1e6 * t_gv,
+            "verify_GBps": stats_bytes / t_gv / 1e9,
+            "mean_accepted": float(sets[0].n_accepted.float().mean()),
         }
 
     out = {

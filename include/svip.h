@@ -14,6 +14,8 @@
  *                     rejected, the bonus token drawn from the next target row
  *                                                       (Algorithm 1, verification loop;
  *                                                        Algorithm 2 Verify, Algorithm 4 Correct)
+ *   svip_draft_step_greedy, svip_verify_greedy    the same two steps under greedy decoding
+ *                                                       (Algorithm 3 Verify, Algorithm 5 Correct)
  *
  * General rules
  *   - Every pointer marked "device" is GPU memory of the current HIP device; "host" is CPU
@@ -152,6 +154,40 @@ svip_status svip_verify(
     int *n_accepted_out,             /* device [B] */
     int *next_token_out,             /* device [B] */
     float *accept_prob_out,          /* device [B, k_max] or NULL */
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Greedy decoding (Appendix A, Algorithms 3 and 5; the paper's reasoning-model and greedy
+ * long-form runs).
+ *
+ * svip_draft_step_greedy is svip_draft_step with the draw replaced by the first maximum:
+ * token = argmax of the row (the smallest index among equal maxima), q_tok_out = its
+ * probability; entropy (of softmax(logits / temperature)), logsumexp, stop test, cap, skipping
+ * of stopped rows and the output layout are identical.  No uniforms are needed.
+ */
+svip_status svip_draft_step_greedy(
+    const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+    float temperature, float h, int step_j, int k_max,
+    const unsigned char *stop_in, int *token_out, float *entropy_out, float *q_tok_out,
+    double *lse_out, unsigned char *stop_out, int *draft_len_out, long long io_stride,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Greedy verification of one round.  For each sequence b with g = draft_len[b]:
+ *   accept_j = (argmax target_logits[b, j, :] == draft_tokens[b, j])  for j < g   (Algorithm 3)
+ *   r = first j with accept_j false, or g;  n_accepted_out[b] = r
+ *   next_token_out[b] = argmax target_logits[b, r, :]   (Algorithm 5 correction, or the bonus token)
+ * argmax takes the smallest index among equal maxima.  Only the target rows j <= g are read; the
+ * draft logits are not needed.  Results are exact (comparisons only), for any dtype.
+ */
+svip_status svip_verify_greedy(
+    const void *target_logits,       /* device, row (b, j) at b * seq_stride_t + j * row_stride, j <= k_max */
+    svip_dtype dtype, int B, int k_max, int V,
+    long long seq_stride_t, long long row_stride,
+    const int *draft_tokens,         /* device [B, k_max] */
+    const int *draft_len,            /* device [B] */
+    int *n_accepted_out,             /* device [B] */
+    int *next_token_out,             /* device [B] */
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*

@@ -17,8 +17,8 @@ _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 
 # every symbol include/svip.h declares
 EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_reset",
-           "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_profile_begin",
-           "svip_profile_end")
+           "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_draft_step_greedy",
+           "svip_verify_greedy", "svip_profile_begin", "svip_profile_end")
 
 
 class SvipError(RuntimeError):
@@ -50,6 +50,10 @@ def load():
     lib.svip_draft_step.argtypes = [vp, i, i, i, ll, f, f, i, i, vp, vp, vp, vp, vp, vp, vp, vp, ll, vp, sz, vp]
     lib.svip_verify.restype = i
     lib.svip_verify.argtypes = [vp, vp, i, i, i, i, ll, ll, ll, f, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.svip_draft_step_greedy.restype = i
+    lib.svip_draft_step_greedy.argtypes = [vp, i, i, i, ll, f, f, i, i, vp, vp, vp, vp, vp, vp, vp, ll, vp, sz, vp]
+    lib.svip_verify_greedy.restype = i
+    lib.svip_verify_greedy.argtypes = [vp, i, i, i, i, ll, ll, vp, vp, vp, vp, vp, sz, vp]
     lib.svip_profile_begin.restype = i
     lib.svip_profile_begin.argtypes = [i]
     lib.svip_profile_end.restype = i
@@ -111,19 +115,22 @@ def workspace_flags(workspace: torch.Tensor, stream=None) -> int:
     return out.value
 
 
-def draft_step(draft_logits, *, temperature, h, step_j, k_max, u_sample, token_out, lse_out,
-               stop_out, workspace, stop_in=None, entropy_out=None, q_tok_out=None,
+def draft_step(draft_logits, *, temperature, h, step_j, k_max, token_out, lse_out, stop_out, workspace,
+               u_sample=None, greedy=False, stop_in=None, entropy_out=None, q_tok_out=None,
                draft_len_out=None, stream=None):
-    """svip_draft_step.  draft_logits: [B, V] view (unit stride along V); u_sample, token_out,
-    entropy_out, q_tok_out, lse_out: [B] tensors or column views sharing one stride;
-    stop_in / stop_out / draft_len_out: contiguous [B]."""
+    """svip_draft_step, or svip_draft_step_greedy when greedy=True (then u_sample is not used).
+    draft_logits: [B, V] view (unit stride along V); u_sample, token_out, entropy_out, q_tok_out,
+    lse_out: [B] tensors or column views sharing one stride; stop_in / stop_out / draft_len_out:
+    contiguous [B]."""
     if draft_logits.dim() != 2 or draft_logits.stride(1) != 1:
         raise ValueError("draft_logits must be [B, V] with unit stride along V")
     B, V = draft_logits.shape
     row_stride = draft_logits.stride(0) if B > 1 else max(V, draft_logits.stride(0))
     if draft_logits.dtype not in _DTYPES:
         raise SvipError(3, "logits must be float32 or bfloat16")
-    pu, ios = _col(u_sample, B, torch.float32, "u_sample")
+    if not greedy and u_sample is None:
+        raise SvipError(1, "u_sample is required unless greedy=True")
+    pu, ios = _col(None if greedy else u_sample, B, torch.float32, "u_sample")
     pt, ios = _col(token_out, B, torch.int32, "token_out", ios)
     pe, ios = _col(entropy_out, B, torch.float32, "entropy_out", ios)
     pq, ios = _col(q_tok_out, B, torch.float32, "q_tok_out", ios)
@@ -131,12 +138,37 @@ def draft_step(draft_logits, *, temperature, h, step_j, k_max, u_sample, token_o
     for t, n in ((stop_in, "stop_in"), (stop_out, "stop_out"), (draft_len_out, "draft_len_out")):
         if t is not None and (t.dim() != 1 or t.shape[0] != B or not t.is_contiguous()):
             raise ValueError(f"{n} must be contiguous [{B}]")
-    _check(load().svip_draft_step(
-        _ptr(draft_logits, None, "draft_logits"), _DTYPES[draft_logits.dtype], B, V, row_stride,
-        float(temperature), float(h), int(step_j), int(k_max), pu,
-        _ptr(stop_in, torch.uint8, "stop_in"), pt, pe, pq, pl,
-        _ptr(stop_out, torch.uint8, "stop_out"), _ptr(draft_len_out, torch.int32, "draft_len_out"),
-        ios or 1, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+    head = (_ptr(draft_logits, None, "draft_logits"), _DTYPES[draft_logits.dtype], B, V, row_stride,
+            float(temperature), float(h), int(step_j), int(k_max))
+    tail = (_ptr(stop_in, torch.uint8, "stop_in"), pt, pe, pq, pl,
+            _ptr(stop_out, torch.uint8, "stop_out"), _ptr(draft_len_out, torch.int32, "draft_len_out"),
+            ios or 1, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))
+    if greedy:
+        _check(load().svip_draft_step_greedy(*head, *tail))
+    else:
+        _check(load().svip_draft_step(*head, pu, *tail))
+
+
+def verify_greedy(target_logits, *, draft_tokens, draft_len, n_accepted_out, next_token_out, workspace,
+                  stream=None):
+    """svip_verify_greedy.  target_logits [B, k+1, V] (unit stride along V); draft_tokens [B, k]."""
+    if target_logits.dim() != 3 or target_logits.stride(2) != 1:
+        raise ValueError("target_logits must be [B, k+1, V] with unit stride along V")
+    B, kp1, V = target_logits.shape
+    k = kp1 - 1
+    if target_logits.dtype not in _DTYPES:
+        raise SvipError(3, "logits must be float32 or bfloat16")
+    row_stride = target_logits.stride(1)
+    seq_t = target_logits.stride(0) if B > 1 else kp1 * row_stride
+    for t, shape, n in ((draft_tokens, (B, k), "draft_tokens"), (draft_len, (B,), "draft_len"),
+                        (n_accepted_out, (B,), "n_accepted_out"), (next_token_out, (B,), "next_token_out")):
+        if tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError(f"{n} must be contiguous {list(shape)}")
+    _check(load().svip_verify_greedy(
+        _ptr(target_logits, None, "target_logits"), _DTYPES[target_logits.dtype], B, k, V, seq_t, row_stride,
+        _ptr(draft_tokens, torch.int32, "draft_tokens"), _ptr(draft_len, torch.int32, "draft_len"),
+        _ptr(n_accepted_out, torch.int32, "n_accepted_out"), _ptr(next_token_out, torch.int32, "next_token_out"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
 
 
 def verify(target_logits, draft_logits, *, temperature, draft_tokens, draft_len, u_accept,

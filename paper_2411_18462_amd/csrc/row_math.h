@@ -181,20 +181,38 @@ __device__ __forceinline__ ExpRef make_exp_ref(const Scale &sc, double L)
 //   S = sum exp2((z - m) c),   t = sum exp2((z - m) c) * (z - m) c    (t only if WITH_T).
 struct Partial {
     float m;
-    float pad;
+    int idx;       // smallest index holding m (only filled by the argmax-tracking variants)
     double S;
     double t;
 };
 
+// Smallest token index among the batch's elements equal to v (-1 if none); z[u] is vector
+// (t0 + u) * WG + tid of the row.
+template <int N, int NU>
+__device__ __forceinline__ int first_equal(const float (&z)[NU][N], float v, int t0)
+{
+    int found = -1;
+#pragma unroll
+    for (int u = NU - 1; u >= 0; --u) {
+#pragma unroll
+        for (int e = N - 1; e >= 0; --e)
+            if (z[u][e] == v) found = ((t0 + u) * WG + (int)threadIdx.x) * N + e;
+    }
+    return found;
+}
+
 // One batch of NU vectors per thread folded into the thread's running (m, S, t).
-template <int N, int NU, bool WITH_T>
+// With ARG, idx follows the smallest index that holds m: it moves only when the maximum strictly
+// increases, so earlier equal values keep it; t0 is the batch's first tile.
+template <int N, int NU, bool WITH_T, bool ARG = false>
 __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, float &S, float &t,
-                                           const Scale &sc)
+                                           const Scale &sc, int *idx = nullptr, int t0 = 0)
 {
     float mb = tree_max<N>(z[0]);
 #pragma unroll
     for (int u = 1; u < NU; ++u) mb = vmax(mb, tree_max<N>(z[u]));
     if (mb > m) {
+        if (ARG) *idx = first_equal<N, NU>(z, mb, t0);
         if (m != neg_inf()) {
             const float xd = scaled_diff(m, mb, sc);
             const float f = exp2_raw(xd);
@@ -223,8 +241,8 @@ __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, fl
     if (WITH_T) t += tb;
 }
 
-template <typename DT, int NU, bool WITH_T>
-__device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, float &S, float &t,
+template <typename DT, int NU, bool WITH_T, bool ARG>
+__device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, float &S, float &t, int &idx,
                                             const Scale &sc)
 {
     constexpr int N = VecOf<DT>::N;
@@ -234,14 +252,14 @@ __device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, flo
     float z[NU][N];
 #pragma unroll
     for (int u = 0; u < NU; ++u) unpack(raw[u], z[u]);
-    accumulate<N, NU, WITH_T>(z, m, S, t, sc);
+    accumulate<N, NU, WITH_T, ARG>(z, m, S, t, sc, &idx, t0);
 }
 
 // Workgroup combination of the per-thread (m, S, t): maximum first, then every thread
 // rescales to it and the sums are added in fp64.  Result valid in thread 0.
-template <bool WITH_T>
+template <bool WITH_T, bool ARG = false>
 __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const Scale &sc,
-                                              double *lds /* >= 2 * NWAVE doubles */)
+                                              double *lds /* >= 2 * NWAVE doubles */, int idx = -1)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     float *ldsf = reinterpret_cast<float *>(lds);
@@ -269,7 +287,7 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
     __syncthreads();
     Partial p;
     p.m = mg;
-    p.pad = 0.f;
+    p.idx = -1;
     p.S = 0.0;
     p.t = 0.0;
     if (tid == 0) {
@@ -279,6 +297,18 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
             p.t += lds[NWAVE + w];
         }
     }
+    if (ARG) {      // smallest index among the threads that hold the workgroup maximum
+        const int cand = (m == mg && idx >= 0) ? idx : 0x7FFFFFFF;
+        const int wmin = -wave_reduce(-cand, OpMax{});
+        __syncthreads();
+        int *ldsi = reinterpret_cast<int *>(lds);
+        if (lane == 0) ldsi[wave] = wmin;
+        __syncthreads();
+        int best = ldsi[0];
+#pragma unroll
+        for (int w = 1; w < NWAVE; ++w) best = min(best, ldsi[w]);
+        p.idx = best == 0x7FFFFFFF ? -1 : best;
+    }
     return p;
 }
 
@@ -287,25 +317,94 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
 // barrier; the workgroup combines at the end.  Tiles that lie wholly inside the row are read
 // in unchecked batches of 8/4/2/1 vectors per thread; only the row's last tile can be
 // partial and is read with bounds checks.  Result valid in thread 0.
-template <typename DT, bool WITH_T>
+template <typename DT, bool WITH_T, bool ARG = false>
 __device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int te, const Scale &sc,
                                                double *lds /* >= 2 * NWAVE doubles */)
 {
     constexpr int N = VecOf<DT>::N;
     const int tid = threadIdx.x;
     float m = neg_inf(), S = 0.f, t = 0.f;
+    int idx = -1;
     const int fe = min(te, V / (WG * N));      // end of the tiles that are wholly inside the row
     int t0 = tb;
-    for (; t0 + 8 <= fe; t0 += 8) stats_batch<DT, 8, WITH_T>(row, t0, m, S, t, sc);
-    if (t0 + 4 <= fe) { stats_batch<DT, 4, WITH_T>(row, t0, m, S, t, sc); t0 += 4; }
-    if (t0 + 2 <= fe) { stats_batch<DT, 2, WITH_T>(row, t0, m, S, t, sc); t0 += 2; }
-    if (t0 + 1 <= fe) { stats_batch<DT, 1, WITH_T>(row, t0, m, S, t, sc); t0 += 1; }
+    for (; t0 + 8 <= fe; t0 += 8) stats_batch<DT, 8, WITH_T, ARG>(row, t0, m, S, t, idx, sc);
+    if (t0 + 4 <= fe) { stats_batch<DT, 4, WITH_T, ARG>(row, t0, m, S, t, idx, sc); t0 += 4; }
+    if (t0 + 2 <= fe) { stats_batch<DT, 2, WITH_T, ARG>(row, t0, m, S, t, idx, sc); t0 += 2; }
+    if (t0 + 1 <= fe) { stats_batch<DT, 1, WITH_T, ARG>(row, t0, m, S, t, idx, sc); t0 += 1; }
     if (t0 < te) {
         float z[1][N];
         unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
-        accumulate<N, 1, WITH_T>(z, m, S, t, sc);
+        accumulate<N, 1, WITH_T, ARG>(z, m, S, t, sc, &idx, t0);
     }
-    return wg_combine<WITH_T>(m, S, t, sc, lds);
+    return wg_combine<WITH_T, ARG>(m, S, t, sc, lds, idx);
+}
+
+// ---- argmax only (greedy verification): no exponentials, a pure stream ---------------------
+//
+// A 64-bit key orders (value descending, index ascending): the fp32 value mapped to an unsigned
+// integer that sorts the same way, then 0xFFFFFFFF - index.  The largest key of a row is its
+// first maximum.
+__device__ __forceinline__ unsigned long long argmax_key(float v, int idx)
+{
+    unsigned u = __float_as_uint(v);
+    u = u == 0x80000000u ? 0u : u;                  // -0 and +0 compare equal: one key for both
+    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;
+    return ((unsigned long long)u << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)idx);
+}
+__device__ __forceinline__ int argmax_index(unsigned long long key) { return (int)(0xFFFFFFFFu - (unsigned)key); }
+
+template <typename DT, int NU>
+__device__ __forceinline__ void argmax_batch(const DT *row, int t0, float &m, int &idx)
+{
+    constexpr int N = VecOf<DT>::N;
+    typename RawOf<DT>::type raw[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) raw[u] = load_raw<DT>(row, (t0 + u) * WG + (int)threadIdx.x);
+    float z[NU][N];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) unpack(raw[u], z[u]);
+    float mb = tree_max<N>(z[0]);
+#pragma unroll
+    for (int u = 1; u < NU; ++u) mb = vmax(mb, tree_max<N>(z[u]));
+    if (mb > m || idx < 0) {
+        m = mb;
+        idx = first_equal<N, NU>(z, mb, t0);
+    }
+}
+
+// Key of the first maximum of tiles [tb, te) of a row; result in thread 0.
+template <typename DT>
+__device__ __forceinline__ unsigned long long slice_argmax(const DT *row, int V, int tb, int te,
+                                                           unsigned long long *lds /* >= NWAVE */)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    float m = neg_inf();
+    int idx = -1;
+    const int fe = min(te, V / (WG * N));
+    int t0 = tb;
+    for (; t0 + 8 <= fe; t0 += 8) argmax_batch<DT, 8>(row, t0, m, idx);
+    if (t0 + 4 <= fe) { argmax_batch<DT, 4>(row, t0, m, idx); t0 += 4; }
+    if (t0 + 2 <= fe) { argmax_batch<DT, 2>(row, t0, m, idx); t0 += 2; }
+    if (t0 + 1 <= fe) { argmax_batch<DT, 1>(row, t0, m, idx); t0 += 1; }
+    if (t0 < te) {
+        float z[1][N];
+        unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
+        const float mb = tree_max<N>(z[0]);
+        // elements past the end of the row read as -inf: only take the tile if it beats what we have
+        if (mb > m || (idx < 0 && t0 * WG * N + tid * N < V)) {
+            m = mb;
+            idx = first_equal<N, 1>(z, mb, t0);
+        }
+    }
+    unsigned long long key = idx >= 0 ? argmax_key(m, idx) : 0ull;
+    key = wave_reduce(key, OpMax{});
+    if (lane == 0) lds[wave] = key;
+    __syncthreads();
+    unsigned long long best = lds[0];
+#pragma unroll
+    for (int w = 1; w < NWAVE; ++w) best = lds[w] > best ? lds[w] : best;
+    return best;
 }
 
 // Merge of up to MAX_SLICES slice partials by one wave (lane s holds slice s; lanes >= ns

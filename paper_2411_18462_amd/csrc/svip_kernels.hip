@@ -2,10 +2,13 @@
 //
 // svip_draft_step  =  k_draft_stats    grid (slices, rows)       per-slice (m, S, t) of every active row
 //                     k_draft_finish   grid (rows)               merge, entropy, stop test, inverse CDF
+//   (greedy)          k_draft_stats<ARG> + k_draft_finish_greedy     token = first maximum, no search
 // svip_verify      =  k_verify_stats   grid (slices, stat rows)  per-slice (m, S) of every needed row
 //                     k_accept         grid (sequences), 1 wave  p/q test, ballot scan for the first rejection
 //                     k_resid_mass     grid (slices, sequences)  slice masses of the residual / bonus row
 //                     k_resid_finish   grid (sequences)          inverse CDF of the residual / bonus row
+// svip_verify_greedy = k_argmax        grid (slices, target rows) first maximum per slice, no exponentials
+//                     k_accept_greedy  grid (sequences), 1 wave  argmax p == x test, ballot, correction = argmax p
 //
 // The passes are bound by HBM reads of the logits; there is no dense contraction, hence no MFMA.
 // Kernels of one call are ordered by the stream only (no spinning, no device-side waits), and
@@ -218,8 +221,9 @@ __device__ __forceinline__ int pick_slice(double M, double target, double incl, 
 
 // ---- draft step -------------------------------------------------------------------------------
 
-// grid (rows * slices): statistics of slice s of row b.
-template <typename DT>
+// grid (rows * slices): statistics of slice s of row b.  ARG (greedy drafting) also records
+// the smallest index that holds the slice maximum.
+template <typename DT, bool ARG>
 __global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
 {
     __shared__ double lds[2 * NWAVE];
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
     if (a.stop_in && a.stop_in[b]) return;
     const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
     const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    const Partial p = slice_stats<DT, true>(row, a.geo.V, tb, te, a.sc, lds);
+    const Partial p = slice_stats<DT, true, ARG>(row, a.geo.V, tb, te, a.sc, lds);
     if (threadIdx.x == 0) a.part[(size_t)b * a.geo.ns + s] = p;
 }
 
@@ -296,6 +300,117 @@ __global__ __launch_bounds__(WG) void k_draft_finish(DraftArgs a)
         const bool stop = (sqrt(H) > (double)a.h) || (a.step_j + 1 >= a.k_max);
         a.stop[b] = stop ? 1 : 0;
         if (a.draft_len) a.draft_len[b] = a.step_j + 1;
+    }
+}
+
+// grid (rows), one wave: greedy drafting.  Merge of the row's slices, entropy and stop test;
+// the token is the first maximum of the row (Algorithm 1 with argmax in place of the draw).
+__global__ __launch_bounds__(64) void k_draft_finish_greedy(DraftArgs a)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const long long o = (long long)b * a.io_stride;
+    const unsigned char stopped = a.stop_in ? a.stop_in[b] : (unsigned char)0;
+    Partial p;
+    p.m = neg_inf();
+    p.idx = -1;
+    p.S = 0.0;
+    p.t = 0.0;
+    if (lane < a.geo.ns) p = a.part[(size_t)b * a.geo.ns + lane];
+    if (stopped) {
+        if (lane == 0) {
+            a.token[o] = -1;
+            a.stop[b] = 1;
+        }
+        return;
+    }
+    const Merged mg = merge_lane(lane < a.geo.ns ? p.m : neg_inf(), p.S, p.t, a.sc);
+    const double S = wave_sum(mg.M);
+    const double tt = wave_sum(mg.tt);
+    // slices are in index order: the first slice that reaches the row maximum holds its first index
+    const unsigned long long at_max = __ballot(lane < a.geo.ns && p.m == mg.m && p.idx >= 0);
+    const int tok = at_max ? read_lane(p.idx, __ffsll((long long)at_max) - 1) : -1;
+    if (lane == 0) {
+        const double lnS = log(S);
+        double H = lnS - 0.6931471805599453 * tt / S;
+        H = H > 0.0 ? H : 0.0;
+        a.token[o] = tok;
+        if (a.entropy) a.entropy[o] = (float)H;
+        if (a.q_tok) a.q_tok[o] = (float)(1.0 / S);           // the maximum has weight exp2(0) = 1
+        a.lse[o] = (double)mg.m * a.sc.inv_T + lnS;
+        const bool stop = (sqrt(H) > (double)a.h) || (a.step_j + 1 >= a.k_max);
+        a.stop[b] = stop ? 1 : 0;
+        if (a.draft_len) a.draft_len[b] = a.step_j + 1;
+    }
+}
+
+// ---- greedy verification (Algorithms 3 and 5) ------------------------------------------------
+
+struct GreedyArgs {
+    const void *target;
+    long long seq_t, row_stride;
+    int B, k;
+    Geo geo;
+    const int *tokens;
+    const int *draft_len;
+    int *n_accepted;
+    int *next_token;
+    unsigned long long *keys;    // [B (k+1)][ns] first-maximum keys
+    unsigned *flags;
+};
+
+// grid (sequences * (k+1) * slices): first maximum of slice s of target row (b, j), j <= draft_len[b].
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_argmax(GreedyArgs a)
+{
+    __shared__ unsigned long long lds[NWAVE];
+    const int y = blockIdx.x / a.geo.ns, s = blockIdx.x - y * a.geo.ns;
+    const int b = y / (a.k + 1), j = y - b * (a.k + 1);
+    const int g = clamp_len(a.draft_len[b], a.k);
+    if (j > g) return;
+    const DT *row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
+    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const unsigned long long key = slice_argmax<DT>(row, a.geo.V, tb, te, lds);
+    if (threadIdx.x == 0) a.keys[(size_t)y * a.geo.ns + s] = key;
+}
+
+// grid (sequences), one wave: lane = position.  argmax of target row j from its slice keys;
+// position j < draft_len is accepted iff that argmax is the draft token; a ballot finds the first
+// failure r, and the correction (or, if none failed, the bonus token) is the argmax of row r.
+__global__ __launch_bounds__(64) void k_accept_greedy(GreedyArgs a)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int graw = a.draft_len[b];
+    const int g = clamp_len(graw, a.k);
+    if (graw != g && lane == 0) atomicOr(a.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
+    int r = -1, next = -1;
+    for (int j0 = 0; j0 <= g && r < 0; j0 += 64) {
+        const int j = j0 + lane;
+        int am = -1;
+        bool reject = false;
+        if (j <= g) {
+            const unsigned long long *kr = a.keys + ((size_t)b * (a.k + 1) + j) * a.geo.ns;
+            unsigned long long best = 0ull;
+            for (int s = 0; s < a.geo.ns; ++s) best = kr[s] > best ? kr[s] : best;
+            am = argmax_index(best);
+            if (j < g) {
+                const int x = a.tokens[(size_t)b * a.k + j];
+                if (x < 0 || x >= a.geo.V) atomicOr(a.flags, (unsigned)SVIP_FLAG_BAD_TOKEN);
+                reject = am != x;
+            }
+        }
+        const unsigned long long rej = __ballot(reject);
+        if (rej) {
+            const int first = __ffsll((long long)rej) - 1;
+            r = j0 + first;
+            next = read_lane(am, first);
+        } else if (g - j0 < 64) {
+            r = g;
+            next = read_lane(am, g - j0);
+        }
+    }
+    if (lane == 0) {
+        a.n_accepted[b] = r;
+        a.next_token[b] = next;
     }
 }
 
@@ -612,14 +727,14 @@ svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsign
     return hipStreamSynchronize(st) == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
 }
 
-svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
-                            float temperature, float h, int step_j, int k_max, const float *u_sample,
-                            const unsigned char *stop_in, int *token_out, float *entropy_out,
-                            float *q_tok_out, double *lse_out, unsigned char *stop_out,
-                            int *draft_len_out, long long io_stride, void *workspace,
-                            size_t workspace_bytes, void *hip_stream)
+static svip_status draft_step_impl(bool greedy, const void *draft_logits, svip_dtype dtype, int B, int V,
+                                   long long row_stride, float temperature, float h, int step_j, int k_max,
+                                   const float *u_sample, const unsigned char *stop_in, int *token_out,
+                                   float *entropy_out, float *q_tok_out, double *lse_out,
+                                   unsigned char *stop_out, int *draft_len_out, long long io_stride,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!draft_logits || !u_sample || !token_out || !lse_out || !stop_out) return SVIP_ERR_NULL;
+    if (!draft_logits || (!greedy && !u_sample) || !token_out || !lse_out || !stop_out) return SVIP_ERR_NULL;
     if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
     if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || step_j < 0 ||
         step_j >= k_max || io_stride < 1 || row_stride < V)
@@ -653,13 +768,81 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
     a.part = w.part;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 grid((unsigned)a.geo.ns * (unsigned)B);
-    if (dtype == SVIP_BF16) {
-        hipLaunchKernelGGL(k_draft_stats<bf16>, grid, dim3(WG), 0, st, a);
+    if (greedy) {
+        if (dtype == SVIP_BF16) hipLaunchKernelGGL((k_draft_stats<bf16, true>), grid, dim3(WG), 0, st, a);
+        else hipLaunchKernelGGL((k_draft_stats<float, true>), grid, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_draft_finish_greedy, dim3(B), dim3(64), 0, st, a);
+    } else if (dtype == SVIP_BF16) {
+        hipLaunchKernelGGL((k_draft_stats<bf16, false>), grid, dim3(WG), 0, st, a);
         hipLaunchKernelGGL(k_draft_finish<bf16>, dim3(B), dim3(WG), 0, st, a);
     } else {
-        hipLaunchKernelGGL(k_draft_stats<float>, grid, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL((k_draft_stats<float, false>), grid, dim3(WG), 0, st, a);
         hipLaunchKernelGGL(k_draft_finish<float>, dim3(B), dim3(WG), 0, st, a);
     }
+    return check_launch();
+}
+
+svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+                            float temperature, float h, int step_j, int k_max, const float *u_sample,
+                            const unsigned char *stop_in, int *token_out, float *entropy_out,
+                            float *q_tok_out, double *lse_out, unsigned char *stop_out,
+                            int *draft_len_out, long long io_stride, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    return draft_step_impl(false, draft_logits, dtype, B, V, row_stride, temperature, h, step_j, k_max, u_sample,
+                           stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out, draft_len_out,
+                           io_stride, workspace, workspace_bytes, hip_stream);
+}
+
+svip_status svip_draft_step_greedy(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+                                   float temperature, float h, int step_j, int k_max,
+                                   const unsigned char *stop_in, int *token_out, float *entropy_out,
+                                   float *q_tok_out, double *lse_out, unsigned char *stop_out,
+                                   int *draft_len_out, long long io_stride, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream)
+{
+    return draft_step_impl(true, draft_logits, dtype, B, V, row_stride, temperature, h, step_j, k_max, nullptr,
+                           stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out, draft_len_out,
+                           io_stride, workspace, workspace_bytes, hip_stream);
+}
+
+svip_status svip_verify_greedy(const void *target_logits, svip_dtype dtype, int B, int k_max, int V,
+                               long long seq_stride_t, long long row_stride, const int *draft_tokens,
+                               const int *draft_len, int *n_accepted_out, int *next_token_out,
+                               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!target_logits || !draft_tokens || !draft_len || !n_accepted_out || !next_token_out) return SVIP_ERR_NULL;
+    if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || row_stride < V ||
+        seq_stride_t < (long long)k_max * row_stride + V)
+        return SVIP_ERR_SHAPE;
+    const long long rows = (long long)B * (k_max + 1);
+    if (rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;
+    const int vec = dtype == SVIP_BF16 ? 8 : 4;
+    if (!aligned16(target_logits) || row_stride % vec != 0 || seq_stride_t % vec != 0) return SVIP_ERR_ALIGN;
+    GreedyArgs a;
+    a.geo = make_geo(V, vec, rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    const size_t need = HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) +
+                        (size_t)rows * a.geo.ns * sizeof(unsigned long long);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+        return SVIP_ERR_WORKSPACE;
+    const Workspace w = carve(workspace, B);
+    a.target = target_logits;
+    a.seq_t = seq_stride_t;
+    a.row_stride = row_stride;
+    a.B = B;
+    a.k = k_max;
+    a.tokens = draft_tokens;
+    a.draft_len = draft_len;
+    a.n_accepted = n_accepted_out;
+    a.next_token = next_token_out;
+    a.keys = reinterpret_cast<unsigned long long *>(w.part);
+    a.flags = w.flags;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid((unsigned)(rows * a.geo.ns));
+    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_argmax<bf16>, grid, dim3(WG), 0, st, a);
+    else hipLaunchKernelGGL(k_argmax<float>, grid, dim3(WG), 0, st, a);
+    hipLaunchKernelGGL(k_accept_greedy, dim3(B), dim3(64), 0, st, a);
     return check_launch();
 }
 

@@ -32,7 +32,21 @@ __device__ __forceinline__ double dpp_mov(double v)
     return __hiloint2double(hi, lo);
 }
 
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_mov(unsigned long long v)
+{
+    const unsigned lo = (unsigned)dpp_mov<CTRL>((int)(unsigned)v);
+    const unsigned hi = (unsigned)dpp_mov<CTRL>((int)(unsigned)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+
 __device__ __forceinline__ int read_lane(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ unsigned long long read_lane(unsigned long long v, int lane)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), lane);
+    return ((unsigned long long)hi << 32) | lo;
+}
 __device__ __forceinline__ float read_lane(float v, int lane)
 {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
@@ -50,6 +64,10 @@ struct OpSum {
 struct OpMax {
     __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); }
     __device__ __forceinline__ int operator()(int a, int b) const { return a > b ? a : b; }
+    __device__ __forceinline__ unsigned long long operator()(unsigned long long a, unsigned long long b) const
+    {
+        return a > b ? a : b;
+    }
 };
 
 template <typename T, typename Op>
