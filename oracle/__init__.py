@@ -66,6 +66,9 @@ def _load():
         lib.oracle_verify_greedy.argtypes = [_D, ctypes.c_long, ctypes.c_long, ctypes.c_long, _L, _L, _L, _L]
         lib.oracle_pair_stats.restype = None
         lib.oracle_pair_stats.argtypes = [_D, _D, ctypes.c_long, ctypes.c_double, _D]
+        lib.oracle_diagnostics.restype = None
+        lib.oracle_diagnostics.argtypes = [_D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
+                                           _L, ctypes.c_double, _D]
         lib.oracle_sd_position_trials.restype = None
         lib.oracle_sd_position_trials.argtypes = [
             _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_ulonglong, ctypes.c_int, _L, _L]
@@ -224,6 +227,24 @@ def pair_stats(zp_row, zq_row, T: float = 1.0) -> dict:
     out = np.empty(5)
     _load().oracle_pair_stats(_p(zp_row, _D), _p(zq_row, _D), zp_row.size, float(T), _p(out, _D))
     return dict(beta=out[0], kl=out[1], hqp=out[2], hq=out[3], tvd=out[4])
+
+
+DIAG_FIELDS = ("beta", "kl", "hqp", "hq", "bound_oracle", "bound_bh", "bound_approx", "ratio")
+
+
+def diagnostics(zp, zq, T, gamma, c) -> np.ndarray:
+    """[B, k, 8] per-position diagnostics (DIAG_FIELDS order), NaN where j >= gamma[b];
+    zp[B, k+1, V], zq[B, k, V]; see oracle_diagnostics in svip_oracle.c."""
+    zp = _f64(zp)
+    zq = _f64(zq)
+    B, kp1, V = zp.shape
+    k = kp1 - 1
+    assert zq.shape == (B, k, V)
+    gamma = _i64(gamma).ravel()
+    assert gamma.size == B and (gamma >= 0).all() and (gamma <= k).all()
+    out = np.empty((B, k, 8))
+    _load().oracle_diagnostics(_p(zp, _D), _p(zq, _D), B, k, V, float(T), _p(gamma, _L), float(c), _p(out, _D))
+    return out
 
 
 def sd_position_trials(p, q, N: int, seed: int, resid_sign: int = +1):

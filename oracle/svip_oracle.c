@@ -298,6 +298,44 @@ void oracle_pair_stats(const double *zp_row, const double *zq_row, long V, doubl
     free(p); free(q);
 }
 
+/*
+ * Per-position diagnostics of Section 2.2 and Appendix B for one round.
+ * zp [B][k+1][V] target logits, zq [B][k][V] draft logits, gamma[b] drafted positions.
+ * out [B][k][8]; entries of positions j >= gamma[b] are NaN.
+ *   0 beta                       Eq. beta
+ *   1 KL(q||p)                   Eq. pinsker
+ *   2 H_{q,p}                    Eq. beta-bound
+ *   3 H_q
+ *   4 oracle bound        1 - sqrt(KL / 2)            Eq. pinsker / Eq. beta-bound
+ *   5 Bretagnolle-Huber   1 - sqrt(1 - exp(-KL))      Appendix B
+ *   6 approximation bound 1 - sqrt(c H_q)             Eq. appro_bound, c the constant standing in
+ *                                                     for (gamma - 1) / 2
+ *   7 ratio H_{q,p} / H_q        the paper's gamma (NaN when H_q = 0)
+ */
+void oracle_diagnostics(const double *zp, const double *zq, long B, long k, long V, double T,
+                        const long *gamma, double c, double *out)
+{
+    for (long b = 0; b < B; ++b)
+        for (long j = 0; j < k; ++j) {
+            double *o = out + (b * k + j) * 8;
+            if (j >= gamma[b]) {
+                for (int i = 0; i < 8; ++i) o[i] = NAN;
+                continue;
+            }
+            double st[5];
+            oracle_pair_stats(zp + (b * (k + 1) + j) * V, zq + (b * k + j) * V, V, T, st);
+            const double beta = st[0], kl = st[1], hqp = st[2], hq = st[3];
+            o[0] = beta;
+            o[1] = kl;
+            o[2] = hqp;
+            o[3] = hq;
+            o[4] = 1.0 - sqrt(0.5 * kl);
+            o[5] = 1.0 - sqrt(1.0 - exp(-kl));
+            o[6] = 1.0 - sqrt(c * hq);
+            o[7] = hq > 0.0 ? hqp / hq : NAN;
+        }
+}
+
 /* ---- brute-force law of one speculative position (Algorithms 2 + 4) ------------ */
 
 /*

@@ -426,3 +426,63 @@ def test_greedy_identical_models_accept_everything():
     nacc, nxt = oracle.verify_greedy(z, tok, np.array([6, 4, 0, 1]))
     assert np.array_equal(nacc, [6, 4, 0, 1])
     assert np.array_equal(nxt, [np.argmax(z[b, g]) for b, g in enumerate([6, 4, 0, 1])])
+
+
+# ---------------------------------------------------------------- diagnostics (Section 2.2, Appendix B)
+
+def test_diagnostics_two_point_closed_form():
+    """p = (a, 1-a), q = (b, 1-b): every quantity has an elementary closed form."""
+    a, b, c = 0.5, 0.25, 0.2
+    zp = np.log(np.array([[[a, 1 - a], [a, 1 - a]]]))          # [1, k+1 = 2, V = 2]
+    zq = np.log(np.array([[[b, 1 - b]]]))                      # [1, k = 1, 2]
+    d = oracle.diagnostics(zp, zq, 1.0, [1], c)[0, 0]
+    beta = 1 - abs(a - b)                                       # min(a,b) + min(1-a,1-b)
+    hq = -(b * math.log(b) + (1 - b) * math.log(1 - b))
+    hqp = -(b * math.log(a) + (1 - b) * math.log(1 - a))
+    kl = b * math.log(b / a) + (1 - b) * math.log((1 - b) / (1 - a))
+    want = [beta, kl, hqp, hq, 1 - math.sqrt(kl / 2), 1 - math.sqrt(1 - math.exp(-kl)),
+            1 - math.sqrt(c * hq), hqp / hq]
+    assert np.allclose(d, want, rtol=0, atol=1e-14)
+    # digits worked by hand for this pair: beta = 3/4, KL = 0.75 ln 1.5 - 0.25 ln 2
+    assert abs(d[0] - 0.75) < 1e-15 and abs(d[1] - 0.13081203594113694) < 1e-15
+    assert abs(d[4] - 0.7442538) < 1e-6 and abs(d[5] - 0.6498333) < 1e-6
+
+
+def test_diagnostics_identities_and_signs():
+    rng = _rng(21)
+    B, k = 3, 4
+    for trial in range(30):
+        V = int(rng.integers(2, 50))
+        zq = rng.normal(0, rng.uniform(0.2, 5), (B, k, V))
+        zp = rng.normal(0, rng.uniform(0.2, 5), (B, k + 1, V))
+        c = float(rng.uniform(0.05, 1.0))
+        g = rng.integers(0, k + 1, B)
+        d = oracle.diagnostics(zp, zq, 1.0, g, c)
+        for b in range(B):
+            assert np.isnan(d[b, g[b]:]).all() and np.isfinite(d[b, :g[b]]).all()
+            for j in range(g[b]):
+                beta, kl, hqp, hq, bo, bh, ba, ratio = d[b, j]
+                assert beta >= bo - 1e-12 and beta >= bh - 1e-12          # both are lower bounds
+                assert bh > 0.0                                            # Appendix B: always positive
+                # the bound written with gamma = H_{q,p}/H_q is the oracle bound again
+                assert abs(bo - (1 - math.sqrt(0.5 * (ratio - 1) * hq))) < 1e-9
+                # the approximation is conservative exactly when c >= (gamma - 1) / 2
+                assert (ba <= bo + 1e-12) == (c >= 0.5 * (ratio - 1) - 1e-12)
+    # a far-apart pair: KL > 2 makes the Pinsker form negative while Bretagnolle-Huber stays positive
+    zp = np.array([[[8.0, 0.0], [0.0, 0.0]]])
+    zq = np.array([[[0.0, 8.0]]])
+    d = oracle.diagnostics(zp, zq, 1.0, [1], 0.3)[0, 0]
+    assert d[1] > 2 and d[4] < 0 < d[5] <= d[0]
+
+
+def test_diagnostics_uniform_and_temperature():
+    V, k = 64, 2
+    z = np.zeros((1, k + 1, V))
+    d = oracle.diagnostics(z, z[:, :k], 1.0, [k], 0.1)
+    lnV = math.log(V)
+    assert np.allclose(d[0, :, :6], [1.0, 0.0, lnV, lnV, 1.0, 1.0], atol=1e-12)
+    assert np.allclose(d[0, :, 6], 1 - math.sqrt(0.1 * lnV)) and np.allclose(d[0, :, 7], 1.0)
+    rng = _rng(22)
+    zp, zq = rng.normal(0, 3, (2, k + 1, V)), rng.normal(0, 3, (2, k, V))
+    assert np.allclose(oracle.diagnostics(zp, zq, 2.0, [k, 1], 0.2), oracle.diagnostics(zp / 2, zq / 2, 1.0, [k, 1], 0.2),
+                       rtol=1e-12, equal_nan=True)
