@@ -297,6 +297,22 @@ def main():
             "mean_accepted": float(sets[0].n_accepted.float().mean()),
         }
 
+        # acceptance diagnostics of every drafted position (two passes over the target row, one over
+        # the draft row whose logsumexp the draft step already produced)
+        stats = torch.empty(B, k, svip.PAIR_NSTAT, dtype=torch.float32, device=dev)
+        for s in sets:
+            s.draft_round(H_FULL)          # eager: every position drafted, logsumexps of all k rows
+        torch.cuda.synchronize()
+        assert int(sets[0].draft_len.min()) == k
+        t_d = phase(lambda s: svip.pair_stats(s.target, s.draft, temperature=w.T, draft_len=s.draft_len, c=0.15,
+                                              stats_out=stats, workspace=s.ws, draft_lse=s.lse), steps_h)
+        extra["diagnostics"] = {
+            "us": 1e6 * t_d,
+            "GBps": 3 * draft_bytes / t_d / 1e9,
+            "mean_beta": float(stats[..., 0].mean()),
+            "mean_oracle_bound": float(stats[..., 4].mean()),
+        }
+
     out = {
         "metric": "draft+verify rows/sec and achieved HBM GB/s (% peak) at V=128K bf16, B=64",
         "value": rows_per_step * a.steps / dt,

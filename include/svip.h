@@ -14,6 +14,7 @@
  *                     rejected, the bonus token drawn from the next target row
  *                                                       (Algorithm 1, verification loop;
  *                                                        Algorithm 2 Verify, Algorithm 4 Correct)
+ *   svip_pair_stats  acceptance diagnostics per drafted position (Section 2.2, Appendix B)
  *   svip_draft_step_greedy, svip_verify_greedy    the same two steps under greedy decoding
  *                                                       (Algorithm 3 Verify, Algorithm 5 Correct)
  *
@@ -188,6 +189,38 @@ svip_status svip_verify_greedy(
     const int *draft_len,            /* device [B] */
     int *n_accepted_out,             /* device [B] */
     int *next_token_out,             /* device [B] */
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Per-position diagnostics of the acceptance analysis (Section 2.2, Eq. beta, Eq. tvd,
+ * Eq. pinsker, Eq. beta-bound, Eq. appro_bound; Appendix B).  For each sequence b and each
+ * drafted position j < draft_len[b], with p = softmax(target_logits[b, j] / T) and
+ * q = softmax(draft_logits[b, j] / T), stats_out[b, j, :] receives
+ *   [0] beta = sum_x min(p(x), q(x))          expected acceptance probability (= 1 - TVD)
+ *   [1] KL(q || p)                            nats
+ *   [2] H_{q,p} = -sum_x q(x) ln p(x)         cross entropy, nats (= [3] + [1])
+ *   [3] H_q                                   nats
+ *   [4] 1 - sqrt(KL / 2)                      the oracle bound
+ *   [5] 1 - sqrt(1 - exp(-KL))                the Bretagnolle-Huber bound
+ *   [6] 1 - sqrt(c H_q)                       the approximation bound with constant c
+ *   [7] H_{q,p} / H_q                         the ratio the paper calls gamma (NaN if H_q = 0)
+ * and NaN in all SVIP_PAIR_NSTAT entries of positions j >= draft_len[b].  Target row draft_len[b]
+ * (the bonus row) is not read.  draft_lse as in svip_verify (NULL: recomputed here).  Two passes
+ * over both rows of every drafted position: 4 V elements of traffic per position (3 V when
+ * draft_lse is given).  A logit of -inf counts as probability 2^-200 in the sums, so a token
+ * the target masks but the draft can emit gives a large finite KL rather than +inf.
+ */
+#define SVIP_PAIR_NSTAT 8
+svip_status svip_pair_stats(
+    const void *target_logits,       /* device, row (b, j) at b * seq_stride_t + j * row_stride, j < k_max */
+    const void *draft_logits,        /* device, row (b, j) at b * seq_stride_d + j * row_stride, j < k_max */
+    svip_dtype dtype, int B, int k_max, int V,
+    long long seq_stride_t, long long seq_stride_d, long long row_stride,
+    float temperature,
+    const int *draft_len,            /* device [B] */
+    const double *draft_lse,         /* device [B, k_max] natural-log logsumexp of draft rows, or NULL */
+    float c,                         /* >= 0 */
+    float *stats_out,                /* device [B, k_max, SVIP_PAIR_NSTAT] */
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*

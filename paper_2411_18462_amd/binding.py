@@ -18,7 +18,7 @@ _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 # every symbol include/svip.h declares
 EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_reset",
            "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_draft_step_greedy",
-           "svip_verify_greedy", "svip_profile_begin", "svip_profile_end")
+           "svip_verify_greedy", "svip_pair_stats", "svip_profile_begin", "svip_profile_end")
 
 
 class SvipError(RuntimeError):
@@ -54,6 +54,8 @@ def load():
     lib.svip_draft_step_greedy.argtypes = [vp, i, i, i, ll, f, f, i, i, vp, vp, vp, vp, vp, vp, vp, ll, vp, sz, vp]
     lib.svip_verify_greedy.restype = i
     lib.svip_verify_greedy.argtypes = [vp, i, i, i, i, ll, ll, vp, vp, vp, vp, vp, sz, vp]
+    lib.svip_pair_stats.restype = i
+    lib.svip_pair_stats.argtypes = [vp, vp, i, i, i, i, ll, ll, ll, f, vp, vp, f, vp, vp, sz, vp]
     lib.svip_profile_begin.restype = i
     lib.svip_profile_begin.argtypes = [i]
     lib.svip_profile_end.restype = i
@@ -169,6 +171,40 @@ def verify_greedy(target_logits, *, draft_tokens, draft_len, n_accepted_out, nex
         _ptr(draft_tokens, torch.int32, "draft_tokens"), _ptr(draft_len, torch.int32, "draft_len"),
         _ptr(n_accepted_out, torch.int32, "n_accepted_out"), _ptr(next_token_out, torch.int32, "next_token_out"),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+PAIR_NSTAT = 8
+PAIR_FIELDS = ("beta", "kl", "hqp", "hq", "bound_oracle", "bound_bh", "bound_approx", "ratio")
+
+
+def pair_stats(target_logits, draft_logits, *, temperature, draft_len, c, stats_out, workspace,
+               draft_lse=None, stream=None):
+    """svip_pair_stats.  target_logits [B, >=k, V] (rows j < k are used), draft_logits [B, k, V],
+    stats_out contiguous float32 [B, k, PAIR_NSTAT]."""
+    if target_logits.dim() != 3 or draft_logits.dim() != 3:
+        raise ValueError("logits must be [B, rows, V]")
+    B, k, V = draft_logits.shape
+    if target_logits.shape[0] != B or target_logits.shape[1] < k or target_logits.shape[2] != V:
+        raise ValueError("target_logits must be [B, >=k, V]")
+    if target_logits.dtype != draft_logits.dtype or draft_logits.dtype not in _DTYPES:
+        raise SvipError(3, "logits must both be float32 or both bfloat16")
+    if target_logits.stride(2) != 1 or draft_logits.stride(2) != 1 or target_logits.stride(1) != draft_logits.stride(1):
+        raise ValueError("logits need unit stride along V and a common row stride")
+    row_stride = draft_logits.stride(1) if k > 1 else max(V, draft_logits.stride(1))
+    seq_t = target_logits.stride(0) if B > 1 else target_logits.shape[1] * row_stride
+    seq_d = draft_logits.stride(0) if B > 1 else k * row_stride
+    if tuple(stats_out.shape) != (B, k, PAIR_NSTAT) or not stats_out.is_contiguous():
+        raise ValueError(f"stats_out must be contiguous [{B}, {k}, {PAIR_NSTAT}]")
+    if tuple(draft_len.shape) != (B,) or not draft_len.is_contiguous():
+        raise ValueError(f"draft_len must be contiguous [{B}]")
+    if draft_lse is not None and (tuple(draft_lse.shape) != (B, k) or not draft_lse.is_contiguous()):
+        raise ValueError(f"draft_lse must be contiguous [{B}, {k}]")
+    _check(load().svip_pair_stats(
+        _ptr(target_logits, None, "target_logits"), _ptr(draft_logits, None, "draft_logits"),
+        _DTYPES[draft_logits.dtype], B, k, V, seq_t, seq_d, row_stride, float(temperature),
+        _ptr(draft_len, torch.int32, "draft_len"), _ptr(draft_lse, torch.float64, "draft_lse"), float(c),
+        _ptr(stats_out, torch.float32, "stats_out"), _ptr(workspace, torch.uint8, "workspace"),
+        workspace.numel(), _stream(stream)))
 
 
 def verify(target_logits, draft_logits, *, temperature, draft_tokens, draft_len, u_accept,

@@ -161,11 +161,13 @@ __device__ __forceinline__ float scaled_diff(float z, float m, const Scale &sc)
 // Probability-like weight exp2(z * c - L), L given as fp32 hi + lo.
 struct ExpRef {
     float c_hi, c_lo, L_hi, L_lo;
-    __device__ __forceinline__ float operator()(float z) const
+    // log2 of the weight, floored (see X_FLOOR)
+    __device__ __forceinline__ float arg(float z) const
     {
         const float x = fmaf(z, c_hi, -L_hi) + fmaf(z, c_lo, -L_lo);
-        return exp2_raw(vmax(x, X_FLOOR));
+        return vmax(x, X_FLOOR);
     }
+    __device__ __forceinline__ float operator()(float z) const { return exp2_raw(arg(z)); }
 };
 __device__ __forceinline__ ExpRef make_exp_ref(const Scale &sc, double L)
 {

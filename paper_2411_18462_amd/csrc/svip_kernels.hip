@@ -10,6 +10,10 @@
 // svip_verify_greedy = k_argmax        grid (slices, target rows) first maximum per slice, no exponentials
 //                     k_accept_greedy  grid (sequences), 1 wave  argmax p == x test, ballot, correction = argmax p
 //
+// svip_pair_stats  =  k_verify_stats   (rows j < draft_len of both models), k_pair_L (logsumexps),
+//                     k_pair_sums      grid (slices, positions)  sum min(p,q), sum q log(q/p), sum q log q
+//                     k_pair_finish    one thread per position   beta, KL, cross entropy, the bounds
+//
 // The passes are bound by HBM reads of the logits; there is no dense contraction, hence no MFMA.
 // Kernels of one call are ordered by the stream only (no spinning, no device-side waits), and
 // each small kernel issues all of its independent loads before the first dependent one, because
@@ -89,6 +93,7 @@ struct VerifyArgs {
     long long seq_t, seq_d, row_stride;
     int B, k;
     int kd;        // draft rows per sequence in the statistics pass: k if the draft logsumexps are recomputed, else 0
+    int bonus;     // 1: the statistics pass also covers target row draft_len (verification), 0: rows j < draft_len only
     Geo geo;       // slicing of the statistics pass
     Geo geo_s;     // slicing of the sampling pass (slices of at most LOCATE_UNROLL tiles when possible)
     Scale sc;
@@ -439,7 +444,7 @@ __global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
         row = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)jj * a.row_stride;
     } else {
         const int j = jj - a.kd;
-        if (j > g) return;
+        if (j >= g + a.bonus) return;
         row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
     }
     const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
@@ -618,6 +623,150 @@ __global__ __launch_bounds__(WG) void k_resid_finish(VerifyArgs a)
     if (tid == 0) a.next_token[b] = tok;
 }
 
+// ---- per-position diagnostics (Section 2.2, Appendix B) ----------------------------------------
+
+struct PairArgs {
+    VerifyArgs v;        // statistics pass: rows j < draft_len of both models (bonus = 0)
+    Geo geo2;            // slicing of the second pass
+    float c;             // constant of the approximation bound
+    double *L;           // [B k][2] logsumexp * log2(e) of target and draft row
+    double *sums;        // [B k][ns2][3] slice sums
+    float *out;          // [B k][SVIP_PAIR_NSTAT]
+};
+
+// One thread per position (b, j < draft_len): logsumexps of its two rows from the slice statistics.
+__global__ __launch_bounds__(64) void k_pair_L(PairArgs a)
+{
+    const long long y = (long long)blockIdx.x * 64 + threadIdx.x;
+    if (y >= (long long)a.v.B * a.v.k) return;
+    const int b = (int)(y / a.v.k), j = (int)(y - (long long)b * a.v.k);
+    const int graw = a.v.draft_len[b];
+    const int g = clamp_len(graw, a.v.k);
+    if (graw != g && j == 0) atomicOr(a.v.ws.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
+    if (j >= g) return;
+    a.L[2 * y] = row_L(a.v.ws.part, stat_row(a.v, b, a.v.kd + j), a.v.geo.ns, a.v.sc);
+    a.L[2 * y + 1] = a.v.draft_lse ? a.v.draft_lse[y] * 1.4426950408889634
+                                   : row_L(a.v.ws.part, stat_row(a.v, b, j), a.v.geo.ns, a.v.sc);
+}
+
+// One batch of NU vector pairs per thread: with p = exp2(xp), q = exp2(xq) the normalised
+// probabilities, adds  sum min(p, q),  sum q (xq - xp)  and  sum q xq  (log2 units).
+template <typename DT, int NU, bool CHECKED>
+__device__ __forceinline__ void pair_batch(const DT *prow, const DT *qrow, int V, int t0, const ExpRef &ep,
+                                           const ExpRef &eq, float &beta, float &kl, float &hq)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x;
+    typename RawOf<DT>::type rp[NU], rq[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        const int vi = (t0 + u) * WG + tid;
+        rp[u] = CHECKED ? load_raw_checked(prow, vi, V) : load_raw<DT>(prow, vi);
+        rq[u] = CHECKED ? load_raw_checked(qrow, vi, V) : load_raw<DT>(qrow, vi);
+    }
+    float bb = 0.f, kb = 0.f, hb = 0.f;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        float zp[N], zq[N], mn[N], dk[N], dh[N];
+        unpack(rp[u], zp);
+        unpack(rq[u], zq);
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            const float xp = ep.arg(zp[e]), xq = eq.arg(zq[e]);
+            const float pe = exp2_raw(xp), qe = exp2_raw(xq);
+            mn[e] = fminf(pe, qe);
+            dk[e] = qe * (xq - xp);
+            dh[e] = qe * xq;
+        }
+        bb += tree_sum<N>(mn);
+        kb += tree_sum<N>(dk);
+        hb += tree_sum<N>(dh);
+    }
+    beta += bb;
+    kl += kb;
+    hq += hb;
+}
+
+// grid (positions * slices): the three sums over slice s of the rows of position (b, j).
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_pair_sums(PairArgs a)
+{
+    constexpr int N = VecOf<DT>::N;
+    __shared__ double lds[3 * NWAVE];
+    const int ns = a.geo2.ns;
+    const long long y = blockIdx.x / ns;
+    const int s = (int)(blockIdx.x - y * ns), tid = threadIdx.x;
+    const int b = (int)(y / a.v.k), j = (int)(y - (long long)b * a.v.k);
+    if (j >= clamp_len(a.v.draft_len[b], a.v.k)) return;
+    const DT *prow = static_cast<const DT *>(a.v.target) + (long long)b * a.v.seq_t + (long long)j * a.v.row_stride;
+    const DT *qrow = static_cast<const DT *>(a.v.draft) + (long long)b * a.v.seq_d + (long long)j * a.v.row_stride;
+    const ExpRef ep = make_exp_ref(a.v.sc, a.L[2 * y]), eq = make_exp_ref(a.v.sc, a.L[2 * y + 1]);
+    const int V = a.geo2.V, tb = s * a.geo2.tps, te = min(tb + a.geo2.tps, a.geo2.ntiles);
+    const int fe = min(te, V / (WG * N));
+    float beta = 0.f, kl = 0.f, hq = 0.f;
+    int t0 = tb;
+    for (; t0 + 4 <= fe; t0 += 4) pair_batch<DT, 4, false>(prow, qrow, V, t0, ep, eq, beta, kl, hq);
+    if (t0 + 2 <= fe) { pair_batch<DT, 2, false>(prow, qrow, V, t0, ep, eq, beta, kl, hq); t0 += 2; }
+    if (t0 + 1 <= fe) { pair_batch<DT, 1, false>(prow, qrow, V, t0, ep, eq, beta, kl, hq); t0 += 1; }
+    if (t0 < te) pair_batch<DT, 1, true>(prow, qrow, V, t0, ep, eq, beta, kl, hq);
+    const double bd = wave_sum((double)beta), kd = wave_sum((double)kl), hd = wave_sum((double)hq);
+    const int wave = tid >> 6, lane = tid & 63;
+    if (lane == 0) {
+        lds[wave] = bd;
+        lds[NWAVE + wave] = kd;
+        lds[2 * NWAVE + wave] = hd;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double o[3] = {0.0, 0.0, 0.0};
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) {
+            o[0] += lds[w];
+            o[1] += lds[NWAVE + w];
+            o[2] += lds[2 * NWAVE + w];
+        }
+        double *dst = a.sums + ((size_t)y * ns + s) * 3;
+        dst[0] = o[0];
+        dst[1] = o[1];
+        dst[2] = o[2];
+    }
+}
+
+// One thread per position: slice sums added in slice order, then the bounds.
+__global__ __launch_bounds__(64) void k_pair_finish(PairArgs a)
+{
+    const long long y = (long long)blockIdx.x * 64 + threadIdx.x;
+    if (y >= (long long)a.v.B * a.v.k) return;
+    const int b = (int)(y / a.v.k), j = (int)(y - (long long)b * a.v.k);
+    float *o = a.out + y * SVIP_PAIR_NSTAT;
+    if (j >= clamp_len(a.v.draft_len[b], a.v.k)) {
+#pragma unroll
+        for (int i = 0; i < SVIP_PAIR_NSTAT; ++i) o[i] = __int_as_float(0x7FC00000);
+        return;
+    }
+    double beta = 0.0, A = 0.0, Bq = 0.0;
+    for (int s = 0; s < a.geo2.ns; ++s) {
+        const double *src = a.sums + ((size_t)y * a.geo2.ns + s) * 3;
+        beta += src[0];
+        A += src[1];
+        Bq += src[2];
+    }
+    constexpr double LN2 = 0.6931471805599453;
+    double kl = LN2 * A, hq = -LN2 * Bq;
+    kl = kl > 0.0 ? kl : 0.0;             // both are non-negative; rounding can leave a tiny negative sum
+    hq = hq > 0.0 ? hq : 0.0;
+    beta = beta < 1.0 ? beta : 1.0;
+    const double hqp = hq + kl;
+    o[0] = (float)beta;
+    o[1] = (float)kl;
+    o[2] = (float)hqp;
+    o[3] = (float)hq;
+    o[4] = (float)(1.0 - sqrt(0.5 * kl));
+    o[5] = (float)(1.0 - sqrt(1.0 - exp(-kl)));
+    o[6] = (float)(1.0 - sqrt((double)a.c * hq));
+    o[7] = hq > 0.0 ? (float)(hqp / hq) : __int_as_float(0x7FC00000);
+}
+
 __global__ void k_zero(unsigned *p) { *p = 0u; }
 
 // ---- host side -------------------------------------------------------------------------------
@@ -690,7 +839,7 @@ const char *svip_status_string(int status)
         case SVIP_ERR_DTYPE: return "SVIP_ERR_DTYPE: unknown logits dtype";
         case SVIP_ERR_ALIGN: return "SVIP_ERR_ALIGN: pointer or stride not 16-byte aligned";
         case SVIP_ERR_WORKSPACE: return "SVIP_ERR_WORKSPACE: workspace missing, misaligned or too small";
-        case SVIP_ERR_PARAM: return "SVIP_ERR_PARAM: temperature or threshold out of range";
+        case SVIP_ERR_PARAM: return "SVIP_ERR_PARAM: temperature, threshold or constant out of range";
         case SVIP_ERR_HIP: return "SVIP_ERR_HIP: HIP runtime error";
         default: return "SVIP: unknown status";
     }
@@ -705,7 +854,10 @@ size_t svip_workspace_bytes(int B, int k_max, int V)
     const size_t vrows = (size_t)B * (2 * (size_t)k_max + 1);
     size_t parts = (size_t)B * MAX_SLICES;
     if (2 * vrows + 2048 > parts) parts = 2 * vrows + 2048;
-    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + align256(parts * sizeof(Partial));
+    // diagnostics: two logsumexps per position, and three slice sums for at most 2 B k + 2048 slices
+    const size_t pos = (size_t)B * (size_t)k_max;
+    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + align256(parts * sizeof(Partial)) +
+           align256(pos * 2 * sizeof(double)) + align256((2 * pos + 2048) * 3 * sizeof(double));
 }
 
 svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -885,6 +1037,7 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
     a.B = B;
     a.k = k_max;
     a.kd = kd;
+    a.bonus = 1;
     a.sc = make_scale(temperature);
     a.tokens = draft_tokens;
     a.draft_len = draft_len;
@@ -914,6 +1067,72 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
         hipLaunchKernelGGL(k_resid_mass<float>, g_mass, dim3(WG), 0, st, a);
         hipLaunchKernelGGL(k_resid_finish<float>, dim3(B), dim3(WG), 0, st, a);
     }
+    return check_launch();
+}
+
+svip_status svip_pair_stats(const void *target_logits, const void *draft_logits, svip_dtype dtype, int B,
+                            int k_max, int V, long long seq_stride_t, long long seq_stride_d,
+                            long long row_stride, float temperature, const int *draft_len,
+                            const double *draft_lse, float c, float *stats_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    if (!target_logits || !draft_logits || !draft_len || !stats_out) return SVIP_ERR_NULL;
+    if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || row_stride < V ||
+        seq_stride_t < (long long)(k_max - 1) * row_stride + V || seq_stride_d < (long long)(k_max - 1) * row_stride + V)
+        return SVIP_ERR_SHAPE;
+    const int kd = draft_lse ? 0 : k_max;
+    const long long stat_rows = (long long)B * (kd + k_max + 1), pos = (long long)B * k_max;
+    if (stat_rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;
+    const int vec = dtype == SVIP_BF16 ? 8 : 4;
+    if (!aligned16(target_logits) || !aligned16(draft_logits) || row_stride % vec != 0 ||
+        seq_stride_t % vec != 0 || seq_stride_d % vec != 0)
+        return SVIP_ERR_ALIGN;
+    if (!(temperature > 0.f) || !isfinite(temperature) || !(c >= 0.f) || !isfinite(c)) return SVIP_ERR_PARAM;
+
+    PairArgs a;
+    a.v.geo = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    a.v.geo_s = a.v.geo;
+    a.geo2 = make_geo(V, vec, pos, false, env_int("SVIP_PAIR_SLICES", 0));
+    const size_t part_bytes = align256((size_t)stat_rows * a.v.geo.ns * sizeof(Partial));
+    const size_t L_bytes = align256((size_t)pos * 2 * sizeof(double));
+    const size_t need = HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + part_bytes + L_bytes +
+                        (size_t)pos * a.geo2.ns * 3 * sizeof(double);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+        return SVIP_ERR_WORKSPACE;
+    a.v.target = target_logits;
+    a.v.draft = draft_logits;
+    a.v.seq_t = seq_stride_t;
+    a.v.seq_d = seq_stride_d;
+    a.v.row_stride = row_stride;
+    a.v.B = B;
+    a.v.k = k_max;
+    a.v.kd = kd;
+    a.v.bonus = 0;
+    a.v.sc = make_scale(temperature);
+    a.v.tokens = nullptr;
+    a.v.draft_len = draft_len;
+    a.v.draft_lse = draft_lse;
+    a.v.u_accept = nullptr;
+    a.v.u_resample = nullptr;
+    a.v.n_accepted = nullptr;
+    a.v.next_token = nullptr;
+    a.v.accept_prob = nullptr;
+    a.v.ws = carve(workspace, B);
+    char *after = reinterpret_cast<char *>(a.v.ws.part) + part_bytes;
+    a.L = reinterpret_cast<double *>(after);
+    a.sums = reinterpret_cast<double *>(after + L_bytes);
+    a.c = c;
+    a.out = stats_out;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 g_stats((unsigned)(stat_rows * a.v.geo.ns)), g_pos((unsigned)((pos + 63) / 64)),
+        g_sums((unsigned)(pos * a.geo2.ns));
+    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a.v);
+    else hipLaunchKernelGGL(k_verify_stats<float>, g_stats, dim3(WG), 0, st, a.v);
+    hipLaunchKernelGGL(k_pair_L, g_pos, dim3(64), 0, st, a);
+    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_pair_sums<bf16>, g_sums, dim3(WG), 0, st, a);
+    else hipLaunchKernelGGL(k_pair_sums<float>, g_sums, dim3(WG), 0, st, a);
+    hipLaunchKernelGGL(k_pair_finish, g_pos, dim3(64), 0, st, a);
     return check_launch();
 }
 
