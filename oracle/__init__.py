@@ -69,6 +69,11 @@ def _load():
         lib.oracle_diagnostics.restype = None
         lib.oracle_diagnostics.argtypes = [_D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
                                            _L, ctypes.c_double, _D]
+        lib.oracle_generate.restype = ctypes.c_long
+        lib.oracle_generate.argtypes = [
+            _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_long, ctypes.c_long, ctypes.c_double,
+            ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_long, _D, _D, _D, ctypes.c_long, ctypes.c_int,
+            ctypes.c_long, _L, _L, _L, _D]
         lib.oracle_sd_position_trials.restype = None
         lib.oracle_sd_position_trials.argtypes = [
             _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_ulonglong, ctypes.c_int, _L, _L]
@@ -245,6 +250,39 @@ def diagnostics(zp, zq, T, gamma, c) -> np.ndarray:
     out = np.empty((B, k, 8))
     _load().oracle_diagnostics(_p(zp, _D), _p(zq, _D), B, k, V, float(T), _p(gamma, _L), float(c), _p(out, _D))
     return out
+
+
+@dataclass
+class GenerateResult:
+    tokens: np.ndarray      # int64 [n_out] produced tokens in order
+    log: np.ndarray         # int64 [rounds, 5]: n at round start, cap, drafted, accepted, last token
+    min_margin: float       # smallest decision margin met on the way
+
+
+def generate(zp, zq, T, n0, max_new, h, gamma0, gamma_max, inc, dec, us=None, ua=None, ur=None,
+             greedy=False, max_rounds=None) -> GenerateResult:
+    """One sequence through the decoding loop over traces zp[L, V], zq[L, V]; see oracle_generate
+    in svip_oracle.c.  us, ua: [rounds, kw] uniforms, ur: [rounds]."""
+    zp = _f64(zp)
+    zq = _f64(zq)
+    L, V = zq.shape
+    assert zp.shape == (L, V) and 1 <= gamma0 <= gamma_max
+    R = int(max_rounds) if max_rounds is not None else int(max_new)
+    if greedy:
+        us = ua = np.zeros((R, gamma_max))
+        ur = np.zeros(R)
+    us, ua, ur = _f64(us), _f64(ua), _f64(ur).ravel()
+    assert us.ndim == 2 and us.shape == ua.shape and us.shape[1] >= gamma_max
+    R = min(R, us.shape[0], ur.size)
+    out = np.empty(R * (gamma_max + 1), np.int64)
+    log = np.empty((R, 5), np.int64)
+    n_out = ctypes.c_long(0)
+    mm = ctypes.c_double(0.0)
+    rounds = _load().oracle_generate(
+        _p(zp, _D), _p(zq, _D), L, V, float(T), int(n0), int(max_new), float(h), int(gamma0), int(gamma_max),
+        int(inc), int(dec), _p(us, _D), _p(ua, _D), _p(ur, _D), us.shape[1], int(bool(greedy)), R,
+        _p(out, _L), ctypes.byref(n_out), _p(log, _L), ctypes.byref(mm))
+    return GenerateResult(out[:n_out.value].copy(), log[:rounds].copy(), mm.value)
 
 
 def sd_position_trials(p, q, N: int, seed: int, resid_sign: int = +1):

@@ -336,6 +336,85 @@ void oracle_diagnostics(const double *zp, const double *zq, long B, long k, long
         }
 }
 
+/* ---- the decoding loop (Algorithm 1, Algorithm 6) ------------------------------------- */
+
+/*
+ * One sequence decoded over logit traces.  Algorithm 1 (stop drafting when sqrt(H_q) > h) and
+ * Algorithm 6 (a fixed draft length) are the same loop with different stopping rules, so one
+ * function covers both, and the Heuristic baseline of Section 3 (next draft length + inc if every
+ * drafted token was accepted, else - dec) is a rule for the cap between rounds:
+ *   SVIP:      h finite, gamma0 = gamma_max = the length limit, inc = dec = 0
+ *   Constant:  h = INFINITY, gamma0 = the draft length, inc = dec = 0
+ *   Heuristic: h = INFINITY, gamma0 the first length, inc = 2, dec = 1, lengths kept in [1, gamma_max]
+ *
+ * zq[L][V], zp[L][V]: logits of the draft / target model for the token at absolute position n
+ * (in this synthetic setting they do not depend on the tokens chosen before).  Generation
+ * starts at position n0 and a new round begins while fewer than max_new tokens were produced
+ * and the trace still holds cap + 1 rows from n on.  Round r draws with us[r*kw + j] (draft
+ * token j), ua[r*kw + j] (its acceptance test) and ur[r] (correction or bonus token); kw is the
+ * row width of those arrays (>= gamma_max).  greedy != 0 uses Algorithms 3 and 5 and no uniforms.
+ *
+ * out_tok receives the produced tokens in order (accepted draft tokens, then the correction or
+ * bonus token, per round); log[r][5] = {n at the start of round r, cap, drafted, accepted, last
+ * token of the round}.  Returns the number of rounds; *n_out = tokens produced; *min_margin = the
+ * smallest decision margin met (stop tests, draws, acceptance tests).
+ */
+long oracle_generate(const double *zp, const double *zq, long L, long V, double T,
+                     long n0, long max_new, double h, long gamma0, long gamma_max, long inc, long dec,
+                     const double *us, const double *ua, const double *ur, long kw, int greedy,
+                     long max_rounds, long *out_tok, long *n_out, long *log, double *min_margin)
+{
+    long n = n0, gamma = gamma0, rounds = 0, produced = 0;
+    double mm = INFINITY;
+    long *tok = (long *)malloc(sizeof(long) * (size_t)(gamma_max > gamma0 ? gamma_max : gamma0));
+    double *ap = (double *)malloc(sizeof(double) * (size_t)(gamma_max > gamma0 ? gamma_max : gamma0));
+    while (n - n0 < max_new && n + gamma + 1 <= L && rounds < max_rounds) {
+        const long cap = gamma;
+        /* drafting: one token per step until the stop test or the cap says stop */
+        long drafted = 0;
+        unsigned char stop = 0;
+        while (!stop) {
+            long x; double H, qx, lse, mh, ms = INFINITY;
+            if (greedy)
+                oracle_draft_step_greedy(zq + (n + drafted) * V, 1, V, V, T, h, drafted, cap, NULL,
+                                         &x, &H, &qx, &lse, &stop, &mh);
+            else
+                oracle_draft_step(zq + (n + drafted) * V, 1, V, V, T, h, drafted, cap,
+                                  us + rounds * kw + drafted, NULL, &x, &H, &qx, &lse, &stop, &mh, &ms);
+            tok[drafted] = x;
+            if (mh < mm) mm = mh;
+            if (ms < mm) mm = ms;
+            ++drafted;
+        }
+        /* verification of the drafted tokens against target rows n .. n + drafted */
+        long nacc, next;
+        if (greedy) {
+            oracle_verify_greedy(zp + n * V, 1, cap, V, tok, &drafted, &nacc, &next);
+        } else {
+            double mv, rm;
+            oracle_verify(zp + n * V, zq + n * V, 1, cap, V, T, tok, &drafted, ua + rounds * kw, ur + rounds,
+                          &nacc, &next, ap, &mv, &rm);
+            if (mv < mm) mm = mv;
+        }
+        for (long j = 0; j < nacc; ++j) out_tok[produced++] = tok[j];
+        out_tok[produced++] = next;
+        log[rounds * 5 + 0] = n;
+        log[rounds * 5 + 1] = cap;
+        log[rounds * 5 + 2] = drafted;
+        log[rounds * 5 + 3] = nacc;
+        log[rounds * 5 + 4] = next;
+        n += nacc + 1;
+        gamma += (nacc == drafted) ? inc : -dec;
+        if (gamma < 1) gamma = 1;
+        if (gamma > gamma_max) gamma = gamma_max;
+        ++rounds;
+    }
+    *n_out = produced;
+    *min_margin = mm;
+    free(tok); free(ap);
+    return rounds;
+}
+
 /* ---- brute-force law of one speculative position (Algorithms 2 + 4) ------------ */
 
 /*

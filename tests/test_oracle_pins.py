@@ -486,3 +486,115 @@ def test_diagnostics_uniform_and_temperature():
     zp, zq = rng.normal(0, 3, (2, k + 1, V)), rng.normal(0, 3, (2, k, V))
     assert np.allclose(oracle.diagnostics(zp, zq, 2.0, [k, 1], 0.2), oracle.diagnostics(zp / 2, zq / 2, 1.0, [k, 1], 0.2),
                        rtol=1e-12, equal_nan=True)
+
+
+# ---------------------------------------------------------------- the decoding loop (Algorithms 1 and 6)
+
+def _cdf_draw(z, u):
+    """Inverse-CDF draw from softmax(z) written with library routines."""
+    c = np.cumsum(scipy.special.softmax(z))
+    return int(np.searchsorted(c, u * c[-1], side="right"))
+
+
+def test_loop_constant_length_identical_models():
+    """p = q: every drafted token is accepted, a round of gamma draft tokens yields gamma + 1
+    (Algorithm 6); the tokens are the draws themselves."""
+    rng = _rng(31)
+    L, V, gam, new = 80, 12, 5, 40
+    z = rng.normal(0, 2, (L, V))
+    R = 20
+    us, ua, ur = rng.random((R, gam)), rng.random((R, gam)), rng.random(R)
+    r = oracle.generate(z, z, 1.0, 3, new, np.inf, gam, gam, 0, 0, us, ua, ur)
+    rounds = -(-new // (gam + 1))
+    assert r.log.shape[0] == rounds and r.tokens.size == rounds * (gam + 1)     # overshoots max_new within a round
+    for i in range(rounds):
+        n = 3 + i * (gam + 1)
+        assert r.log[i].tolist()[:4] == [n, gam, gam, gam]
+        want = [_cdf_draw(z[n + j], us[i, j]) for j in range(gam)] + [_cdf_draw(z[n + gam], ur[i])]
+        assert r.tokens[i * (gam + 1):(i + 1) * (gam + 1)].tolist() == want
+        assert r.log[i, 4] == want[-1]
+
+
+def test_loop_heuristic_length_rule():
+    """Next length + 2 after a fully accepted round, - 1 otherwise, kept inside [1, limit]."""
+    rng = _rng(32)
+    L, V = 400, 6
+    z = rng.normal(0, 1, (L, V))
+    R = 12
+    u = rng.random((R, 12))
+    r = oracle.generate(z, z, 1.0, 0, 10 ** 6, np.inf, 5, 12, 2, 1, u, u, rng.random(R), max_rounds=R)
+    assert r.log[:, 1].tolist() == [5, 7, 9, 11, 12, 12, 12, 12, 12, 12, 12, 12]
+    assert (r.log[:, 2] == r.log[:, 1]).all() and (r.log[:, 3] == r.log[:, 1]).all()
+    # disjoint supports: the first drafted token always fails and the correction is the target's token
+    zp = np.full((L, V), -np.inf)
+    zp[:, 0] = 0.0
+    zq = np.full((L, V), -np.inf)
+    zq[:, 1] = 0.0
+    r = oracle.generate(zp, zq, 1.0, 0, 9, np.inf, 5, 12, 2, 1, u, u, rng.random(R))
+    assert r.log[:, 1].tolist() == [5, 4, 3, 2, 1, 1, 1, 1, 1]
+    assert (r.log[:, 3] == 0).all() and (r.tokens == 0).all() and r.tokens.size == 9
+    assert r.log[:, 0].tolist() == list(range(9))                      # one token per round
+
+
+def test_loop_entropy_threshold_draft_lengths():
+    """Algorithm 1 on a trace whose flat rows (sqrt(H) = sqrt(ln V) > h) sit at known positions:
+    drafting runs up to and including the first flat row, the round adds one bonus token."""
+    L, V, h, cap = 64, 50, 1.0, 6
+    flat = {2, 3, 11, 12, 13, 30, 31, 40, 47, 55}
+    z = np.zeros((L, V))
+    for n in range(L):
+        if n not in flat:
+            z[n, (7 * n) % V] = 40.0                                     # H ~ 0
+    rng = _rng(33)
+    R = 30
+    us, ua, ur = rng.random((R, cap)), rng.random((R, cap)), rng.random(R)
+    r = oracle.generate(z, z, 1.0, 0, 40, h, cap, cap, 0, 0, us, ua, ur)
+    n, want = 0, []
+    while n < 40 and n + cap + 1 <= L:
+        d = next((f - n + 1 for f in sorted(flat) if f >= n and f - n + 1 <= cap), cap)
+        want.append([n, cap, d, d])
+        n += d + 1
+    assert r.log[:, :4].tolist() == want
+    # sharp rows yield their spike
+    pos = np.concatenate([np.arange(a, a + d + 1) for a, _, d, _ in want])
+    sharp = np.array([p not in flat for p in pos])
+    assert (r.tokens[sharp] == (7 * pos[sharp]) % V).all()
+
+
+def test_loop_tokens_per_round_matches_geometric_law():
+    """Same (p, q) at every position: each drafted token is accepted with probability beta, so a
+    round of gamma drafts produces (1 - beta^(gamma+1)) / (1 - beta) tokens on average, and the
+    produced tokens follow p."""
+    rng = _rng(34)
+    V, gam, R = 5, 4, 6000
+    zq, zp = rng.normal(0, 1, V), rng.normal(0, 1, V)
+    L = R * (gam + 1) + gam + 2
+    beta = oracle.pair_stats(zp, zq)["beta"]
+    r = oracle.generate(np.broadcast_to(zp, (L, V)), np.broadcast_to(zq, (L, V)), 1.0, 0, 10 ** 9, np.inf,
+                        gam, gam, 0, 0, rng.random((R, gam)), rng.random((R, gam)), rng.random(R))
+    assert r.log.shape[0] == R
+    per_round = r.log[:, 3] + 1
+    mean = (1 - beta ** (gam + 1)) / (1 - beta)
+    assert abs(per_round.mean() - mean) < 4.5 * per_round.std() / math.sqrt(R)
+    p = scipy.special.softmax(zp)
+    cnt = np.bincount(r.tokens, minlength=V)
+    chi2 = ((cnt - r.tokens.size * p) ** 2 / (r.tokens.size * p)).sum()
+    assert chi2 < scipy.stats.chi2.ppf(1 - 1e-6, V - 1)
+
+
+def test_loop_greedy_and_limits():
+    rng = _rng(35)
+    L, V = 50, 9
+    zq = rng.normal(0, 1, (L, V))
+    zp = zq.copy()
+    zp[7] = -zq[7]                                                        # argmax differs at position 7
+    r = oracle.generate(zp, zq, 1.0, 0, 20, np.inf, 4, 4, 0, 0, greedy=True)
+    am_q, am_p = zq.argmax(1), zp.argmax(1)
+    assert r.log[:, :4].tolist()[:3] == [[0, 4, 4, 4], [5, 4, 4, 2], [8, 4, 4, 4]]
+    assert r.tokens[:5].tolist() == am_q[:5].tolist() and r.tokens[5:8].tolist() == [am_q[5], am_q[6], am_p[7]]
+    # the trace must hold cap + 1 rows from n on: no round starts past L - cap - 1
+    r = oracle.generate(zq, zq, 1.0, 40, 100, np.inf, 4, 4, 0, 0, greedy=True)
+    assert r.log[:, 0].tolist() == [40, 45] and r.tokens.size == 10
+    # max_new is tested at the start of a round only
+    r = oracle.generate(zq, zq, 1.0, 0, 6, np.inf, 4, 4, 0, 0, greedy=True)
+    assert r.log.shape[0] == 2 and r.tokens.size == 10
