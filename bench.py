@@ -169,6 +169,47 @@ def cpu_baseline(w, h, nseq, threads):
     return rows, wall, busy
 
 
+def loop_policies(svip, si, dev, max_new=96, gamma_max=40, draft_cost=0.1):
+    """The decoding loop (Algorithm 1 / Algorithm 6) over Markov low/high-entropy traces shaped like
+    BASELINE config 4 (B = 8, V = 151936, bf16; the models agree on low-entropy rows and disagree on
+    high-entropy ones) under the three draft-length policies the paper compares,
+    with its auxiliary metrics.  `modelled_speedup` prices a draft step at `draft_cost` target
+    forward passes (tokens / (rounds + draft_cost * drafted)); it is a model, not a measurement."""
+    import math
+    import torch
+    w = si.workload("cfg4_loop")
+    L = max_new + gamma_max + 1
+    tr = si.gen_trace(w, L, rounds=max_new, gamma_max=gamma_max, seed=0)
+    zt, zd = tr["target"].to(dev), tr["draft"].to(dev)
+    us, ua, ur = tr["u_sample"].to(dev), tr["u_accept"].to(dev), tr["u_resample"].to(dev)
+    res = {"workload": f"{w.name} traces: B={w.B} V={w.V} {w.dtype}, L={L}, max_new={max_new}, limit {gamma_max}, T={w.T}",
+           "draft_cost": draft_cost}
+    for name, (h, g0, gmax, inc, dec) in (("svip_h3", (w.h, gamma_max, gamma_max, 0, 0)),
+                                          ("constant_5", (math.inf, 5, 5, 0, 0)),
+                                          ("heuristic", (math.inf, 5, gamma_max, 2, 1))):
+        best = None
+        for rep in range(2):            # second run is the timed one (first touches every page)
+            loop = svip.Loop(zt, zd, temperature=w.T, h=h, gamma0=g0, gamma_max=gmax, gamma_inc=inc, gamma_dec=dec,
+                             max_new=max_new, rounds=max_new, u_sample=us[:, :, :gmax].contiguous(),
+                             u_accept=ua[:, :, :gmax].contiguous(), u_resample=ur, log=False)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            loop.run()
+            best = time.perf_counter() - t0
+        st = loop.state.cpu().numpy()
+        rounds, drafted, accepted, produced = (int(st[:, i].sum()) for i in (3, 4, 5, 6))
+        res[name] = {
+            "mean_draft_len": drafted / rounds,
+            "accept_rate": accepted / drafted,
+            "tokens_per_round": produced / rounds,
+            "batch_rounds": loop.next_round,
+            "us_per_batch_round": 1e6 * best / max(loop.next_round, 1),
+            "tokens_per_s": produced / best,
+            "modelled_speedup": produced / (rounds + draft_cost * drafted),
+        }
+    return res
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the statistics kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE scaled by a plain copy of known size), or None if there is none."""
@@ -312,6 +353,8 @@ def main():
             "mean_beta": float(stats[..., 0].mean()),
             "mean_oracle_bound": float(stats[..., 4].mean()),
         }
+
+        extra["loop_policies"] = loop_policies(svip, si, dev)
 
     out = {
         "metric": "draft+verify rows/sec and achieved HBM GB/s (% peak) at V=128K bf16, B=64",

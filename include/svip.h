@@ -14,6 +14,8 @@
  *                     rejected, the bonus token drawn from the next target row
  *                                                       (Algorithm 1, verification loop;
  *                                                        Algorithm 2 Verify, Algorithm 4 Correct)
+ *   svip_loop_init, svip_loop_run   the decoding loop over logit traces with the draft-length
+ *                    policies the paper compares (Algorithm 1, Algorithm 6, Section 3)
  *   svip_pair_stats  acceptance diagnostics per drafted position (Section 2.2, Appendix B)
  *   svip_draft_step_greedy, svip_verify_greedy    the same two steps under greedy decoding
  *                                                       (Algorithm 3 Verify, Algorithm 5 Correct)
@@ -222,6 +224,65 @@ svip_status svip_pair_stats(
     float c,                         /* >= 0 */
     float *stats_out,                /* device [B, k_max, SVIP_PAIR_NSTAT] */
     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Decoding loop over logit traces: Algorithm 1 (stop drafting when sqrt(H_q) > h) and Algorithm 6
+ * (a fixed draft length) are one loop with different stopping rules, and the Heuristic baseline of
+ * Section 3 is a rule for the length limit between rounds:
+ *   SVIP:      h finite,   gamma0 = gamma_max = the length limit, gamma_inc = gamma_dec = 0
+ *   Constant:  h = +inf,   gamma0 = gamma_max = the draft length,  gamma_inc = gamma_dec = 0
+ *   Heuristic: h = +inf,   gamma0 = the first length, gamma_inc = 2, gamma_dec = 1; lengths stay in
+ *              [1, gamma_max]
+ * The models are stood in for by traces: row n of sequence b's trace holds the logits for the token
+ * at absolute position n (independent of the tokens chosen before).  A sequence starts a new round
+ * while it has produced fewer than max_new tokens and its trace holds limit + 1 more rows; a round
+ * produces the accepted draft tokens followed by the correction or bonus token.  Everything per
+ * round stays on the device; the host reads one counter per round (and, if check_every > 0, one
+ * more every check_every draft steps to end the drafting phase early).
+ *
+ * state[b, :] (int32): 0 position, 1 length limit of the next round, 2 finished, 3 rounds,
+ * 4 drafted tokens, 5 accepted tokens, 6 produced tokens, 7 start position.
+ * round_log[r, b, :] (optional): position, limit, drafted, accepted of round r (-1 when finished).
+ * Round r draws with u_sample[r, b, j], u_accept[r, b, j], u_resample[r, b].
+ */
+#define SVIP_LOOP_NSTATE 8
+typedef struct svip_loop_config {
+    const void *target_trace;   /* device [B, L, V]: row (b, n) at b * seq_stride + n * row_stride */
+    const void *draft_trace;    /* device, same layout */
+    svip_dtype dtype;
+    int B, L, V;
+    long long seq_stride, row_stride;   /* elements; multiples of 16 bytes */
+    float temperature;
+    int greedy;                 /* 0: Algorithms 2 and 4 with the uniforms below; 1: Algorithms 3 and 5 */
+    float h;                    /* entropy threshold; +inf disables the test */
+    int gamma0, gamma_max, gamma_inc, gamma_dec;
+    int n0;                     /* first position to generate */
+    int max_new;                /* tokens to produce per sequence (a round may overshoot by gamma_max) */
+    int rounds;                 /* rounds the uniform arrays and the log hold */
+    const float *u_sample;      /* device [rounds, B, gamma_max] (unused when greedy) */
+    const float *u_accept;      /* device [rounds, B, gamma_max] */
+    const float *u_resample;    /* device [rounds, B] */
+    int *state;                 /* device [B, SVIP_LOOP_NSTATE] */
+    int *out_tokens;            /* device [B, out_stride], out_stride >= max_new + gamma_max */
+    long long out_stride;
+    int *round_log;             /* device [rounds, B, 4] or NULL */
+    int check_every;            /* 0: never ask the device during drafting */
+    void *workspace;            /* device, svip_loop_workspace_bytes(B, gamma_max, V), 256-byte aligned */
+    size_t workspace_bytes;
+    void *hip_stream;
+} svip_loop_config;
+
+/* Bytes of device workspace the loop needs (kernel workspace plus the buffers of one round). */
+size_t svip_loop_workspace_bytes(int B, int gamma_max, int V);
+
+/* Set every sequence to position n0 with limit gamma0 and clear the counters and flags (enqueued). */
+svip_status svip_loop_init(const svip_loop_config *config /* host */);
+
+/* Run rounds first_round .. first_round + max_rounds - 1 (or until every sequence has finished).
+ * Synchronises the stream.  *rounds_run_host and *running_host (host, optional) receive the rounds
+ * executed and the sequences still running. */
+svip_status svip_loop_run(const svip_loop_config *config /* host */, int first_round, int max_rounds,
+                          int *rounds_run_host, int *running_host);
 
 /*
  * Timing hook for benchmarks: between svip_profile_begin and svip_profile_end every

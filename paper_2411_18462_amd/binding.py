@@ -18,13 +18,30 @@ _DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 # every symbol include/svip.h declares
 EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_reset",
            "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_draft_step_greedy",
-           "svip_verify_greedy", "svip_pair_stats", "svip_profile_begin", "svip_profile_end")
+           "svip_verify_greedy", "svip_pair_stats", "svip_loop_workspace_bytes", "svip_loop_init", "svip_loop_run",
+           "svip_profile_begin", "svip_profile_end")
 
 
 class SvipError(RuntimeError):
     def __init__(self, status: int, text: str):
         super().__init__(text)
         self.status = status
+
+
+class LoopConfig(ctypes.Structure):
+    """svip_loop_config of include/svip.h, field for field."""
+    _fields_ = [
+        ("target_trace", ctypes.c_void_p), ("draft_trace", ctypes.c_void_p), ("dtype", ctypes.c_int),
+        ("B", ctypes.c_int), ("L", ctypes.c_int), ("V", ctypes.c_int),
+        ("seq_stride", ctypes.c_longlong), ("row_stride", ctypes.c_longlong),
+        ("temperature", ctypes.c_float), ("greedy", ctypes.c_int), ("h", ctypes.c_float),
+        ("gamma0", ctypes.c_int), ("gamma_max", ctypes.c_int), ("gamma_inc", ctypes.c_int),
+        ("gamma_dec", ctypes.c_int), ("n0", ctypes.c_int), ("max_new", ctypes.c_int), ("rounds", ctypes.c_int),
+        ("u_sample", ctypes.c_void_p), ("u_accept", ctypes.c_void_p), ("u_resample", ctypes.c_void_p),
+        ("state", ctypes.c_void_p), ("out_tokens", ctypes.c_void_p), ("out_stride", ctypes.c_longlong),
+        ("round_log", ctypes.c_void_p), ("check_every", ctypes.c_int),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("hip_stream", ctypes.c_void_p),
+    ]
 
 
 def load():
@@ -56,6 +73,12 @@ def load():
     lib.svip_verify_greedy.argtypes = [vp, i, i, i, i, ll, ll, vp, vp, vp, vp, vp, sz, vp]
     lib.svip_pair_stats.restype = i
     lib.svip_pair_stats.argtypes = [vp, vp, i, i, i, i, ll, ll, ll, f, vp, vp, f, vp, vp, sz, vp]
+    lib.svip_loop_workspace_bytes.restype = sz
+    lib.svip_loop_workspace_bytes.argtypes = [i, i, i]
+    lib.svip_loop_init.restype = i
+    lib.svip_loop_init.argtypes = [ctypes.POINTER(LoopConfig)]
+    lib.svip_loop_run.restype = i
+    lib.svip_loop_run.argtypes = [ctypes.POINTER(LoopConfig), i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
     lib.svip_profile_begin.restype = i
     lib.svip_profile_begin.argtypes = [i]
     lib.svip_profile_end.restype = i
@@ -241,6 +264,78 @@ def verify(target_logits, draft_logits, *, temperature, draft_tokens, draft_len,
         _ptr(u_resample, torch.float32, "u_resample"), _ptr(n_accepted_out, torch.int32, "n_accepted_out"),
         _ptr(next_token_out, torch.int32, "next_token_out"), _ptr(accept_prob_out, torch.float32, "accept_prob_out"),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+LOOP_NSTATE = 8
+LOOP_STATE_FIELDS = ("pos", "limit", "finished", "rounds", "drafted", "accepted", "produced", "start")
+
+
+class Loop:
+    """The decoding loop over logit traces (svip_loop_init / svip_loop_run).  Holds the device
+    buffers the configuration points to; all arithmetic and bookkeeping runs in the library."""
+
+    def __init__(self, target_trace, draft_trace, *, temperature, h, gamma0, gamma_max, gamma_inc=0, gamma_dec=0,
+                 n0=0, max_new, rounds, greedy=False, u_sample=None, u_accept=None, u_resample=None,
+                 log=True, check_every=4, stream=None):
+        if target_trace.dim() != 3 or target_trace.shape != draft_trace.shape:
+            raise ValueError("traces must both be [B, L, V]")
+        if target_trace.dtype != draft_trace.dtype or draft_trace.dtype not in _DTYPES:
+            raise SvipError(3, "traces must both be float32 or both bfloat16")
+        if target_trace.stride() != draft_trace.stride() or draft_trace.stride(2) != 1:
+            raise ValueError("traces need the same strides and unit stride along V")
+        B, L, V = draft_trace.shape
+        dev = draft_trace.device
+        self.target_trace, self.draft_trace = target_trace, draft_trace
+        self.B, self.L, self.V, self.rounds, self.gamma_max = B, L, V, int(rounds), int(gamma_max)
+        self.u = []
+        if not greedy:
+            for t, shape, n in ((u_sample, (rounds, B, gamma_max), "u_sample"), (u_accept, (rounds, B, gamma_max), "u_accept"),
+                                (u_resample, (rounds, B), "u_resample")):
+                if t is None or tuple(t.shape) != shape or not t.is_contiguous():
+                    raise ValueError(f"{n} must be contiguous {list(shape)}")
+                self.u.append(t)
+        self.state = torch.zeros(B, LOOP_NSTATE, dtype=torch.int32, device=dev)
+        self.out_stride = int(max_new) + int(gamma_max)
+        self.out_tokens = torch.full((B, self.out_stride), -1, dtype=torch.int32, device=dev)
+        self.round_log = torch.full((rounds, B, 4), -2, dtype=torch.int32, device=dev) if log else None
+        n = int(load().svip_loop_workspace_bytes(B, gamma_max, V))
+        if n == 0:
+            raise SvipError(2, "svip_loop_workspace_bytes: bad B, gamma_max or V")
+        self.workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+        row_stride = draft_trace.stride(1) if L > 1 else max(V, draft_trace.stride(1))
+        seq_stride = draft_trace.stride(0) if B > 1 else L * row_stride
+        c = LoopConfig()
+        c.target_trace, c.draft_trace = _ptr(target_trace, None, "target_trace"), _ptr(draft_trace, None, "draft_trace")
+        c.dtype, c.B, c.L, c.V = _DTYPES[draft_trace.dtype], B, L, V
+        c.seq_stride, c.row_stride = seq_stride, row_stride
+        c.temperature, c.greedy, c.h = float(temperature), int(bool(greedy)), float(h)
+        c.gamma0, c.gamma_max, c.gamma_inc, c.gamma_dec = int(gamma0), int(gamma_max), int(gamma_inc), int(gamma_dec)
+        c.n0, c.max_new, c.rounds = int(n0), int(max_new), int(rounds)
+        if not greedy:
+            c.u_sample = _ptr(u_sample, torch.float32, "u_sample")
+            c.u_accept = _ptr(u_accept, torch.float32, "u_accept")
+            c.u_resample = _ptr(u_resample, torch.float32, "u_resample")
+        c.state, c.out_tokens, c.out_stride = self.state.data_ptr(), self.out_tokens.data_ptr(), self.out_stride
+        c.round_log = self.round_log.data_ptr() if log else None
+        c.check_every = int(check_every)
+        c.workspace, c.workspace_bytes, c.hip_stream = self.workspace.data_ptr(), n, _stream(stream)
+        self.config = c
+        self.next_round = 0
+        _check(load().svip_loop_init(ctypes.byref(c)))
+
+    def run(self, max_rounds=None):
+        """Runs up to max_rounds further rounds (default: all that are left); returns
+        (rounds run, sequences still running).  Synchronises the stream."""
+        left = self.rounds - self.next_round
+        n = left if max_rounds is None else min(int(max_rounds), left)
+        ran, running = ctypes.c_int(0), ctypes.c_int(0)
+        _check(load().svip_loop_run(ctypes.byref(self.config), self.next_round, n, ctypes.byref(ran),
+                                    ctypes.byref(running)))
+        self.next_round += ran.value
+        return ran.value, running.value
+
+    def flags(self) -> int:
+        return workspace_flags(self.workspace)
 
 
 def profile_begin(max_samples: int):

@@ -25,6 +25,7 @@
 
 #include "../../include/svip.h"
 #include "row_math.h"
+#include "svip_internal.h"
 
 namespace svip {
 
@@ -69,7 +70,10 @@ static Workspace carve(void *ws, int B)
 
 struct DraftArgs {
     const void *logits;
-    long long row_stride;
+    long long row_stride;   // between the rows of consecutive sequences
+    const int *pos;         // optional [B]: sequence b reads trace row pos[b] + step_j of its own trace
+    long long pos_stride;   // elements between consecutive trace rows (used with pos)
+    const int *cap;         // optional [B]: per-sequence limit on the draft length (at most k_max)
     int B;
     Geo geo;
     Scale sc;
@@ -91,6 +95,7 @@ struct VerifyArgs {
     const void *target;
     const void *draft;
     long long seq_t, seq_d, row_stride;
+    const int *pos;   // optional [B]: row j of sequence b is trace row pos[b] + j
     int B, k;
     int kd;        // draft rows per sequence in the statistics pass: k if the draft logsumexps are recomputed, else 0
     int bonus;     // 1: the statistics pass also covers target row draft_len (verification), 0: rows j < draft_len only
@@ -109,6 +114,13 @@ struct VerifyArgs {
 };
 
 __device__ __forceinline__ int clamp_len(int g, int k) { return g < 0 ? 0 : (g > k ? k : g); }
+
+// Element offset of row j of sequence b (seq_stride between sequences, optional trace position).
+template <typename A>
+__device__ __forceinline__ long long row_offset(const A &a, long long seq_stride, int b, int j)
+{
+    return (long long)b * seq_stride + (long long)(j + (a.pos ? a.pos[b] : 0)) * a.row_stride;
+}
 
 // ---- weights for the inverse CDF ---------------------------------------------------------
 
@@ -226,6 +238,16 @@ __device__ __forceinline__ int pick_slice(double M, double target, double incl, 
 
 // ---- draft step -------------------------------------------------------------------------------
 
+__device__ __forceinline__ long long draft_row_offset(const DraftArgs &a, int b)
+{
+    return (long long)b * a.row_stride + (a.pos ? (long long)(a.pos[b] + a.step_j) * a.pos_stride : 0ll);
+}
+__device__ __forceinline__ bool at_cap(const DraftArgs &a, int b)
+{
+    const int cap = a.cap ? min(a.cap[b], a.k_max) : a.k_max;
+    return a.step_j + 1 >= cap;
+}
+
 // grid (rows * slices): statistics of slice s of row b.  ARG (greedy drafting) also records
 // the smallest index that holds the slice maximum.
 template <typename DT, bool ARG>
@@ -234,7 +256,7 @@ __global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
     __shared__ double lds[2 * NWAVE];
     const int b = blockIdx.x / a.geo.ns, s = blockIdx.x - b * a.geo.ns;
     if (a.stop_in && a.stop_in[b]) return;
-    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
+    const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
     const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
     const Partial p = slice_stats<DT, true, ARG>(row, a.geo.V, tb, te, a.sc, lds);
     if (threadIdx.x == 0) a.part[(size_t)b * a.geo.ns + s] = p;
@@ -271,7 +293,7 @@ __global__ __launch_bounds__(WG) void k_draft_finish(DraftArgs a)
         }
         return;
     }
-    const DT *row = static_cast<const DT *>(a.logits) + (long long)b * a.row_stride;
+    const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
     if (tid < 64) {
         const Merged mg = merge_lane(tid < a.geo.ns ? p.m : neg_inf(), p.S, p.t, a.sc);
         const double incl = wave_inclusive_sum(mg.M);
@@ -302,7 +324,7 @@ __global__ __launch_bounds__(WG) void k_draft_finish(DraftArgs a)
         if (a.entropy) a.entropy[o] = (float)H;
         if (a.q_tok) a.q_tok[o] = (float)((double)wtok / S);
         a.lse[o] = (double)sh.m * a.sc.inv_T + lnS;
-        const bool stop = (sqrt(H) > (double)a.h) || (a.step_j + 1 >= a.k_max);
+        const bool stop = (sqrt(H) > (double)a.h) || at_cap(a, b);
         a.stop[b] = stop ? 1 : 0;
         if (a.draft_len) a.draft_len[b] = a.step_j + 1;
     }
@@ -342,7 +364,7 @@ __global__ __launch_bounds__(64) void k_draft_finish_greedy(DraftArgs a)
         if (a.entropy) a.entropy[o] = (float)H;
         if (a.q_tok) a.q_tok[o] = (float)(1.0 / S);           // the maximum has weight exp2(0) = 1
         a.lse[o] = (double)mg.m * a.sc.inv_T + lnS;
-        const bool stop = (sqrt(H) > (double)a.h) || (a.step_j + 1 >= a.k_max);
+        const bool stop = (sqrt(H) > (double)a.h) || at_cap(a, b);
         a.stop[b] = stop ? 1 : 0;
         if (a.draft_len) a.draft_len[b] = a.step_j + 1;
     }
@@ -353,6 +375,7 @@ __global__ __launch_bounds__(64) void k_draft_finish_greedy(DraftArgs a)
 struct GreedyArgs {
     const void *target;
     long long seq_t, row_stride;
+    const int *pos;   // optional [B]: row j of sequence b is trace row pos[b] + j
     int B, k;
     Geo geo;
     const int *tokens;
@@ -372,7 +395,7 @@ __global__ __launch_bounds__(WG) void k_argmax(GreedyArgs a)
     const int b = y / (a.k + 1), j = y - b * (a.k + 1);
     const int g = clamp_len(a.draft_len[b], a.k);
     if (j > g) return;
-    const DT *row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
+    const DT *row = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, j);
     const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
     const unsigned long long key = slice_argmax<DT>(row, a.geo.V, tb, te, lds);
     if (threadIdx.x == 0) a.keys[(size_t)y * a.geo.ns + s] = key;
@@ -441,11 +464,11 @@ __global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
     const DT *row;
     if (jj < a.kd) {
         if (jj >= g) return;
-        row = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)jj * a.row_stride;
+        row = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, jj);
     } else {
         const int j = jj - a.kd;
         if (j >= g + a.bonus) return;
-        row = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)j * a.row_stride;
+        row = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, j);
     }
     const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
     const Partial p = slice_stats<DT, false>(row, a.geo.V, tb, te, a.sc, lds);
@@ -481,8 +504,8 @@ __global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
     const int graw = a.draft_len[b];
     const int g = clamp_len(graw, a.k);
     if (graw != g && lane == 0) atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
-    const DT *tgt = static_cast<const DT *>(a.target) + (long long)b * a.seq_t;
-    const DT *drf = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d;
+    const DT *tgt = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, 0);
+    const DT *drf = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, 0);
     constexpr double LOG2E = 1.4426950408889634;
     int r = -1;                 // first rejection, once known
     double Lp_r = 0.0, Lq_r = 0.0;
@@ -551,8 +574,8 @@ __global__ __launch_bounds__(WG) void k_resid_mass(VerifyArgs a)
     __shared__ double lds[2 * NWAVE];
     const int b = blockIdx.x / a.geo_s.ns, s = blockIdx.x - b * a.geo_s.ns, tid = threadIdx.x;
     const SeqRec rec = a.ws.rec[b];
-    const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
-    const DT *qrow = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)rec.r * a.row_stride;
+    const DT *prow = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, rec.r);
+    const DT *qrow = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, rec.r);
     const ExpRef ep = make_exp_ref(a.sc, rec.Lp), eq = make_exp_ref(a.sc, rec.Lq);
     const int tb = s * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
     float Wacc = 0.f, Pacc = 0.f;
@@ -608,8 +631,8 @@ __global__ __launch_bounds__(WG) void k_resid_finish(VerifyArgs a)
         }
     }
     __syncthreads();
-    const DT *prow = static_cast<const DT *>(a.target) + (long long)b * a.seq_t + (long long)rec.r * a.row_stride;
-    const DT *qrow = static_cast<const DT *>(a.draft) + (long long)b * a.seq_d + (long long)rec.r * a.row_stride;
+    const DT *prow = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, rec.r);
+    const DT *qrow = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, rec.r);
     const int tb = sh.slice * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
     float wtok;
     int tok;
@@ -698,8 +721,8 @@ __global__ __launch_bounds__(WG) void k_pair_sums(PairArgs a)
     const int s = (int)(blockIdx.x - y * ns), tid = threadIdx.x;
     const int b = (int)(y / a.v.k), j = (int)(y - (long long)b * a.v.k);
     if (j >= clamp_len(a.v.draft_len[b], a.v.k)) return;
-    const DT *prow = static_cast<const DT *>(a.v.target) + (long long)b * a.v.seq_t + (long long)j * a.v.row_stride;
-    const DT *qrow = static_cast<const DT *>(a.v.draft) + (long long)b * a.v.seq_d + (long long)j * a.v.row_stride;
+    const DT *prow = static_cast<const DT *>(a.v.target) + row_offset(a.v, a.v.seq_t, b, j);
+    const DT *qrow = static_cast<const DT *>(a.v.draft) + row_offset(a.v, a.v.seq_d, b, j);
     const ExpRef ep = make_exp_ref(a.v.sc, a.L[2 * y]), eq = make_exp_ref(a.v.sc, a.L[2 * y + 1]);
     const int V = a.geo2.V, tb = s * a.geo2.tps, te = min(tb + a.geo2.tps, a.geo2.ntiles);
     const int fe = min(te, V / (WG * N));
@@ -824,6 +847,169 @@ struct Profile {
 };
 static Profile g_prof;
 
+// ---- the calls behind the entry points ---------------------------------------------------------
+
+svip_status draft_step_call(const DraftCall &c)
+{
+    if (!c.logits || (!c.greedy && !c.u_sample) || !c.token_out || !c.lse_out || !c.stop_out) return SVIP_ERR_NULL;
+    if (c.dtype != SVIP_F32 && c.dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (c.B <= 0 || c.B > MAX_BATCH || c.V <= 0 || c.k_max < 1 || c.k_max > SVIP_MAX_K || c.step_j < 0 ||
+        c.step_j >= c.k_max || c.io_stride < 1 || c.row_stride < c.V || (c.pos && c.pos_stride < c.V))
+        return SVIP_ERR_SHAPE;
+    const int vec = c.dtype == SVIP_BF16 ? 8 : 4;
+    if (!aligned16(c.logits) || c.row_stride % vec != 0 || (c.pos && c.pos_stride % vec != 0)) return SVIP_ERR_ALIGN;
+    if (!(c.temperature > 0.f) || !isfinite(c.temperature) || !(c.h >= 0.f)) return SVIP_ERR_PARAM;
+
+    DraftArgs a;
+    a.geo = make_geo(c.V, vec, c.B, true, env_int("SVIP_DRAFT_SLICES", 0));
+    const size_t need = HEADER_BYTES + ws_rec_bytes(c.B) + ws_mass_bytes(c.B) +
+                        (size_t)c.B * a.geo.ns * sizeof(Partial);
+    if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
+        return SVIP_ERR_WORKSPACE;
+    const Workspace w = carve(c.workspace, c.B);
+    a.logits = c.logits;
+    a.row_stride = c.row_stride;
+    a.pos = c.pos;
+    a.pos_stride = c.pos_stride;
+    a.cap = c.cap;
+    a.B = c.B;
+    a.sc = make_scale(c.temperature);
+    a.h = c.h;
+    a.step_j = c.step_j;
+    a.k_max = c.k_max;
+    a.u = c.u_sample;
+    a.stop_in = c.stop_in;
+    a.token = c.token_out;
+    a.entropy = c.entropy_out;
+    a.q_tok = c.q_tok_out;
+    a.lse = c.lse_out;
+    a.stop = c.stop_out;
+    a.draft_len = c.draft_len_out;
+    a.io_stride = c.io_stride;
+    a.part = w.part;
+    hipStream_t st = static_cast<hipStream_t>(c.stream);
+    const dim3 grid((unsigned)a.geo.ns * (unsigned)c.B);
+    if (c.greedy) {
+        if (c.dtype == SVIP_BF16) hipLaunchKernelGGL((k_draft_stats<bf16, true>), grid, dim3(WG), 0, st, a);
+        else hipLaunchKernelGGL((k_draft_stats<float, true>), grid, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_draft_finish_greedy, dim3(c.B), dim3(64), 0, st, a);
+    } else if (c.dtype == SVIP_BF16) {
+        hipLaunchKernelGGL((k_draft_stats<bf16, false>), grid, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_draft_finish<bf16>, dim3(c.B), dim3(WG), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((k_draft_stats<float, false>), grid, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_draft_finish<float>, dim3(c.B), dim3(WG), 0, st, a);
+    }
+    return check_launch();
+}
+
+static svip_status verify_greedy_call(const VerifyCall &c)
+{
+    if (!c.target || !c.draft_tokens || !c.draft_len || !c.n_accepted_out || !c.next_token_out) return SVIP_ERR_NULL;
+    if (c.dtype != SVIP_F32 && c.dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (c.B <= 0 || c.B > MAX_BATCH || c.V <= 0 || c.k_max < 1 || c.k_max > SVIP_MAX_K || c.row_stride < c.V ||
+        c.seq_stride_t < (long long)c.k_max * c.row_stride + c.V)
+        return SVIP_ERR_SHAPE;
+    const long long rows = (long long)c.B * (c.k_max + 1);
+    if (rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;
+    const int vec = c.dtype == SVIP_BF16 ? 8 : 4;
+    if (!aligned16(c.target) || c.row_stride % vec != 0 || c.seq_stride_t % vec != 0) return SVIP_ERR_ALIGN;
+    GreedyArgs a;
+    a.geo = make_geo(c.V, vec, rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    const size_t need = HEADER_BYTES + ws_rec_bytes(c.B) + ws_mass_bytes(c.B) +
+                        (size_t)rows * a.geo.ns * sizeof(unsigned long long);
+    if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
+        return SVIP_ERR_WORKSPACE;
+    const Workspace w = carve(c.workspace, c.B);
+    a.target = c.target;
+    a.seq_t = c.seq_stride_t;
+    a.row_stride = c.row_stride;
+    a.pos = c.pos;
+    a.B = c.B;
+    a.k = c.k_max;
+    a.tokens = c.draft_tokens;
+    a.draft_len = c.draft_len;
+    a.n_accepted = c.n_accepted_out;
+    a.next_token = c.next_token_out;
+    a.keys = reinterpret_cast<unsigned long long *>(w.part);
+    a.flags = w.flags;
+    hipStream_t st = static_cast<hipStream_t>(c.stream);
+    const dim3 grid((unsigned)(rows * a.geo.ns));
+    if (c.dtype == SVIP_BF16) hipLaunchKernelGGL(k_argmax<bf16>, grid, dim3(WG), 0, st, a);
+    else hipLaunchKernelGGL(k_argmax<float>, grid, dim3(WG), 0, st, a);
+    hipLaunchKernelGGL(k_accept_greedy, dim3(c.B), dim3(64), 0, st, a);
+    return check_launch();
+}
+
+svip_status verify_call(const VerifyCall &c)
+{
+    if (c.greedy) return verify_greedy_call(c);
+    if (!c.target || !c.draft || !c.draft_tokens || !c.draft_len || !c.u_accept || !c.u_resample ||
+        !c.n_accepted_out || !c.next_token_out)
+        return SVIP_ERR_NULL;
+    if (c.dtype != SVIP_F32 && c.dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (c.B <= 0 || c.B > MAX_BATCH || c.V <= 0 || c.k_max < 1 || c.k_max > SVIP_MAX_K || c.row_stride < c.V ||
+        c.seq_stride_t < (long long)c.k_max * c.row_stride + c.V ||
+        c.seq_stride_d < (long long)(c.k_max - 1) * c.row_stride + c.V)
+        return SVIP_ERR_SHAPE;
+    const int kd = c.draft_lse ? 0 : c.k_max;
+    const long long stat_rows = (long long)c.B * (kd + c.k_max + 1);
+    if (stat_rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;          // workgroups of the statistics pass
+    const int vec = c.dtype == SVIP_BF16 ? 8 : 4;
+    if (!aligned16(c.target) || !aligned16(c.draft) || c.row_stride % vec != 0 || c.seq_stride_t % vec != 0 ||
+        c.seq_stride_d % vec != 0)
+        return SVIP_ERR_ALIGN;
+    if (!(c.temperature > 0.f) || !isfinite(c.temperature)) return SVIP_ERR_PARAM;
+
+    VerifyArgs a;
+    a.geo = make_geo(c.V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    a.geo_s = make_geo(c.V, vec, c.B, true, env_int("SVIP_SAMPLE_SLICES", 0));
+    const size_t need = HEADER_BYTES + ws_rec_bytes(c.B) + ws_mass_bytes(c.B) +
+                        (size_t)stat_rows * a.geo.ns * sizeof(Partial);
+    if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
+        return SVIP_ERR_WORKSPACE;
+    a.target = c.target;
+    a.draft = c.draft;
+    a.seq_t = c.seq_stride_t;
+    a.seq_d = c.seq_stride_d;
+    a.row_stride = c.row_stride;
+    a.pos = c.pos;
+    a.B = c.B;
+    a.k = c.k_max;
+    a.kd = kd;
+    a.bonus = 1;
+    a.sc = make_scale(c.temperature);
+    a.tokens = c.draft_tokens;
+    a.draft_len = c.draft_len;
+    a.draft_lse = c.draft_lse;
+    a.u_accept = c.u_accept;
+    a.u_resample = c.u_resample;
+    a.n_accepted = c.n_accepted_out;
+    a.next_token = c.next_token_out;
+    a.accept_prob = c.accept_prob_out;
+    a.ws = carve(c.workspace, c.B);
+    hipStream_t st = static_cast<hipStream_t>(c.stream);
+    const dim3 g_stats((unsigned)(stat_rows * a.geo.ns)), g_mass((unsigned)a.geo_s.ns * (unsigned)c.B);
+    const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
+    if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], st);
+    if (c.dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a);
+    else hipLaunchKernelGGL(k_verify_stats<float>, g_stats, dim3(WG), 0, st, a);
+    if (timed) {
+        (void)hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st);
+        ++g_prof.used;
+    }
+    if (c.dtype == SVIP_BF16) {
+        hipLaunchKernelGGL(k_accept<bf16>, dim3(c.B), dim3(64), 0, st, a);
+        hipLaunchKernelGGL(k_resid_mass<bf16>, g_mass, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_resid_finish<bf16>, dim3(c.B), dim3(WG), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(k_accept<float>, dim3(c.B), dim3(64), 0, st, a);
+        hipLaunchKernelGGL(k_resid_mass<float>, g_mass, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_resid_finish<float>, dim3(c.B), dim3(WG), 0, st, a);
+    }
+    return check_launch();
+}
+
 }  // namespace svip
 
 using namespace svip;
@@ -879,61 +1065,6 @@ svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsign
     return hipStreamSynchronize(st) == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
 }
 
-static svip_status draft_step_impl(bool greedy, const void *draft_logits, svip_dtype dtype, int B, int V,
-                                   long long row_stride, float temperature, float h, int step_j, int k_max,
-                                   const float *u_sample, const unsigned char *stop_in, int *token_out,
-                                   float *entropy_out, float *q_tok_out, double *lse_out,
-                                   unsigned char *stop_out, int *draft_len_out, long long io_stride,
-                                   void *workspace, size_t workspace_bytes, void *hip_stream)
-{
-    if (!draft_logits || (!greedy && !u_sample) || !token_out || !lse_out || !stop_out) return SVIP_ERR_NULL;
-    if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
-    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || step_j < 0 ||
-        step_j >= k_max || io_stride < 1 || row_stride < V)
-        return SVIP_ERR_SHAPE;
-    const int vec = dtype == SVIP_BF16 ? 8 : 4;
-    if (!aligned16(draft_logits) || row_stride % vec != 0) return SVIP_ERR_ALIGN;
-    if (!(temperature > 0.f) || !isfinite(temperature) || !(h >= 0.f)) return SVIP_ERR_PARAM;
-
-    DraftArgs a;
-    a.geo = make_geo(V, vec, B, true, env_int("SVIP_DRAFT_SLICES", 0));
-    const size_t need = HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + (size_t)B * a.geo.ns * sizeof(Partial);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
-        return SVIP_ERR_WORKSPACE;
-    const Workspace w = carve(workspace, B);
-    a.logits = draft_logits;
-    a.row_stride = row_stride;
-    a.B = B;
-    a.sc = make_scale(temperature);
-    a.h = h;
-    a.step_j = step_j;
-    a.k_max = k_max;
-    a.u = u_sample;
-    a.stop_in = stop_in;
-    a.token = token_out;
-    a.entropy = entropy_out;
-    a.q_tok = q_tok_out;
-    a.lse = lse_out;
-    a.stop = stop_out;
-    a.draft_len = draft_len_out;
-    a.io_stride = io_stride;
-    a.part = w.part;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid((unsigned)a.geo.ns * (unsigned)B);
-    if (greedy) {
-        if (dtype == SVIP_BF16) hipLaunchKernelGGL((k_draft_stats<bf16, true>), grid, dim3(WG), 0, st, a);
-        else hipLaunchKernelGGL((k_draft_stats<float, true>), grid, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_draft_finish_greedy, dim3(B), dim3(64), 0, st, a);
-    } else if (dtype == SVIP_BF16) {
-        hipLaunchKernelGGL((k_draft_stats<bf16, false>), grid, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_draft_finish<bf16>, dim3(B), dim3(WG), 0, st, a);
-    } else {
-        hipLaunchKernelGGL((k_draft_stats<float, false>), grid, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_draft_finish<float>, dim3(B), dim3(WG), 0, st, a);
-    }
-    return check_launch();
-}
-
 svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
                             float temperature, float h, int step_j, int k_max, const float *u_sample,
                             const unsigned char *stop_in, int *token_out, float *entropy_out,
@@ -941,9 +1072,10 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
                             int *draft_len_out, long long io_stride, void *workspace,
                             size_t workspace_bytes, void *hip_stream)
 {
-    return draft_step_impl(false, draft_logits, dtype, B, V, row_stride, temperature, h, step_j, k_max, u_sample,
-                           stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out, draft_len_out,
-                           io_stride, workspace, workspace_bytes, hip_stream);
+    const DraftCall c{false, draft_logits, dtype, B, V, row_stride, nullptr, 0, nullptr, temperature, h, step_j,
+                      k_max, u_sample, stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out,
+                      draft_len_out, io_stride, workspace, workspace_bytes, hip_stream};
+    return draft_step_call(c);
 }
 
 svip_status svip_draft_step_greedy(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
@@ -953,9 +1085,10 @@ svip_status svip_draft_step_greedy(const void *draft_logits, svip_dtype dtype, i
                                    int *draft_len_out, long long io_stride, void *workspace,
                                    size_t workspace_bytes, void *hip_stream)
 {
-    return draft_step_impl(true, draft_logits, dtype, B, V, row_stride, temperature, h, step_j, k_max, nullptr,
-                           stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out, draft_len_out,
-                           io_stride, workspace, workspace_bytes, hip_stream);
+    const DraftCall c{true, draft_logits, dtype, B, V, row_stride, nullptr, 0, nullptr, temperature, h, step_j,
+                      k_max, nullptr, stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out,
+                      draft_len_out, io_stride, workspace, workspace_bytes, hip_stream};
+    return draft_step_call(c);
 }
 
 svip_status svip_verify_greedy(const void *target_logits, svip_dtype dtype, int B, int k_max, int V,
@@ -963,39 +1096,10 @@ svip_status svip_verify_greedy(const void *target_logits, svip_dtype dtype, int 
                                const int *draft_len, int *n_accepted_out, int *next_token_out,
                                void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!target_logits || !draft_tokens || !draft_len || !n_accepted_out || !next_token_out) return SVIP_ERR_NULL;
-    if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
-    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || row_stride < V ||
-        seq_stride_t < (long long)k_max * row_stride + V)
-        return SVIP_ERR_SHAPE;
-    const long long rows = (long long)B * (k_max + 1);
-    if (rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;
-    const int vec = dtype == SVIP_BF16 ? 8 : 4;
-    if (!aligned16(target_logits) || row_stride % vec != 0 || seq_stride_t % vec != 0) return SVIP_ERR_ALIGN;
-    GreedyArgs a;
-    a.geo = make_geo(V, vec, rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    const size_t need = HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) +
-                        (size_t)rows * a.geo.ns * sizeof(unsigned long long);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
-        return SVIP_ERR_WORKSPACE;
-    const Workspace w = carve(workspace, B);
-    a.target = target_logits;
-    a.seq_t = seq_stride_t;
-    a.row_stride = row_stride;
-    a.B = B;
-    a.k = k_max;
-    a.tokens = draft_tokens;
-    a.draft_len = draft_len;
-    a.n_accepted = n_accepted_out;
-    a.next_token = next_token_out;
-    a.keys = reinterpret_cast<unsigned long long *>(w.part);
-    a.flags = w.flags;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid((unsigned)(rows * a.geo.ns));
-    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_argmax<bf16>, grid, dim3(WG), 0, st, a);
-    else hipLaunchKernelGGL(k_argmax<float>, grid, dim3(WG), 0, st, a);
-    hipLaunchKernelGGL(k_accept_greedy, dim3(B), dim3(64), 0, st, a);
-    return check_launch();
+    const VerifyCall c{true, target_logits, nullptr, dtype, B, k_max, V, seq_stride_t, 0, row_stride, nullptr, 1.f,
+                       draft_tokens, draft_len, nullptr, nullptr, nullptr, n_accepted_out, next_token_out,
+                       nullptr, workspace, workspace_bytes, hip_stream};
+    return verify_call(c);
 }
 
 svip_status svip_verify(const void *target_logits, const void *draft_logits, svip_dtype dtype, int B,
@@ -1006,68 +1110,11 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
                         float *accept_prob_out, void *workspace, size_t workspace_bytes,
                         void *hip_stream)
 {
-    if (!target_logits || !draft_logits || !draft_tokens || !draft_len || !u_accept || !u_resample ||
-        !n_accepted_out || !next_token_out)
-        return SVIP_ERR_NULL;
-    if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
-    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || row_stride < V ||
-        seq_stride_t < (long long)k_max * row_stride + V || seq_stride_d < (long long)(k_max - 1) * row_stride + V)
-        return SVIP_ERR_SHAPE;
-    const int kd = draft_lse ? 0 : k_max;
-    const long long stat_rows = (long long)B * (kd + k_max + 1);
-    if (stat_rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;          // workgroups of the statistics pass
-    const int vec = dtype == SVIP_BF16 ? 8 : 4;
-    if (!aligned16(target_logits) || !aligned16(draft_logits) || row_stride % vec != 0 ||
-        seq_stride_t % vec != 0 || seq_stride_d % vec != 0)
-        return SVIP_ERR_ALIGN;
-    if (!(temperature > 0.f) || !isfinite(temperature)) return SVIP_ERR_PARAM;
-
-    VerifyArgs a;
-    a.geo = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    a.geo_s = make_geo(V, vec, B, true, env_int("SVIP_SAMPLE_SLICES", 0));
-    const size_t need = HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) +
-                        (size_t)stat_rows * a.geo.ns * sizeof(Partial);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
-        return SVIP_ERR_WORKSPACE;
-    a.target = target_logits;
-    a.draft = draft_logits;
-    a.seq_t = seq_stride_t;
-    a.seq_d = seq_stride_d;
-    a.row_stride = row_stride;
-    a.B = B;
-    a.k = k_max;
-    a.kd = kd;
-    a.bonus = 1;
-    a.sc = make_scale(temperature);
-    a.tokens = draft_tokens;
-    a.draft_len = draft_len;
-    a.draft_lse = draft_lse;
-    a.u_accept = u_accept;
-    a.u_resample = u_resample;
-    a.n_accepted = n_accepted_out;
-    a.next_token = next_token_out;
-    a.accept_prob = accept_prob_out;
-    a.ws = carve(workspace, B);
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 g_stats((unsigned)(stat_rows * a.geo.ns)), g_mass((unsigned)a.geo_s.ns * (unsigned)B);
-    const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
-    if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], st);
-    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a);
-    else hipLaunchKernelGGL(k_verify_stats<float>, g_stats, dim3(WG), 0, st, a);
-    if (timed) {
-        (void)hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st);
-        ++g_prof.used;
-    }
-    if (dtype == SVIP_BF16) {
-        hipLaunchKernelGGL(k_accept<bf16>, dim3(B), dim3(64), 0, st, a);
-        hipLaunchKernelGGL(k_resid_mass<bf16>, g_mass, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_resid_finish<bf16>, dim3(B), dim3(WG), 0, st, a);
-    } else {
-        hipLaunchKernelGGL(k_accept<float>, dim3(B), dim3(64), 0, st, a);
-        hipLaunchKernelGGL(k_resid_mass<float>, g_mass, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_resid_finish<float>, dim3(B), dim3(WG), 0, st, a);
-    }
-    return check_launch();
+    const VerifyCall c{false, target_logits, draft_logits, dtype, B, k_max, V, seq_stride_t, seq_stride_d,
+                       row_stride, nullptr, temperature, draft_tokens, draft_len, draft_lse, u_accept,
+                       u_resample, n_accepted_out, next_token_out, accept_prob_out, workspace,
+                       workspace_bytes, hip_stream};
+    return verify_call(c);
 }
 
 svip_status svip_pair_stats(const void *target_logits, const void *draft_logits, svip_dtype dtype, int B,
@@ -1105,6 +1152,7 @@ svip_status svip_pair_stats(const void *target_logits, const void *draft_logits,
     a.v.seq_t = seq_stride_t;
     a.v.seq_d = seq_stride_d;
     a.v.row_stride = row_stride;
+    a.v.pos = nullptr;
     a.v.B = B;
     a.v.k = k_max;
     a.v.kd = kd;

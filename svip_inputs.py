@@ -16,7 +16,9 @@ read the same bits):
     "spike"  : N(0, sigma^2) background with `spike` added at one seeded index
     "low"    : N(0, 1) background, the logit at one seeded index SET to 12.0
     "high"   : N(0, 0.5^2)
-  target row = stored draft row (widened to fp32) + N(0, noise^2), rounded to the dtype;
+  target row = stored draft row (widened to fp32) + N(0, noise^2), rounded to the dtype
+  (workloads with noise_high use that std on "high" rows, so that acceptance falls where the
+  draft entropy is high);
   the extra target row after the last draft position is a fresh row of a drawn type + noise.
   row types: "mixture" draws low w.p. 0.7 independently per row; "markov" follows a
   two-state chain per sequence (stay-probabilities 0.9 in low, 0.7 in high, start low).
@@ -43,6 +45,7 @@ class Workload:
     sigma: float = 3.0  # background std for "spike" rows
     spike: float = 8.0  # spike height for "spike" rows
     uid: int = 0        # enters the seed
+    noise_high: float | None = None   # std of the target perturbation on "high" rows (None: same as noise)
 
 
 # h = 3.0 separates the synthetic low rows (sqrt(H) <= 2.85) from the high rows
@@ -52,6 +55,9 @@ WORKLOADS = {
     "cfg2": Workload("cfg2", 16, 32000, "f32", 16, 1.0, 3.0, "mixture", 1.0, uid=2),
     "cfg3": Workload("cfg3", 64, 128256, "bf16", 16, 1.0, 3.0, "mixture", 1.5, uid=3),
     "cfg4": Workload("cfg4", 8, 151936, "bf16", 64, 1.0, 3.0, "markov", 1.5, uid=4),
+    # traces for the decoding loop: the models agree where the draft is confident (low rows, expected
+    # acceptance about 0.9) and disagree where it is not (high rows, about 0.45), the split of Section 2.1
+    "cfg4_loop": Workload("cfg4_loop", 8, 151936, "bf16", 64, 1.0, 3.0, "markov", 0.3, uid=5, noise_high=1.5),
 }
 
 
@@ -112,7 +118,8 @@ def gen_sequence(w: Workload, b: int, seed: int = 0) -> dict:
     base = _rows(w, types, g)                     # fp32, k+1 rows; last one has no draft row
     draft = base[: w.k].to(dt)
     stored = torch.cat([draft.float(), base[w.k:].to(dt).float()], 0)
-    target = (stored + w.noise * torch.randn(w.k + 1, w.V, generator=g)).to(dt)
+    scale = torch.tensor([w.noise_high if (t == "high" and w.noise_high is not None) else w.noise for t in types])
+    target = (stored + scale[:, None] * torch.randn(w.k + 1, w.V, generator=g)).to(dt)
     u = torch.rand(2 * w.k + 1, generator=g, dtype=torch.float32)
     return dict(draft=draft, target=target, u_sample=u[: w.k].clone(),
                 u_accept=u[w.k: 2 * w.k].clone(), u_resample=u[2 * w.k].clone(), types=types)
@@ -127,3 +134,21 @@ def gen_batch(w: Workload, seed: int = 0, rows=None) -> dict:
            ("draft", "target", "u_sample", "u_accept", "u_resample")}
     out["types"] = [s["types"] for s in seqs]
     return out
+
+
+def gen_trace(w: Workload, L: int, rounds: int, gamma_max: int, seed: int = 0, rows=None) -> dict:
+    """Logit traces for the decoding loop: sequence b's workload rows continued to L positions.
+    draft [B, L, V], target [B, L, V] (target row n = stored draft row n + noise), and the loop's
+    uniforms u_sample / u_accept [rounds, B, gamma_max], u_resample [rounds, B] (float32)."""
+    rows = list(range(w.B)) if rows is None else list(rows)
+    ww = replace(w, k=L)
+    seqs = [gen_sequence(ww, b, seed) for b in rows]
+    draft = torch.stack([s["draft"] for s in seqs])
+    target = torch.stack([s["target"][:L] for s in seqs])
+    g = torch.Generator(device="cpu")
+    g.manual_seed((seed * 7_919 + w.uid * 104_729 + 17) & 0x7FFFFFFFFFFFFFFF)
+    n = len(rows)
+    u = torch.rand(2, rounds, n, gamma_max, generator=g, dtype=torch.float32)
+    ur = torch.rand(rounds, n, generator=g, dtype=torch.float32)
+    return dict(draft=draft, target=target, u_sample=u[0].contiguous(), u_accept=u[1].contiguous(),
+                u_resample=ur, types=[s["types"][:L] for s in seqs])
