@@ -90,3 +90,64 @@ def test_host_checks_reject_before_any_gpu_call():
     ms, n = ctypes.c_double(0), ctypes.c_int(0)
     assert lib.svip_profile_end(ctypes.byref(ms), ctypes.byref(n)) == 6      # not begun
     assert lib.svip_profile_begin(0) == 6
+
+
+def test_host_checks_of_the_greedy_diagnostic_and_loop_calls():
+    lib = svip.load()
+    buf = ctypes.create_string_buffer(1 << 16)
+    p = (ctypes.addressof(buf) + 255) & ~255
+    V = 64
+    wsb = svip.workspace_bytes(2, 4, V)
+
+    def gdraft(**kw):
+        a = dict(logits=p, dtype=1, B=2, V=V, rs=V, T=1.0, h=0.3, j=0, k=4, stop_in=None, tok=p, ent=None, q=None,
+                 lse=p, stop=p, dl=None, ios=1, ws=p, wsb=wsb, st=None)
+        a.update(kw)
+        return lib.svip_draft_step_greedy(a["logits"], a["dtype"], a["B"], a["V"], a["rs"], a["T"], a["h"], a["j"],
+                                          a["k"], a["stop_in"], a["tok"], a["ent"], a["q"], a["lse"], a["stop"],
+                                          a["dl"], a["ios"], a["ws"], a["wsb"], a["st"])
+
+    assert gdraft(logits=None) == 1 and gdraft(tok=None) == 1 and gdraft(dtype=5) == 3 and gdraft(j=4) == 2
+    assert gdraft(rs=V + 4) == 4 and gdraft(T=0.0) == 6 and gdraft(wsb=256) == 5
+
+    def gverify(**kw):
+        a = dict(t=p, dtype=1, B=2, k=4, V=V, st_t=5 * V, rs=V, tok=p, dl=p, na=p, nt=p, ws=p, wsb=wsb, st=None)
+        a.update(kw)
+        return lib.svip_verify_greedy(a["t"], a["dtype"], a["B"], a["k"], a["V"], a["st_t"], a["rs"], a["tok"],
+                                      a["dl"], a["na"], a["nt"], a["ws"], a["wsb"], a["st"])
+
+    assert gverify(t=None) == 1 and gverify(tok=None) == 1 and gverify(dl=None) == 1 and gverify(nt=None) == 1
+    assert gverify(dtype=9) == 3 and gverify(k=0) == 2 and gverify(st_t=4 * V) == 2 and gverify(t=p + 4) == 4
+    assert gverify(ws=None) == 5 and gverify(wsb=64) == 5
+
+    def pair(**kw):
+        a = dict(t=p, d=p, dtype=1, B=2, k=4, V=V, st_t=4 * V, st_d=4 * V, rs=V, T=1.0, dl=p, lse=None, c=0.2,
+                 out=p, ws=p, wsb=wsb, st=None)
+        a.update(kw)
+        return lib.svip_pair_stats(a["t"], a["d"], a["dtype"], a["B"], a["k"], a["V"], a["st_t"], a["st_d"], a["rs"],
+                                   a["T"], a["dl"], a["lse"], a["c"], a["out"], a["ws"], a["wsb"], a["st"])
+
+    assert pair(t=None) == 1 and pair(d=None) == 1 and pair(dl=None) == 1 and pair(out=None) == 1
+    assert pair(dtype=-1) == 3 and pair(V=0) == 2 and pair(st_t=3 * V) == 2 and pair(d=p + 2) == 4
+    assert pair(T=float("nan")) == 6 and pair(c=-0.5) == 6 and pair(c=float("inf")) == 6 and pair(wsb=1024) == 5
+
+    lwsb = lib.svip_loop_workspace_bytes(2, 4, V)
+    assert lwsb > wsb and lwsb % 256 == 0 and lib.svip_loop_workspace_bytes(0, 4, V) == 0
+
+    def loop(**kw):
+        c = svip.LoopConfig()
+        a = dict(target_trace=p, draft_trace=p, dtype=1, B=2, L=20, V=V, seq_stride=20 * V, row_stride=V,
+                 temperature=1.0, greedy=0, h=0.3, gamma0=4, gamma_max=4, gamma_inc=0, gamma_dec=0, n0=0, max_new=8,
+                 rounds=8, u_sample=p, u_accept=p, u_resample=p, state=p, out_tokens=p, out_stride=12,
+                 round_log=None, check_every=4, workspace=p, workspace_bytes=lwsb, hip_stream=None)
+        a.update(kw)
+        for name, val in a.items():
+            setattr(c, name, val)
+        return lib.svip_loop_init(ctypes.byref(c)), lib.svip_loop_run(ctypes.byref(c), 0, 1, None, None)
+
+    assert lib.svip_loop_init(None) == 1
+    assert loop(target_trace=None) == (1, 1) and loop(state=None) == (1, 1) and loop(u_accept=None) == (1, 1)
+    assert loop(gamma0=5) == (2, 2) and loop(gamma_max=0) == (2, 2) and loop(n0=20) == (2, 2)
+    assert loop(seq_stride=19 * V) == (2, 2) and loop(out_stride=11) == (2, 2) and loop(rounds=0) == (2, 2)
+    assert loop(gamma_inc=-1) == (6, 6) and loop(check_every=-1) == (6, 6)
+    assert loop(workspace=None) == (5, 5) and loop(workspace_bytes=wsb) == (5, 5)
