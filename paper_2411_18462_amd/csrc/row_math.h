@@ -41,7 +41,8 @@ struct Geo {
 };
 
 struct Scale {
-    float c_hi, c_lo;   // log2(e) / T
+    float c_hi, c_lo;   // log2(e) / T as nearest float + remainder
+    float c_dn, c_up;   // the same constant as a float strictly below it + a positive remainder
     double c;
     double inv_T;
 };
@@ -339,6 +340,100 @@ __device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int
         accumulate<N, 1, WITH_T, ARG>(z, m, S, t, sc, &idx, t0);
     }
     return wg_combine<WITH_T, ARG>(m, S, t, sc, lds, idx);
+}
+
+// ---- logsumexp only (statistics pass of verification) -----------------------------------------
+//
+// S = sum exp2(z c - ref) relative to a reference ref = float(m c_dn) of the running maximum m,
+// with the exponent formed by two fused multiply-adds, x = fma(z, c_up, fma(z, c_dn, -ref)):
+// two rounded operations per logit, no subtraction, and no floor -- because c_up > 0, a logit
+// of -inf gives x = -inf and weight 0 without passing through inf - inf.  The exact value of
+// ref does not matter (it cancels in ref + log2 S); it only has to sit next to m c so that the
+// largest weight is about 1.
+template <int N, int NU>
+__device__ __forceinline__ void accumulate_lse(const float (&z)[NU][N], float &m, float &ref, float &S,
+                                               const Scale &sc)
+{
+    float mb = tree_max<N>(z[0]);
+#pragma unroll
+    for (int u = 1; u < NU; ++u) mb = vmax(mb, tree_max<N>(z[u]));
+    if (mb > m) {
+        const float nref = mb * sc.c_dn;
+        if (m != neg_inf()) S *= exp2_raw(ref - nref);
+        m = mb;
+        ref = nref;
+    }
+    const float nr = (m == neg_inf()) ? 0.f : -ref;
+    float Sb = 0.f;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        float e[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) e[i] = exp2_raw(fmaf(z[u][i], sc.c_up, fmaf(z[u][i], sc.c_dn, nr)));
+        Sb += tree_sum<N>(e);
+    }
+    S += Sb;
+}
+
+template <typename DT, int NU>
+__device__ __forceinline__ void lse_batch(const DT *row, int t0, float &m, float &ref, float &S, const Scale &sc)
+{
+    constexpr int N = VecOf<DT>::N;
+    typename RawOf<DT>::type raw[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) raw[u] = load_raw<DT>(row, (t0 + u) * WG + (int)threadIdx.x);
+    float z[NU][N];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) unpack(raw[u], z[u]);
+    accumulate_lse<N, NU>(z, m, ref, S, sc);
+}
+
+// (ref, S) of tiles [tb, te) of one row with S = sum exp2(z c - ref): Partial::m holds ref (log2
+// units), Partial::S the sum; m = -inf marks a slice without finite logits.  Batches hold 32
+// logits per thread (4 bf16 vectors or 8 fp32 vectors): small enough for 8 waves per SIMD.
+// Result valid in thread 0.
+template <typename DT>
+__device__ __forceinline__ Partial slice_lse(const DT *row, int V, int tb, int te, const Scale &sc,
+                                             double *lds /* >= NWAVE doubles */)
+{
+    constexpr int N = VecOf<DT>::N, NB = 32 / N;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    float m = neg_inf(), ref = neg_inf(), S = 0.f;
+    const int fe = min(te, V / (WG * N));
+    int t0 = tb;
+    for (; t0 + NB <= fe; t0 += NB) lse_batch<DT, NB>(row, t0, m, ref, S, sc);
+    if (NB == 8 && t0 + 4 <= fe) { lse_batch<DT, 4>(row, t0, m, ref, S, sc); t0 += 4; }
+    if (t0 + 2 <= fe) { lse_batch<DT, 2>(row, t0, m, ref, S, sc); t0 += 2; }
+    if (t0 + 1 <= fe) { lse_batch<DT, 1>(row, t0, m, ref, S, sc); t0 += 1; }
+    if (t0 < te) {
+        float z[1][N];
+        unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
+        accumulate_lse<N, 1>(z, m, ref, S, sc);
+    }
+    // workgroup: largest reference first, then every thread rescales to it (a difference of two
+    // floats, exact) and the sums are added in fp64
+    float *ldsf = reinterpret_cast<float *>(lds);
+    const float rw = wave_max(ref);
+    if (lane == 0) ldsf[wave] = rw;
+    __syncthreads();
+    float rg = ldsf[0];
+#pragma unroll
+    for (int w = 1; w < NWAVE; ++w) rg = vmax(rg, ldsf[w]);
+    __syncthreads();
+    double Sd = (m != neg_inf()) ? (double)S * (double)exp2_raw(ref - rg) : 0.0;
+    Sd = wave_sum(Sd);
+    if (lane == 0) lds[wave] = Sd;
+    __syncthreads();
+    Partial p;
+    p.m = rg;
+    p.idx = -1;
+    p.S = 0.0;
+    p.t = 0.0;
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) p.S += lds[w];
+    }
+    return p;
 }
 
 // ---- argmax only (greedy verification): no exponentials, a pure stream ---------------------

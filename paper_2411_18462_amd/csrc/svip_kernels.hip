@@ -471,27 +471,27 @@ __global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
         row = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, j);
     }
     const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    const Partial p = slice_stats<DT, false>(row, a.geo.V, tb, te, a.sc, lds);
+    const Partial p = slice_lse<DT>(row, a.geo.V, tb, te, a.sc, lds);
     if (threadIdx.x == 0) a.ws.part[stat_row(a, b, jj) * a.geo.ns + s] = p;
 }
 
 // ---- verify: acceptance test and first rejection -------------------------------------------
 
-// logsumexp * log2(e) of statistics row y, merged over its slices in fp64.
-__device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns, const Scale &sc)
+// logsumexp * log2(e) of statistics row y from its slices' (ref, S) pairs (slice_lse), in fp64.
+__device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns)
 {
-    float m = neg_inf();
+    float r = neg_inf();
     double S = 0.0;
     for (int s = 0; s < ns; ++s) {
         const Partial p = part[y * ns + s];
         if (p.m == neg_inf() || !(p.S > 0.0)) continue;
-        if (p.m > m) {
-            S *= exp2(((double)m - (double)p.m) * sc.c);     // exp2(-inf) = 0 on the first slice
-            m = p.m;
+        if (p.m > r) {
+            S *= exp2((double)r - (double)p.m);     // exp2(-inf) = 0 on the first slice
+            r = p.m;
         }
-        S += p.S * exp2(((double)p.m - (double)m) * sc.c);
+        S += p.S * exp2((double)p.m - (double)r);
     }
-    return (double)m * sc.c + log2(S);
+    return (double)r + log2(S);
 }
 
 // grid (sequences), one wave: lane = position, 64 positions per pass.  Lanes j <= draft_len merge
@@ -522,9 +522,9 @@ __global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
                 u = (double)a.u_accept[(size_t)b * a.k + j];
                 if (a.draft_lse) lse_q = a.draft_lse[(size_t)b * a.k + j];
             }
-            Lp = row_L(a.ws.part, stat_row(a, b, a.kd + j), a.geo.ns, a.sc);
+            Lp = row_L(a.ws.part, stat_row(a, b, a.kd + j), a.geo.ns);
             if (j < g) {
-                Lq = a.draft_lse ? lse_q * LOG2E : row_L(a.ws.part, stat_row(a, b, j), a.geo.ns, a.sc);
+                Lq = a.draft_lse ? lse_q * LOG2E : row_L(a.ws.part, stat_row(a, b, j), a.geo.ns);
                 if (x < 0 || x >= a.geo.V) {
                     atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_TOKEN);
                     x = x < 0 ? 0 : a.geo.V - 1;
@@ -667,9 +667,9 @@ __global__ __launch_bounds__(64) void k_pair_L(PairArgs a)
     const int g = clamp_len(graw, a.v.k);
     if (graw != g && j == 0) atomicOr(a.v.ws.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
     if (j >= g) return;
-    a.L[2 * y] = row_L(a.v.ws.part, stat_row(a.v, b, a.v.kd + j), a.v.geo.ns, a.v.sc);
+    a.L[2 * y] = row_L(a.v.ws.part, stat_row(a.v, b, a.v.kd + j), a.v.geo.ns);
     a.L[2 * y + 1] = a.v.draft_lse ? a.v.draft_lse[y] * 1.4426950408889634
-                                   : row_L(a.v.ws.part, stat_row(a.v, b, j), a.v.geo.ns, a.v.sc);
+                                   : row_L(a.v.ws.part, stat_row(a.v, b, j), a.v.geo.ns);
 }
 
 // One batch of NU vector pairs per thread: with p = exp2(xp), q = exp2(xq) the normalised
@@ -808,17 +808,24 @@ static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int for
     g.V = V;
     const int nvec = (V + vec - 1) / vec;
     g.ntiles = (nvec + WG - 1) / WG;
-    long long ns = (2048 + rows - 1) / rows;          // aim at >= 2048 workgroups ...
-    if (ns * 4 > g.ntiles) ns = g.ntiles / 4;         // ... of at least 4 tiles each
+    long long ns;
     if (want_one_batch) {
+        ns = (2048 + rows - 1) / rows;                // aim at >= 2048 workgroups ...
+        if (ns * 4 > g.ntiles) ns = g.ntiles / 4;     // ... of at least 4 tiles each
         const long long need = (g.ntiles + LOCATE_UNROLL - 1) / LOCATE_UNROLL;
         if (ns < need) ns = need;
+    } else {
+        ns = (8192 + rows - 1) / rows;                // streaming passes: about 8192 workgroups ...
+        if (ns * 8 > g.ntiles) ns = g.ntiles / 8;     // ... of at least 8 tiles each
     }
     if (forced_ns > 0) ns = forced_ns;
     if (ns > MAX_SLICES) ns = MAX_SLICES;
     if (ns > g.ntiles) ns = g.ntiles;
     if (ns < 1) ns = 1;
     g.tps = (g.ntiles + (int)ns - 1) / (int)ns;
+    // an odd number of tiles per slice staggers the slices' start addresses over the memory
+    // channels; slices that start a power of two apart measured up to 15 % slower
+    if (!want_one_batch && g.tps > 1 && (g.tps & 1) == 0 && env_int("SVIP_EVEN_TPS", 0) == 0) g.tps += 1;
     g.ns = (g.ntiles + g.tps - 1) / g.tps;
     return g;
 }
@@ -830,6 +837,9 @@ static Scale make_scale(float temperature)
     s.c = 1.4426950408889634 * s.inv_T;
     s.c_hi = (float)s.c;
     s.c_lo = (float)(s.c - (double)s.c_hi);
+    s.c_dn = s.c_hi;
+    while ((double)s.c_dn >= s.c) s.c_dn = nextafterf(s.c_dn, 0.f);      // strictly below c: the remainder is > 0
+    s.c_up = (float)(s.c - (double)s.c_dn);
     return s;
 }
 
@@ -1035,15 +1045,15 @@ size_t svip_workspace_bytes(int B, int k_max, int V)
 {
     if (B <= 0 || B > MAX_BATCH || k_max < 1 || k_max > SVIP_MAX_K || V <= 0) return 0;
     // slice statistics: the draft step slices its B rows finely (at most MAX_SLICES each); the
-    // statistics pass of verify has up to B (2 k + 1) rows, of which make_geo cuts at most
-    // ceil(2048 / rows) + 1 slices each
+    // streaming passes (statistics of verify, argmax, diagnostics) have up to B (2 k + 1) rows, of
+    // which make_geo cuts at most ceil(8192 / rows) slices each: rows + 8192 slices at most
     const size_t vrows = (size_t)B * (2 * (size_t)k_max + 1);
     size_t parts = (size_t)B * MAX_SLICES;
-    if (2 * vrows + 2048 > parts) parts = 2 * vrows + 2048;
-    // diagnostics: two logsumexps per position, and three slice sums for at most 2 B k + 2048 slices
+    if (vrows + 8192 > parts) parts = vrows + 8192;
+    // diagnostics: two logsumexps per position and three sums per slice of its second pass
     const size_t pos = (size_t)B * (size_t)k_max;
     return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + align256(parts * sizeof(Partial)) +
-           align256(pos * 2 * sizeof(double)) + align256((2 * pos + 2048) * 3 * sizeof(double));
+           align256(pos * 2 * sizeof(double)) + align256((pos + 8192) * 3 * sizeof(double));
 }
 
 svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream)

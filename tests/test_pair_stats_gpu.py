@@ -3,7 +3,8 @@
 Tolerances: beta, H_q and H_{q,p} to REL; KL to REL * H_{q,p} absolute (it is the difference of two
 entropies, each held to REL); the bounds to the same error carried through their square roots
 (|sqrt a - sqrt b| <= min(sqrt|a - b|, |a - b| / (2 sqrt b))), and exactly consistent with the
-GPU's own KL and H_q.
+GPU's own KL and H_q.  Quantities that are exactly 0 (identical rows, a one-token vocabulary) come out
+within FLOOR of 0.
 """
 import math
 
@@ -16,6 +17,8 @@ import svip_inputs as si
 from helpers import REL, f32
 
 pytestmark = pytest.mark.gpu
+
+FLOOR = 3e-7     # nats: the logsumexps behind every term are resolved to about one fp32 ulp of a sum near 1
 
 
 def _say(*a):
@@ -57,14 +60,14 @@ def _check(g, zp, zq, T, glen, c, stats=None):
             gb, gk, ghqp, ghq, gbo, gbh, gba, gr = g[b, j]
             where = f"seq {b} pos {j}"
             st["n"] += 1
-            assert abs(gb - beta) <= REL * beta + 1e-9, f"{where}: beta {gb} vs {beta}"
-            assert abs(ghq - hq) <= REL * hq + 1e-9, f"{where}: H_q {ghq} vs {hq}"
-            assert abs(ghqp - hqp) <= REL * hqp + 1e-9, f"{where}: H_qp {ghqp} vs {hqp}"
-            d = REL * hqp + 1e-9
+            assert abs(gb - beta) <= REL * beta + FLOOR, f"{where}: beta {gb} vs {beta}"
+            assert abs(ghq - hq) <= REL * hq + FLOOR, f"{where}: H_q {ghq} vs {hq}"
+            assert abs(ghqp - hqp) <= REL * hqp + FLOOR, f"{where}: H_qp {ghqp} vs {hqp}"
+            d = REL * hqp + FLOOR
             assert abs(gk - kl) <= d, f"{where}: KL {gk} vs {kl}"
             assert abs(gbo - bo) <= _sqrt_tol(d / 2, kl / 2) + 1e-6, f"{where}: oracle bound {gbo} vs {bo}"
             assert abs(gbh - bh) <= _sqrt_tol(d, 1 - math.exp(-kl)) + 1e-6, f"{where}: BH bound {gbh} vs {bh}"
-            assert abs(gba - ba) <= _sqrt_tol(cc * (REL * hq + 1e-9), cc * hq) + 1e-6, f"{where}: approx bound"
+            assert abs(gba - ba) <= _sqrt_tol(cc * (REL * hq + FLOOR), cc * hq) + 1e-6, f"{where}: approx bound"
             if hq > 1e-6:
                 assert abs(gr - ratio) <= 3 * REL * ratio + 1e-6, f"{where}: ratio {gr} vs {ratio}"
             # consistent with its own KL and H_q (fp32 outputs of fp64 arithmetic)
@@ -128,9 +131,9 @@ def test_pair_stats_ragged_vocab(svip, V, dtype):
     g = _run(svip, _padded(zp), _padded(zq), 0.9, glen, 0.3)
     zp_o = torch.cat([zp, zp[:, :1]], 1)                                   # the oracle's layout has a bonus row
     _check(g, zp_o, zq, 0.9, glen, 0.3)
-    assert g[1, 2, 0] > 1 - 1e-6 and g[1, 2, 1] < 1e-6 and abs(g[1, 2, 7] - 1) < 1e-5 or V == 1
+    assert g[1, 2, 0] > 1 - 1e-6 and g[1, 2, 1] < 1e-6 and (abs(g[1, 2, 7] - 1) < 1e-5 or g[1, 2, 3] < 0.1) or V == 1
     if V == 1:
-        assert g[0, 0, 0] == 1.0 and g[0, 0, 3] < 1e-12 and g[0, 0, 1] < 1e-12     # a one-token vocabulary
+        assert abs(g[0, 0, 0] - 1.0) < FLOOR and g[0, 0, 3] < FLOOR and g[0, 0, 1] < FLOOR     # a one-token vocabulary
 
 
 def test_pair_stats_host_errors(svip):
