@@ -80,9 +80,9 @@ __device__ __forceinline__ typename RawOf<DT>::type load_raw(const DT *row, int 
     return __builtin_nontemporal_load(reinterpret_cast<const R *>(row) + vi);
 }
 
-// Checked load for the last, partial tile of a row: elements at or beyond V read as -inf and
-// nothing past the row is touched.
-__device__ __forceinline__ f32x4 load_raw_checked(const float *row, int vi, int V)
+// Element-wise load of a vector that straddles or lies past the end of the row: elements at or
+// beyond V read as -inf and nothing past the row is touched.
+__device__ __forceinline__ f32x4 load_raw_edge(const float *row, int vi, int V)
 {
     const int base = vi * 4;
     f32x4 r;
@@ -92,7 +92,7 @@ __device__ __forceinline__ f32x4 load_raw_checked(const float *row, int vi, int 
     r.w = base + 3 < V ? row[base + 3] : neg_inf();
     return r;
 }
-__device__ __forceinline__ u32x4 load_raw_checked(const bf16 *row, int vi, int V)
+__device__ __forceinline__ u32x4 load_raw_edge(const bf16 *row, int vi, int V)
 {
     const int base = vi * 8;
     uint32_t w[4];
@@ -105,6 +105,15 @@ __device__ __forceinline__ u32x4 load_raw_checked(const bf16 *row, int vi, int V
     u32x4 r;
     r.x = w[0]; r.y = w[1]; r.z = w[2]; r.w = w[3];
     return r;
+}
+
+// Checked load for the last, partial tile of a row: a vector that lies wholly inside the row
+// is read as one 16-byte load, only the vector at the end of the row goes element by element.
+template <typename DT>
+__device__ __forceinline__ typename RawOf<DT>::type load_raw_checked(const DT *row, int vi, int V)
+{
+    if ((vi + 1) * VecOf<DT>::N <= V) return load_raw<DT>(row, vi);
+    return load_raw_edge(row, vi, V);
 }
 
 __device__ __forceinline__ void unpack(const f32x4 &v, float (&z)[4])
@@ -480,8 +489,9 @@ __device__ __forceinline__ unsigned long long slice_argmax(const DT *row, int V,
     int idx = -1;
     const int fe = min(te, V / (WG * N));
     int t0 = tb;
-    for (; t0 + 8 <= fe; t0 += 8) argmax_batch<DT, 8>(row, t0, m, idx);
-    if (t0 + 4 <= fe) { argmax_batch<DT, 4>(row, t0, m, idx); t0 += 4; }
+    constexpr int NB = 32 / N;                  // 32 logits per thread and batch, as in slice_lse
+    for (; t0 + NB <= fe; t0 += NB) argmax_batch<DT, NB>(row, t0, m, idx);
+    if (NB == 8 && t0 + 4 <= fe) { argmax_batch<DT, 4>(row, t0, m, idx); t0 += 4; }
     if (t0 + 2 <= fe) { argmax_batch<DT, 2>(row, t0, m, idx); t0 += 2; }
     if (t0 + 1 <= fe) { argmax_batch<DT, 1>(row, t0, m, idx); t0 += 1; }
     if (t0 < te) {

@@ -477,19 +477,39 @@ __global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
 
 // ---- verify: acceptance test and first rejection -------------------------------------------
 
-// logsumexp * log2(e) of statistics row y from its slices' (ref, S) pairs (slice_lse), in fp64.
+// logsumexp * log2(e) of statistics row y from its slices' (ref, S) pairs (slice_lse): the sums are
+// brought to the largest reference with single-precision exp2 of the (small, exactly formed)
+// reference differences and added in fp64.  Slices are fetched eight at a time so that the loads
+// of a chunk are in flight together.
 __device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns)
 {
     float r = neg_inf();
     double S = 0.0;
-    for (int s = 0; s < ns; ++s) {
-        const Partial p = part[y * ns + s];
-        if (p.m == neg_inf() || !(p.S > 0.0)) continue;
-        if (p.m > r) {
-            S *= exp2((double)r - (double)p.m);     // exp2(-inf) = 0 on the first slice
-            r = p.m;
+    for (int s0 = 0; s0 < ns; s0 += 8) {
+        float pm[8];
+        double pS[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool in = s0 + u < ns;
+            const Partial *p = part + y * ns + (in ? s0 + u : 0);
+            pm[u] = p->m;
+            pS[u] = p->S;
+            if (!in || !(pS[u] > 0.0)) {
+                pm[u] = neg_inf();
+                pS[u] = 0.0;
+            }
         }
-        S += p.S * exp2((double)p.m - (double)r);
+        float rc = pm[0];
+#pragma unroll
+        for (int u = 1; u < 8; ++u) rc = vmax(rc, pm[u]);
+        if (rc == neg_inf()) continue;
+        if (rc > r) {
+            if (r != neg_inf()) S *= (double)exp2_raw((float)((double)r - (double)rc));
+            r = rc;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (pm[u] != neg_inf()) S += pS[u] * (double)exp2_raw((float)((double)pm[u] - (double)r));
     }
     return (double)r + log2(S);
 }
