@@ -834,6 +834,9 @@ static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int for
         if (ns * 4 > g.ntiles) ns = g.ntiles / 4;     // ... of at least 4 tiles each
         const long long need = (g.ntiles + LOCATE_UNROLL - 1) / LOCATE_UNROLL;
         if (ns < need) ns = need;
+        // large batches are bound by bandwidth, not by latency: longer slices of an odd number of
+        // tiles (7) stream better than one-batch slices of 4, at the price of a two-batch search
+        if (rows >= 512 && g.ntiles >= 14) ns = (g.ntiles + 6) / 7;
     } else {
         ns = (8192 + rows - 1) / rows;                // streaming passes: about 8192 workgroups ...
         if (ns * 8 > g.ntiles) ns = g.ntiles / 8;     // ... of at least 8 tiles each
