@@ -8,9 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", "svip_kernels.hip"), os.path.join(HERE, "csrc", "svip_loop.hip")]
-HEADERS = [os.path.join(HERE, "csrc", "row_math.h"), os.path.join(HERE, "csrc", "wave_ops.h"),
-           os.path.join(HERE, "csrc", "svip_internal.h"),
-           os.path.join(ROOT, "include", "svip.h")]
+HEADERS = sorted(os.path.join(HERE, "csrc", f) for f in os.listdir(os.path.join(HERE, "csrc")) if f.endswith(".h")) + \
+    [os.path.join(ROOT, "include", "svip.h")]
 LIB = os.path.join(HERE, "libsvip.so")
 
 # packed-fp32 instructions are switched off for all device code of this library

@@ -1,0 +1,121 @@
+// Weights the inverse-CDF search and the mass kernels draw from: softmax of a row, residual max(0, p - q).
+#pragma once
+#include "kernel_args.h"
+
+namespace svip {
+
+// ---- weights for the inverse CDF ---------------------------------------------------------
+
+template <typename DT>
+struct SoftmaxWeights {        // w_i = exp2(z_i c - L)
+    typedef typename RawOf<DT>::type Pack;
+    const DT *row;
+    int V;
+    ExpRef ex;
+    __device__ __forceinline__ Pack load(int vi) const { return load_raw<DT>(row, vi); }
+    __device__ __forceinline__ Pack load_checked(int vi) const { return load_raw_checked(row, vi, V); }
+    __device__ __forceinline__ void weights(const Pack &pk, float (&w)[VecOf<DT>::N]) const
+    {
+        float z[VecOf<DT>::N];
+        unpack(pk, z);
+#pragma unroll
+        for (int e = 0; e < VecOf<DT>::N; ++e) w[e] = ex(z[e]);
+    }
+};
+
+template <typename DT>
+struct ResidualWeights {       // w_i = max(0, p_i - q_i), normalised p and q
+    struct Pack { typename RawOf<DT>::type p, q; };
+    const DT *prow, *qrow;
+    int V;
+    ExpRef exp_p, exp_q;
+    __device__ __forceinline__ Pack load(int vi) const
+    {
+        Pack pk;
+        pk.p = load_raw<DT>(prow, vi);
+        pk.q = load_raw<DT>(qrow, vi);
+        return pk;
+    }
+    __device__ __forceinline__ Pack load_checked(int vi) const
+    {
+        Pack pk;
+        pk.p = load_raw_checked(prow, vi, V);
+        pk.q = load_raw_checked(qrow, vi, V);
+        return pk;
+    }
+    __device__ __forceinline__ void weights(const Pack &pk, float (&w)[VecOf<DT>::N]) const
+    {
+        float zp[VecOf<DT>::N], zq[VecOf<DT>::N];
+        unpack(pk.p, zp);
+        unpack(pk.q, zq);
+#pragma unroll
+        for (int e = 0; e < VecOf<DT>::N; ++e) w[e] = fmaxf(exp_p(zp[e]) - exp_q(zq[e]), 0.f);
+    }
+};
+
+// One batch of NU vectors per thread of the rejected position's rows: adds the residual
+// mass max(0, p - q) (if RESID) and the target mass p of the batch.
+template <typename DT, int NU, bool RESID, bool CHECKED>
+__device__ __forceinline__ void mass_batch(const DT *prow, const DT *qrow, int V, int t0, const ExpRef &ep,
+                                           const ExpRef &eq, float &Wacc, float &Pacc)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x;
+    typename RawOf<DT>::type rp[NU], rq[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        const int vi = (t0 + u) * WG + tid;
+        rp[u] = CHECKED ? load_raw_checked(prow, vi, V) : load_raw<DT>(prow, vi);
+        if (RESID) rq[u] = CHECKED ? load_raw_checked(qrow, vi, V) : load_raw<DT>(qrow, vi);
+    }
+    float Wb = 0.f, Pb = 0.f;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        float zp[N], pw[N];
+        unpack(rp[u], zp);
+#pragma unroll
+        for (int e = 0; e < N; ++e) pw[e] = ep(zp[e]);
+        Pb += tree_sum<N>(pw);
+        if (RESID) {
+            float zq[N], w[N];
+            unpack(rq[u], zq);
+#pragma unroll
+            for (int e = 0; e < N; ++e) w[e] = fmaxf(pw[e] - eq(zq[e]), 0.f);
+            Wb += tree_sum<N>(w);
+        }
+    }
+    Wacc += Wb;
+    Pacc += Pb;
+}
+
+// Per-thread residual and target masses of tiles [tb, te) in batches of LOCATE_UNROLL vectors
+// (the same grouping of additions as the in-register path of k_resid).
+template <typename DT, bool RESID>
+__device__ __forceinline__ void slice_mass(const DT *prow, const DT *qrow, int V, int tb, int te,
+                                           const ExpRef &ep, const ExpRef &eq, float &Wacc, float &Pacc)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int fe = min(te, V / (WG * N));
+    int t0 = tb;
+    for (; t0 + 4 <= fe; t0 += 4) mass_batch<DT, 4, RESID, false>(prow, qrow, V, t0, ep, eq, Wacc, Pacc);
+    if (t0 + 2 <= fe) { mass_batch<DT, 2, RESID, false>(prow, qrow, V, t0, ep, eq, Wacc, Pacc); t0 += 2; }
+    if (t0 + 1 <= fe) { mass_batch<DT, 1, RESID, false>(prow, qrow, V, t0, ep, eq, Wacc, Pacc); t0 += 1; }
+    if (t0 < te) mass_batch<DT, 1, RESID, true>(prow, qrow, V, t0, ep, eq, Wacc, Pacc);
+}
+
+// Choice of the slice that contains `target` among per-lane slice masses M (lane order =
+// slice order).  Returns (uniform) the slice and the target relative to the slice start.
+__device__ __forceinline__ int pick_slice(double M, double target, double incl, double *local_target)
+{
+    const unsigned long long cross = __ballot(M > 0.0 && incl > target);
+    const unsigned long long mass = __ballot(M > 0.0);
+    int s;
+    if (cross) s = __ffsll((long long)cross) - 1;
+    else if (mass) s = 63 - __clzll((long long)mass);
+    else s = 0;
+    const double excl = read_lane(incl - M, s);
+    *local_target = target - excl;
+    return s;
+}
+
+}  // namespace svip
