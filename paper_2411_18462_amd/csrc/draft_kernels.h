@@ -22,7 +22,7 @@ __device__ __forceinline__ bool at_cap(const DraftArgs &a, int b)
 template <typename DT, bool ARG>
 __global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
 {
-    __shared__ double lds[2 * NWAVE];
+    __shared__ CombineLds lds;
     const int b = blockIdx.x / a.geo.ns, s = blockIdx.x - b * a.geo.ns;
     if (a.stop_in && a.stop_in[b]) return;
     const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
@@ -82,20 +82,26 @@ __global__ __launch_bounds__(WG) void k_draft_finish(DraftArgs a)
     __syncthreads();
     SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, sh.L)};
     const int tb = sh.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    // entropy, logsumexp and the stop test do not depend on the token: thread 0 computes and stores
+    // them while the slice's logits are on their way
+    auto row_outputs = [&]() {
+        if (tid == 0) {
+            // H = ln S - (sum e x ln2) / S  for weights e = exp2(x): the entropy of e / S
+            const double S = sh.S, lnS = log(S);
+            double H = lnS - 0.6931471805599453 * sh.tt / S;
+            H = H > 0.0 ? H : 0.0;
+            if (a.entropy) a.entropy[o] = (float)H;
+            a.lse[o] = (double)sh.m * a.sc.inv_T + lnS;
+            const bool stop = (sqrt(H) > (double)a.h) || at_cap(a, b);
+            a.stop[b] = stop ? 1 : 0;
+            if (a.draft_len) a.draft_len[b] = a.step_j + 1;
+        }
+    };
     float wtok;
-    const int tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    const int tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok, row_outputs);
     if (tid == 0) {
-        // H = ln S - (sum e x ln2) / S  for weights e = exp2(x): the entropy of e / S
-        const double S = sh.S, lnS = log(S);
-        double H = lnS - 0.6931471805599453 * sh.tt / S;
-        H = H > 0.0 ? H : 0.0;
         a.token[o] = tok;
-        if (a.entropy) a.entropy[o] = (float)H;
-        if (a.q_tok) a.q_tok[o] = (float)((double)wtok / S);
-        a.lse[o] = (double)sh.m * a.sc.inv_T + lnS;
-        const bool stop = (sqrt(H) > (double)a.h) || at_cap(a, b);
-        a.stop[b] = stop ? 1 : 0;
-        if (a.draft_len) a.draft_len[b] = a.step_j + 1;
+        if (a.q_tok) a.q_tok[o] = (float)((double)wtok / sh.S);
     }
 }
 

@@ -267,22 +267,27 @@ __device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, flo
     accumulate<N, NU, WITH_T, ARG>(z, m, S, t, sc, &idx, t0);
 }
 
+// LDS of one workgroup combination (each field is written once, so two barriers suffice).
+struct CombineLds {
+    float m[NWAVE];
+    int idx[NWAVE];
+    double S[NWAVE], t[NWAVE];
+};
+
 // Workgroup combination of the per-thread (m, S, t): maximum first, then every thread
-// rescales to it and the sums are added in fp64.  Result valid in thread 0.
+// rescales to it and the sums are added in fp64.  Result valid in thread 0.  One call per
+// kernel and LDS block.
 template <bool WITH_T, bool ARG = false>
-__device__ __forceinline__ Partial wg_combine(float m, float S, float t, const Scale &sc,
-                                              double *lds /* >= 2 * NWAVE doubles */, int idx = -1)
+__device__ __forceinline__ Partial wg_combine(float m, float S, float t, const Scale &sc, CombineLds &lds,
+                                              int idx = -1)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    float *ldsf = reinterpret_cast<float *>(lds);
     const float mw = wave_max(m);
-    __syncthreads();                      // the buffer may still be in use by an earlier call
-    if (lane == 0) ldsf[wave] = mw;
+    if (lane == 0) lds.m[wave] = mw;
     __syncthreads();
-    float mg = ldsf[0];
+    float mg = lds.m[0];
 #pragma unroll
-    for (int w = 1; w < NWAVE; ++w) mg = fmaxf(mg, ldsf[w]);
-    __syncthreads();
+    for (int w = 1; w < NWAVE; ++w) mg = fmaxf(mg, lds.m[w]);
     double Sd = 0.0, td = 0.0;
     if (m != neg_inf()) {
         const float xd = scaled_diff(m, mg, sc);
@@ -292,9 +297,15 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
     }
     Sd = wave_sum(Sd);
     if (WITH_T) td = wave_sum(td);
+    int wmin = 0x7FFFFFFF;
+    if (ARG) {      // smallest index among the threads that hold the workgroup maximum
+        const int cand = (m == mg && idx >= 0) ? idx : 0x7FFFFFFF;
+        wmin = -wave_reduce(-cand, OpMax{});
+    }
     if (lane == 0) {
-        lds[wave] = Sd;
-        lds[NWAVE + wave] = td;
+        lds.S[wave] = Sd;
+        lds.t[wave] = td;
+        if (ARG) lds.idx[wave] = wmin;
     }
     __syncthreads();
     Partial p;
@@ -305,21 +316,15 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
     if (tid == 0) {
 #pragma unroll
         for (int w = 0; w < NWAVE; ++w) {
-            p.S += lds[w];
-            p.t += lds[NWAVE + w];
+            p.S += lds.S[w];
+            p.t += lds.t[w];
         }
-    }
-    if (ARG) {      // smallest index among the threads that hold the workgroup maximum
-        const int cand = (m == mg && idx >= 0) ? idx : 0x7FFFFFFF;
-        const int wmin = -wave_reduce(-cand, OpMax{});
-        __syncthreads();
-        int *ldsi = reinterpret_cast<int *>(lds);
-        if (lane == 0) ldsi[wave] = wmin;
-        __syncthreads();
-        int best = ldsi[0];
+        if (ARG) {
+            int best = lds.idx[0];
 #pragma unroll
-        for (int w = 1; w < NWAVE; ++w) best = min(best, ldsi[w]);
-        p.idx = best == 0x7FFFFFFF ? -1 : best;
+            for (int w = 1; w < NWAVE; ++w) best = min(best, lds.idx[w]);
+            p.idx = best == 0x7FFFFFFF ? -1 : best;
+        }
     }
     return p;
 }
@@ -331,7 +336,7 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
 // partial and is read with bounds checks.  Result valid in thread 0.
 template <typename DT, bool WITH_T, bool ARG = false>
 __device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int te, const Scale &sc,
-                                               double *lds /* >= 2 * NWAVE doubles */)
+                                               CombineLds &lds)
 {
     constexpr int N = VecOf<DT>::N;
     const int tid = threadIdx.x;
@@ -403,7 +408,7 @@ __device__ __forceinline__ void lse_batch(const DT *row, int t0, float &m, float
 // Result valid in thread 0.
 template <typename DT>
 __device__ __forceinline__ Partial slice_lse(const DT *row, int V, int tb, int te, const Scale &sc,
-                                             double *lds /* >= NWAVE doubles */)
+                                             CombineLds &lds)
 {
     constexpr int N = VecOf<DT>::N, NB = 32 / N;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -421,17 +426,15 @@ __device__ __forceinline__ Partial slice_lse(const DT *row, int V, int tb, int t
     }
     // workgroup: largest reference first, then every thread rescales to it (a difference of two
     // floats, exact) and the sums are added in fp64
-    float *ldsf = reinterpret_cast<float *>(lds);
     const float rw = wave_max(ref);
-    if (lane == 0) ldsf[wave] = rw;
+    if (lane == 0) lds.m[wave] = rw;
     __syncthreads();
-    float rg = ldsf[0];
+    float rg = lds.m[0];
 #pragma unroll
-    for (int w = 1; w < NWAVE; ++w) rg = vmax(rg, ldsf[w]);
-    __syncthreads();
+    for (int w = 1; w < NWAVE; ++w) rg = vmax(rg, lds.m[w]);
     double Sd = (m != neg_inf()) ? (double)S * (double)exp2_raw(ref - rg) : 0.0;
     Sd = wave_sum(Sd);
-    if (lane == 0) lds[wave] = Sd;
+    if (lane == 0) lds.S[wave] = Sd;
     __syncthreads();
     Partial p;
     p.m = rg;
@@ -440,7 +443,7 @@ __device__ __forceinline__ Partial slice_lse(const DT *row, int V, int tb, int t
     p.t = 0.0;
     if (tid == 0) {
 #pragma unroll
-        for (int w = 0; w < NWAVE; ++w) p.S += lds[w];
+        for (int w = 0; w < NWAVE; ++w) p.S += lds.S[w];
     }
     return p;
 }
@@ -673,9 +676,15 @@ __device__ __forceinline__ void locate_fallback(WF &wf, int last, LocateLds &L)
 // Search over tiles [tb, te) with the weights fetched by the functor wf:
 // wf.load(vi) / wf.load_checked(vi) fetch the raw vector(s) and wf.weights(pack, w) turns them
 // into the N weights of vector vi (fp32, >= 0).
-template <int N, typename WF>
+struct NoHook {
+    __device__ __forceinline__ void operator()() const {}
+};
+
+// `between` runs once, after the loads of the first batch have been issued and before their data is
+// used: work that does not depend on the search hides behind the memory round trip there.
+template <int N, typename WF, typename Hook = NoHook>
 __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double target, LocateLds &L,
-                                               float *weight_out)
+                                               float *weight_out, Hook between = Hook())
 {
     constexpr int LU = LOCATE_UNROLL;
     const int tid = threadIdx.x;
@@ -689,6 +698,7 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
 #pragma unroll
         for (int u = 0; u < LU; ++u)
             if (t0 + u < fe) pk[u] = wf.load((t0 + u) * WG + tid);
+        if (t0 == tb) between();
 #pragma unroll
         for (int u = 0; u < LU; ++u) {
             if (t0 + u < fe) {

@@ -19,7 +19,7 @@ __device__ __forceinline__ size_t stat_row(const VerifyArgs &a, int b, int jj)
 template <typename DT>
 __global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
 {
-    __shared__ double lds[2 * NWAVE];
+    __shared__ CombineLds lds;
     const int y = blockIdx.x / a.geo.ns, s = blockIdx.x - y * a.geo.ns;
     const int rps = a.kd + a.k + 1;
     const int b = y / rps, jj = y - b * rps;
