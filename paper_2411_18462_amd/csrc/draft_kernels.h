@@ -27,7 +27,7 @@ __global__ __launch_bounds__(WG) void k_draft_stats(DraftArgs a)
     if (a.stop_in && a.stop_in[b]) return;
     const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
     const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    const Partial p = slice_stats<DT, true, ARG>(row, a.geo.V, tb, te, a.sc, lds);
+    const Partial p = slice_stats<DT, ARG>(row, a.geo.V, tb, te, a.sc, lds);
     if (threadIdx.x == 0) a.part[(size_t)b * a.geo.ns + s] = p;
 }
 

@@ -21,7 +21,6 @@ namespace svip {
 constexpr int WG = 256;              // threads per workgroup
 constexpr int NWAVE = WG / 64;
 constexpr int MAX_SLICES = 64;       // a wave merges one slice per lane
-constexpr int UNROLL = 8;            // vectors in flight per thread in the statistics pass
 constexpr int LOCATE_UNROLL = 4;     // tiles per batch of the inverse-CDF search
 constexpr float X_FLOOR = -200.0f;   // exp2 of anything below is 0 in fp32; also squashes NaN from -inf logits
 
@@ -161,7 +160,9 @@ __device__ __forceinline__ float tree_max(const float (&v)[N])
     }
 }
 
-// (z - m) * c in exp2 units, floored (see X_FLOOR).
+// (z - m) * c in exp2 units, floored (see X_FLOOR).  The subtraction comes first so that the
+// row maximum itself gets exactly 0 (weight exactly 1): a one-hot row then has S = 1, t = 0 and
+// H = 0 without rounding, and small entropies keep their relative accuracy.
 __device__ __forceinline__ float scaled_diff(float z, float m, const Scale &sc)
 {
     const float d = z - m;
@@ -213,22 +214,23 @@ __device__ __forceinline__ int first_equal(const float (&z)[NU][N], float v, int
     return found;
 }
 
-// One batch of NU vectors per thread folded into the thread's running (m, S, t).
-// With ARG, idx follows the smallest index that holds m: it moves only when the maximum strictly
-// increases, so earlier equal values keep it; t0 is the batch's first tile.
-template <int N, int NU, bool WITH_T, bool ARG = false>
+// One batch of NU vectors per thread folded into the thread's running (m, S, t): m the maximum of
+// its logits so far, S = sum exp2(x), t = sum exp2(x) x with x = (z - m) c.  With ARG, idx follows
+// the smallest index that holds m: it moves only when the maximum strictly increases, so earlier
+// equal values keep it; t0 is the batch's first tile.
+template <int N, int NU, bool ARG>
 __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, float &S, float &t,
-                                           const Scale &sc, int *idx = nullptr, int t0 = 0)
+                                           const Scale &sc, int &idx, int t0)
 {
     float mb = tree_max<N>(z[0]);
 #pragma unroll
     for (int u = 1; u < NU; ++u) mb = vmax(mb, tree_max<N>(z[u]));
     if (mb > m) {
-        if (ARG) *idx = first_equal<N, NU>(z, mb, t0);
+        if (ARG) idx = first_equal<N, NU>(z, mb, t0);
         if (m != neg_inf()) {
             const float xd = scaled_diff(m, mb, sc);
             const float f = exp2_raw(xd);
-            if (WITH_T) t = f * fmaf(xd, S, t);
+            t = f * fmaf(xd, S, t);
             S *= f;
         }
         m = mb;
@@ -242,18 +244,18 @@ __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, fl
         for (int i = 0; i < N; ++i) {
             const float x = scaled_diff(z[u][i], mref, sc);
             e[i] = exp2_raw(x);
-            if (WITH_T) ex[i] = e[i] * x;
+            ex[i] = e[i] * x;
         }
         // group sums are formed first, then added to the batch sum: the running sums only
         // ever take one addition per batch
         Sb += tree_sum<N>(e);
-        if (WITH_T) tb += tree_sum<N>(ex);
+        tb += tree_sum<N>(ex);
     }
     S += Sb;
-    if (WITH_T) t += tb;
+    t += tb;
 }
 
-template <typename DT, int NU, bool WITH_T, bool ARG>
+template <typename DT, int NU, bool ARG>
 __device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, float &S, float &t, int &idx,
                                             const Scale &sc)
 {
@@ -264,7 +266,7 @@ __device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, flo
     float z[NU][N];
 #pragma unroll
     for (int u = 0; u < NU; ++u) unpack(raw[u], z[u]);
-    accumulate<N, NU, WITH_T, ARG>(z, m, S, t, sc, &idx, t0);
+    accumulate<N, NU, ARG>(z, m, S, t, sc, idx, t0);
 }
 
 // LDS of one workgroup combination (each field is written once, so two barriers suffice).
@@ -277,7 +279,7 @@ struct CombineLds {
 // Workgroup combination of the per-thread (m, S, t): maximum first, then every thread
 // rescales to it and the sums are added in fp64.  Result valid in thread 0.  One call per
 // kernel and LDS block.
-template <bool WITH_T, bool ARG = false>
+template <bool ARG = false>
 __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const Scale &sc, CombineLds &lds,
                                               int idx = -1)
 {
@@ -293,10 +295,10 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
         const float xd = scaled_diff(m, mg, sc);
         const double f = (double)exp2_raw(xd);
         Sd = f * (double)S;
-        if (WITH_T) td = f * ((double)t + (double)xd * (double)S);
+        td = f * ((double)t + (double)xd * (double)S);
     }
     Sd = wave_sum(Sd);
-    if (WITH_T) td = wave_sum(td);
+    td = wave_sum(td);
     int wmin = 0x7FFFFFFF;
     if (ARG) {      // smallest index among the threads that hold the workgroup maximum
         const int cand = (m == mg && idx >= 0) ? idx : 0x7FFFFFFF;
@@ -329,31 +331,31 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
     return p;
 }
 
-// Streaming statistics of tiles [tb, te) of one row.  Every thread keeps a running maximum
-// of its own elements (rescaling its sums on the rare increase), so the loop has no
-// barrier; the workgroup combines at the end.  Tiles that lie wholly inside the row are read
-// in unchecked batches of 8/4/2/1 vectors per thread; only the row's last tile can be
+// Streaming statistics (m, S, t) of tiles [tb, te) of one row.  Every thread keeps a running
+// maximum of its own elements (rescaling its sums on the rare increase), so the loop has no
+// barrier; the workgroup combines at the end.  Tiles that lie wholly inside the row are read in
+// unchecked batches of 32 logits per thread (then 4/2/1 vectors); only the row's last tile can be
 // partial and is read with bounds checks.  Result valid in thread 0.
-template <typename DT, bool WITH_T, bool ARG = false>
+template <typename DT, bool ARG = false>
 __device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int te, const Scale &sc,
                                                CombineLds &lds)
 {
-    constexpr int N = VecOf<DT>::N;
+    constexpr int N = VecOf<DT>::N, NB = 32 / N;
     const int tid = threadIdx.x;
     float m = neg_inf(), S = 0.f, t = 0.f;
     int idx = -1;
     const int fe = min(te, V / (WG * N));      // end of the tiles that are wholly inside the row
     int t0 = tb;
-    for (; t0 + 8 <= fe; t0 += 8) stats_batch<DT, 8, WITH_T, ARG>(row, t0, m, S, t, idx, sc);
-    if (t0 + 4 <= fe) { stats_batch<DT, 4, WITH_T, ARG>(row, t0, m, S, t, idx, sc); t0 += 4; }
-    if (t0 + 2 <= fe) { stats_batch<DT, 2, WITH_T, ARG>(row, t0, m, S, t, idx, sc); t0 += 2; }
-    if (t0 + 1 <= fe) { stats_batch<DT, 1, WITH_T, ARG>(row, t0, m, S, t, idx, sc); t0 += 1; }
+    for (; t0 + NB <= fe; t0 += NB) stats_batch<DT, NB, ARG>(row, t0, m, S, t, idx, sc);
+    if (NB == 8 && t0 + 4 <= fe) { stats_batch<DT, 4, ARG>(row, t0, m, S, t, idx, sc); t0 += 4; }
+    if (t0 + 2 <= fe) { stats_batch<DT, 2, ARG>(row, t0, m, S, t, idx, sc); t0 += 2; }
+    if (t0 + 1 <= fe) { stats_batch<DT, 1, ARG>(row, t0, m, S, t, idx, sc); t0 += 1; }
     if (t0 < te) {
         float z[1][N];
         unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
-        accumulate<N, 1, WITH_T, ARG>(z, m, S, t, sc, &idx, t0);
+        accumulate<N, 1, ARG>(z, m, S, t, sc, idx, t0);
     }
-    return wg_combine<WITH_T, ARG>(m, S, t, sc, lds, idx);
+    return wg_combine<ARG>(m, S, t, sc, lds, idx);
 }
 
 // ---- logsumexp only (statistics pass of verification) -----------------------------------------
