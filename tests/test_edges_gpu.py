@@ -222,3 +222,28 @@ def test_large_batch_of_short_rows(svip):
                           r.draft_len.cpu().numpy().astype(np.int64), ua, ur, r, rows=rows)
     assert svip.workspace_flags(r.ws) == 0
     _say(f"B={B}: chain {st} verify {sv}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_small_entropies_keep_their_relative_accuracy(svip, dtype):
+    """Confident rows: one logit far above the rest, H from 5e-2 down to 1e-8.  The row maximum has
+    weight exactly 1 on the GPU, so the entropy comes from the tail alone and stays accurate to REL."""
+    from helpers import REL
+    V, k = 40003, 6
+    g = torch.Generator().manual_seed(12)
+    spikes = [16.0, 19.0, 22.0, 25.0, 28.0, 31.0]
+    draft = torch.randn(3, k, V, generator=g)
+    for j, s in enumerate(spikes):
+        draft[:, j, 1000 * j + 7] = s
+    draft = draft.to(dtype)
+    target = torch.cat([draft, draft[:, :1]], 1)
+    u = torch.rand(3, 3, k, generator=g)
+    r = Round(svip, _padded(draft, dtype, 8), _padded(target, dtype, 8), u[0], u[1], u[2][:, 0].contiguous(), 1.0, 0.3)
+    r.draft_all(chain=False)
+    H = r.entropy.cpu().numpy()
+    for b in range(3):
+        for j in range(k):
+            p, _ = oracle.softmax_row(draft[b, j].double().numpy(), 1.0)
+            want = oracle.entropy_row(p)
+            assert 1e-9 < want < 0.5
+            assert abs(H[b, j] - want) <= REL * want, f"row {b} step {j}: H {H[b, j]} vs {want}"
