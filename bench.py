@@ -227,7 +227,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards over sequences with no "
-              "exchange; see DESIGN.md); --gpus must be 1", file=sys.stderr)
+              "exchange, so N GPUs would each run this same program on their share of the batch); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
