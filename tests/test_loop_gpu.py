@@ -162,3 +162,25 @@ def test_loop_edges(svip):
         svip.Loop(tr["target"].cuda(), tr["draft"].cuda(), temperature=1.0, h=1.0, gamma0=5, gamma_max=5,
                   gamma_dec=-1, max_new=4, rounds=8, u_sample=tr["u_sample"].cuda(),
                   u_accept=tr["u_accept"].cuda(), u_resample=tr["u_resample"].cuda())
+
+
+def test_loop_full_size_as_benchmarked(svip):
+    """The benchmark's loop configuration (cfg4_loop traces: B = 8, V = 151936, bf16, limit 40, 96 new
+    tokens): the whole batch runs on the GPU, every round of two sampled sequences is replayed through
+    the oracle, and the bookkeeping of all sequences is checked."""
+    w = si.workload("cfg4_loop")
+    max_new, gmax = 96, 40
+    tr = si.gen_trace(w, max_new + gmax + 1, rounds=max_new, gamma_max=gmax, seed=0)
+    policy = (w.h, gmax, gmax, 0, 0)
+    _say("loop full size cfg4_loop")
+    res = _run(svip, tr, w, policy, max_new)
+    st = res["state"]
+    assert (st[:, 2] == 1).all() and (st[:, 6] >= max_new).all() and (st[:, 6] < max_new + gmax + 1).all()
+    assert (st[:, 0] == st[:, 7] + st[:, 6]).all() and (st[:, 5] + st[:, 3] == st[:, 6]).all()
+    rows = [1, 6]
+    sub = dict(draft=tr["draft"][rows], target=tr["target"][rows], u_sample=tr["u_sample"][:, rows],
+               u_accept=tr["u_accept"][:, rows], u_resample=tr["u_resample"][:, rows])
+    sub_res = dict(state=st[rows], out=res["out"][rows], log=res["log"][:, rows], rounds=res["rounds"])
+    chk = _check(sub_res, sub, w, policy, max_new)
+    _say(f"  {chk} {_metrics(st)}")
+    assert chk["in_margin_diff"] <= 0.05 * chk["rounds"]
