@@ -28,9 +28,9 @@
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without synchronising.  Outputs are valid once the stream
  *     has reached that point.
- *   - Logits are row-major rows of V values, bf16 or fp32.  Base pointers must be 16-byte
+ *   - Logits are row-major rows of V values, fp32, bf16 or fp16.  Base pointers must be 16-byte
  *     aligned and every stride (in elements) a multiple of 16 bytes' worth of elements
- *     (8 for bf16, 4 for fp32).  V itself may be any positive number.
+ *     (8 for bf16 and fp16, 4 for fp32).  V itself may be any positive number.
  *   - Arithmetic: fp32 per element with fp64 combination of partial results; entropies are
  *     in nats; logits are divided by `temperature` before the softmax and H is the entropy
  *     of that tempered distribution.  -inf logits carry no mass; a row with no finite logit
@@ -65,7 +65,8 @@ typedef enum {
     SVIP_ERR_HIP = 7         /* a HIP runtime call failed */
 } svip_status;
 
-typedef enum { SVIP_F32 = 0, SVIP_BF16 = 1 } svip_dtype;
+/* Storage type of the logits; every value is widened exactly to fp32 on load. */
+typedef enum { SVIP_F32 = 0, SVIP_BF16 = 1, SVIP_F16 = 2 } svip_dtype;
 
 /* Bits of the sticky device-data flag word. */
 enum { SVIP_FLAG_BAD_TOKEN = 1, SVIP_FLAG_BAD_DRAFT_LEN = 2 };

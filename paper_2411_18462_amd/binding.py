@@ -13,7 +13,7 @@ _lib = None
 MAX_K = 1024
 FLAG_BAD_TOKEN = 1
 FLAG_BAD_DRAFT_LEN = 2
-_DTYPES = {torch.float32: 0, torch.bfloat16: 1}
+_DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 
 # every symbol include/svip.h declares
 EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_reset",
@@ -152,7 +152,7 @@ def draft_step(draft_logits, *, temperature, h, step_j, k_max, token_out, lse_ou
     B, V = draft_logits.shape
     row_stride = draft_logits.stride(0) if B > 1 else max(V, draft_logits.stride(0))
     if draft_logits.dtype not in _DTYPES:
-        raise SvipError(3, "logits must be float32 or bfloat16")
+        raise SvipError(3, "logits must be float32, bfloat16 or float16")
     if not greedy and u_sample is None:
         raise SvipError(1, "u_sample is required unless greedy=True")
     pu, ios = _col(None if greedy else u_sample, B, torch.float32, "u_sample")
@@ -182,7 +182,7 @@ def verify_greedy(target_logits, *, draft_tokens, draft_len, n_accepted_out, nex
     B, kp1, V = target_logits.shape
     k = kp1 - 1
     if target_logits.dtype not in _DTYPES:
-        raise SvipError(3, "logits must be float32 or bfloat16")
+        raise SvipError(3, "logits must be float32, bfloat16 or float16")
     row_stride = target_logits.stride(1)
     seq_t = target_logits.stride(0) if B > 1 else kp1 * row_stride
     for t, shape, n in ((draft_tokens, (B, k), "draft_tokens"), (draft_len, (B,), "draft_len"),
@@ -210,7 +210,7 @@ def pair_stats(target_logits, draft_logits, *, temperature, draft_len, c, stats_
     if target_logits.shape[0] != B or target_logits.shape[1] < k or target_logits.shape[2] != V:
         raise ValueError("target_logits must be [B, >=k, V]")
     if target_logits.dtype != draft_logits.dtype or draft_logits.dtype not in _DTYPES:
-        raise SvipError(3, "logits must both be float32 or both bfloat16")
+        raise SvipError(3, "logits must both be float32, bfloat16 or float16")
     if target_logits.stride(2) != 1 or draft_logits.stride(2) != 1 or target_logits.stride(1) != draft_logits.stride(1):
         raise ValueError("logits need unit stride along V and a common row stride")
     row_stride = draft_logits.stride(1) if k > 1 else max(V, draft_logits.stride(1))
@@ -242,7 +242,7 @@ def verify(target_logits, draft_logits, *, temperature, draft_tokens, draft_len,
     if tuple(draft_logits.shape) != (B, k, V):
         raise ValueError(f"draft_logits must be [{B}, {k}, {V}]")
     if target_logits.dtype != draft_logits.dtype or target_logits.dtype not in _DTYPES:
-        raise SvipError(3, "logits must both be float32 or both bfloat16")
+        raise SvipError(3, "logits must both be float32, bfloat16 or float16")
     if target_logits.stride(2) != 1 or draft_logits.stride(2) != 1:
         raise ValueError("logits need unit stride along V")
     row_stride = target_logits.stride(1)
@@ -280,7 +280,7 @@ class Loop:
         if target_trace.dim() != 3 or target_trace.shape != draft_trace.shape:
             raise ValueError("traces must both be [B, L, V]")
         if target_trace.dtype != draft_trace.dtype or draft_trace.dtype not in _DTYPES:
-            raise SvipError(3, "traces must both be float32 or both bfloat16")
+            raise SvipError(3, "traces must both be float32, bfloat16 or float16")
         if target_trace.stride() != draft_trace.stride() or draft_trace.stride(2) != 1:
             raise ValueError("traces need the same strides and unit stride along V")
         B, L, V = draft_trace.shape

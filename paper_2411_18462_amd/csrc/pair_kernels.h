@@ -50,8 +50,8 @@ __device__ __forceinline__ void pair_batch(const DT *prow, const DT *qrow, int V
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
         float zp[N], zq[N], mn[N], dk[N], dh[N];
-        unpack(rp[u], zp);
-        unpack(rq[u], zq);
+        unpack<DT>(rp[u], zp);
+        unpack<DT>(rq[u], zq);
 #pragma unroll
         for (int e = 0; e < N; ++e) {
             const float xp = ep.arg(zp[e]), xq = eq.arg(zq[e]);

@@ -24,13 +24,15 @@ constexpr int MAX_SLICES = 64;       // a wave merges one slice per lane
 constexpr int LOCATE_UNROLL = 4;     // tiles per batch of the inverse-CDF search
 constexpr float X_FLOOR = -200.0f;   // exp2 of anything below is 0 in fp32; also squashes NaN from -inf logits
 
-struct bf16 { uint16_t bits; };
+struct bf16 { uint16_t bits; };   // storage types: the bits only, widened to fp32 on load
+struct f16 { uint16_t bits; };
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename DT> struct VecOf;
 template <> struct VecOf<float> { static constexpr int N = 4; };
 template <> struct VecOf<bf16> { static constexpr int N = 8; };
+template <> struct VecOf<f16> { static constexpr int N = 8; };
 
 struct Geo {
     int V;        // logits per row
@@ -70,6 +72,7 @@ __device__ __forceinline__ float vmax3(float a, float b, float c)
 template <typename DT> struct RawOf;
 template <> struct RawOf<float> { typedef f32x4 type; };
 template <> struct RawOf<bf16> { typedef u32x4 type; };
+template <> struct RawOf<f16> { typedef u32x4 type; };
 
 // Unchecked load of vector vi: every element must lie inside the row.
 template <typename DT>
@@ -106,6 +109,21 @@ __device__ __forceinline__ u32x4 load_raw_edge(const bf16 *row, int vi, int V)
     return r;
 }
 
+__device__ __forceinline__ u32x4 load_raw_edge(const f16 *row, int vi, int V)
+{
+    const int base = vi * 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t lo = base + 2 * e < V ? row[base + 2 * e].bits : 0xFC00u;       // fp16 -inf
+        const uint32_t hi = base + 2 * e + 1 < V ? row[base + 2 * e + 1].bits : 0xFC00u;
+        w[e] = lo | (hi << 16);
+    }
+    u32x4 r;
+    r.x = w[0]; r.y = w[1]; r.z = w[2]; r.w = w[3];
+    return r;
+}
+
 // Checked load for the last, partial tile of a row: a vector that lies wholly inside the row
 // is read as one 16-byte load, only the vector at the end of the row goes element by element.
 template <typename DT>
@@ -115,17 +133,36 @@ __device__ __forceinline__ typename RawOf<DT>::type load_raw_checked(const DT *r
     return load_raw_edge(row, vi, V);
 }
 
-__device__ __forceinline__ void unpack(const f32x4 &v, float (&z)[4])
+// Widening of one 16-byte vector to fp32 (exact for every storage type).
+template <typename DT>
+__device__ __forceinline__ void unpack(const typename RawOf<DT>::type &v, float (&z)[VecOf<DT>::N]);
+template <>
+__device__ __forceinline__ void unpack<float>(const f32x4 &v, float (&z)[4])
 {
     z[0] = v.x; z[1] = v.y; z[2] = v.z; z[3] = v.w;
 }
-__device__ __forceinline__ void unpack(const u32x4 &v, float (&z)[8])
+template <>
+__device__ __forceinline__ void unpack<bf16>(const u32x4 &v, float (&z)[8])
 {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         z[2 * e] = __uint_as_float(w[e] << 16);
         z[2 * e + 1] = __uint_as_float(w[e] & 0xFFFF0000u);
+    }
+}
+__device__ __forceinline__ float half_bits_to_float(uint32_t bits)
+{
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)bits);
+}
+template <>
+__device__ __forceinline__ void unpack<f16>(const u32x4 &v, float (&z)[8])
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        z[2 * e] = half_bits_to_float(w[e] & 0xFFFFu);
+        z[2 * e + 1] = half_bits_to_float(w[e] >> 16);
     }
 }
 
@@ -138,6 +175,8 @@ __device__ __forceinline__ float load_one<bf16>(const bf16 *row, int i)
 {
     return __uint_as_float((uint32_t)row[i].bits << 16);
 }
+template <>
+__device__ __forceinline__ float load_one<f16>(const f16 *row, int i) { return half_bits_to_float(row[i].bits); }
 
 template <int N>
 __device__ __forceinline__ float tree_sum(const float (&v)[N])
@@ -214,12 +253,17 @@ __device__ __forceinline__ int first_equal(const float (&z)[NU][N], float v, int
     return found;
 }
 
-// One batch of NU vectors per thread folded into the thread's running (m, S, t): m the maximum of
-// its logits so far, S = sum exp2(x), t = sum exp2(x) x with x = (z - m) c.  With ARG, idx follows
-// the smallest index that holds m: it moves only when the maximum strictly increases, so earlier
-// equal values keep it; t0 is the batch's first tile.
+// One batch of NU vectors per thread folded into the thread's running statistics: m, the maximum
+// of its logits so far; with x = (z - m) c and w = exp2(x):  ones = the number of weights that are
+// exactly 1 in fp32 (the maximum, its ties, anything within one rounding of it), S = the sum of all
+// other weights, t = sum w x.  Keeping the ones out of the fp32 sum is what keeps small entropies
+// accurate: next to a 1 the tail of a confident row (1e-4 and less) would lose its low bits.  The
+// loop sums fract(w) (fract(1) = 0, fract(w) = w below 1) beside w itself; the difference of the two
+// batch sums is the batch's count of ones up to rounding far below 1/2.  With ARG, idx follows the
+// smallest index that holds m: it moves only when the maximum strictly increases, so earlier equal
+// values keep it; t0 is the batch's first tile.
 template <int N, int NU, bool ARG>
-__device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, float &S, float &t,
+__device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, float &ones, float &S, float &t,
                                            const Scale &sc, int &idx, int t0)
 {
     float mb = tree_max<N>(z[0]);
@@ -230,34 +274,41 @@ __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, fl
         if (m != neg_inf()) {
             const float xd = scaled_diff(m, mb, sc);
             const float f = exp2_raw(xd);
-            t = f * fmaf(xd, S, t);
-            S *= f;
+            if (f < 1.0f) {                     // the old maximum becomes an ordinary term
+                const float all = S + ones;
+                t = f * fmaf(xd, all, t);
+                S = f * all;
+                ones = 0.f;
+            }                                   // else: still weight 1 at fp32 resolution, nothing moves
         }
         m = mb;
     }
     const float mref = (m == neg_inf()) ? 0.f : m;
-    float Sb = 0.f, tb = 0.f;
+    float Wb = 0.f, Sb = 0.f, tb = 0.f;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-        float e[N], ex[N];
+        float w[N], fr[N], wx[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const float x = scaled_diff(z[u][i], mref, sc);
-            e[i] = exp2_raw(x);
-            ex[i] = e[i] * x;
+            w[i] = exp2_raw(x);
+            wx[i] = w[i] * x;
+            fr[i] = __builtin_amdgcn_fractf(w[i]);
         }
         // group sums are formed first, then added to the batch sum: the running sums only
         // ever take one addition per batch
-        Sb += tree_sum<N>(e);
-        tb += tree_sum<N>(ex);
+        Wb += tree_sum<N>(w);
+        Sb += tree_sum<N>(fr);
+        tb += tree_sum<N>(wx);
     }
+    ones += rintf(Wb - Sb);
     S += Sb;
     t += tb;
 }
 
 template <typename DT, int NU, bool ARG>
-__device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, float &S, float &t, int &idx,
-                                            const Scale &sc)
+__device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, float &ones, float &S, float &t,
+                                            int &idx, const Scale &sc)
 {
     constexpr int N = VecOf<DT>::N;
     typename RawOf<DT>::type raw[NU];
@@ -265,8 +316,8 @@ __device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, flo
     for (int u = 0; u < NU; ++u) raw[u] = load_raw<DT>(row, (t0 + u) * WG + (int)threadIdx.x);
     float z[NU][N];
 #pragma unroll
-    for (int u = 0; u < NU; ++u) unpack(raw[u], z[u]);
-    accumulate<N, NU, ARG>(z, m, S, t, sc, idx, t0);
+    for (int u = 0; u < NU; ++u) unpack<DT>(raw[u], z[u]);
+    accumulate<N, NU, ARG>(z, m, ones, S, t, sc, idx, t0);
 }
 
 // LDS of one workgroup combination (each field is written once, so two barriers suffice).
@@ -276,12 +327,12 @@ struct CombineLds {
     double S[NWAVE], t[NWAVE];
 };
 
-// Workgroup combination of the per-thread (m, S, t): maximum first, then every thread
-// rescales to it and the sums are added in fp64.  Result valid in thread 0.  One call per
+// Workgroup combination of the per-thread (m, ones, S, t): maximum first, then every thread
+// rescales ones + S and t to it and the sums are added in fp64.  Result valid in thread 0.  One call per
 // kernel and LDS block.
 template <bool ARG = false>
-__device__ __forceinline__ Partial wg_combine(float m, float S, float t, const Scale &sc, CombineLds &lds,
-                                              int idx = -1)
+__device__ __forceinline__ Partial wg_combine(float m, float ones, float S, float t, const Scale &sc,
+                                              CombineLds &lds, int idx = -1)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const float mw = wave_max(m);
@@ -293,9 +344,9 @@ __device__ __forceinline__ Partial wg_combine(float m, float S, float t, const S
     double Sd = 0.0, td = 0.0;
     if (m != neg_inf()) {
         const float xd = scaled_diff(m, mg, sc);
-        const double f = (double)exp2_raw(xd);
-        Sd = f * (double)S;
-        td = f * ((double)t + (double)xd * (double)S);
+        const double f = (double)exp2_raw(xd), all = (double)ones + (double)S;      // exact in fp64
+        Sd = f * all;
+        td = f * ((double)t + (double)xd * all);
     }
     Sd = wave_sum(Sd);
     td = wave_sum(td);
@@ -342,20 +393,20 @@ __device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int
 {
     constexpr int N = VecOf<DT>::N, NB = 32 / N;
     const int tid = threadIdx.x;
-    float m = neg_inf(), S = 0.f, t = 0.f;
+    float m = neg_inf(), ones = 0.f, S = 0.f, t = 0.f;
     int idx = -1;
     const int fe = min(te, V / (WG * N));      // end of the tiles that are wholly inside the row
     int t0 = tb;
-    for (; t0 + NB <= fe; t0 += NB) stats_batch<DT, NB, ARG>(row, t0, m, S, t, idx, sc);
-    if (NB == 8 && t0 + 4 <= fe) { stats_batch<DT, 4, ARG>(row, t0, m, S, t, idx, sc); t0 += 4; }
-    if (t0 + 2 <= fe) { stats_batch<DT, 2, ARG>(row, t0, m, S, t, idx, sc); t0 += 2; }
-    if (t0 + 1 <= fe) { stats_batch<DT, 1, ARG>(row, t0, m, S, t, idx, sc); t0 += 1; }
+    for (; t0 + NB <= fe; t0 += NB) stats_batch<DT, NB, ARG>(row, t0, m, ones, S, t, idx, sc);
+    if (NB == 8 && t0 + 4 <= fe) { stats_batch<DT, 4, ARG>(row, t0, m, ones, S, t, idx, sc); t0 += 4; }
+    if (t0 + 2 <= fe) { stats_batch<DT, 2, ARG>(row, t0, m, ones, S, t, idx, sc); t0 += 2; }
+    if (t0 + 1 <= fe) { stats_batch<DT, 1, ARG>(row, t0, m, ones, S, t, idx, sc); t0 += 1; }
     if (t0 < te) {
         float z[1][N];
-        unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
-        accumulate<N, 1, ARG>(z, m, S, t, sc, idx, t0);
+        unpack<DT>(load_raw_checked(row, t0 * WG + tid, V), z[0]);
+        accumulate<N, 1, ARG>(z, m, ones, S, t, sc, idx, t0);
     }
-    return wg_combine<ARG>(m, S, t, sc, lds, idx);
+    return wg_combine<ARG>(m, ones, S, t, sc, lds, idx);
 }
 
 // ---- logsumexp only (statistics pass of verification) -----------------------------------------
@@ -400,7 +451,7 @@ __device__ __forceinline__ void lse_batch(const DT *row, int t0, float &m, float
     for (int u = 0; u < NU; ++u) raw[u] = load_raw<DT>(row, (t0 + u) * WG + (int)threadIdx.x);
     float z[NU][N];
 #pragma unroll
-    for (int u = 0; u < NU; ++u) unpack(raw[u], z[u]);
+    for (int u = 0; u < NU; ++u) unpack<DT>(raw[u], z[u]);
     accumulate_lse<N, NU>(z, m, ref, S, sc);
 }
 
@@ -423,7 +474,7 @@ __device__ __forceinline__ Partial slice_lse(const DT *row, int V, int tb, int t
     if (t0 + 1 <= fe) { lse_batch<DT, 1>(row, t0, m, ref, S, sc); t0 += 1; }
     if (t0 < te) {
         float z[1][N];
-        unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
+        unpack<DT>(load_raw_checked(row, t0 * WG + tid, V), z[0]);
         accumulate_lse<N, 1>(z, m, ref, S, sc);
     }
     // workgroup: largest reference first, then every thread rescales to it (a difference of two
@@ -473,7 +524,7 @@ __device__ __forceinline__ void argmax_batch(const DT *row, int t0, float &m, in
     for (int u = 0; u < NU; ++u) raw[u] = load_raw<DT>(row, (t0 + u) * WG + (int)threadIdx.x);
     float z[NU][N];
 #pragma unroll
-    for (int u = 0; u < NU; ++u) unpack(raw[u], z[u]);
+    for (int u = 0; u < NU; ++u) unpack<DT>(raw[u], z[u]);
     float mb = tree_max<N>(z[0]);
 #pragma unroll
     for (int u = 1; u < NU; ++u) mb = vmax(mb, tree_max<N>(z[u]));
@@ -501,7 +552,7 @@ __device__ __forceinline__ unsigned long long slice_argmax(const DT *row, int V,
     if (t0 + 1 <= fe) { argmax_batch<DT, 1>(row, t0, m, idx); t0 += 1; }
     if (t0 < te) {
         float z[1][N];
-        unpack(load_raw_checked(row, t0 * WG + tid, V), z[0]);
+        unpack<DT>(load_raw_checked(row, t0 * WG + tid, V), z[0]);
         const float mb = tree_max<N>(z[0]);
         // elements past the end of the row read as -inf: only take the tile if it beats what we have
         if (mb > m || (idx < 0 && t0 * WG * N + tid * N < V)) {

@@ -17,7 +17,7 @@ struct SoftmaxWeights {        // w_i = exp2(z_i c - L)
     __device__ __forceinline__ void weights(const Pack &pk, float (&w)[VecOf<DT>::N]) const
     {
         float z[VecOf<DT>::N];
-        unpack(pk, z);
+        unpack<DT>(pk, z);
 #pragma unroll
         for (int e = 0; e < VecOf<DT>::N; ++e) w[e] = ex(z[e]);
     }
@@ -46,8 +46,8 @@ struct ResidualWeights {       // w_i = max(0, p_i - q_i), normalised p and q
     __device__ __forceinline__ void weights(const Pack &pk, float (&w)[VecOf<DT>::N]) const
     {
         float zp[VecOf<DT>::N], zq[VecOf<DT>::N];
-        unpack(pk.p, zp);
-        unpack(pk.q, zq);
+        unpack<DT>(pk.p, zp);
+        unpack<DT>(pk.q, zq);
 #pragma unroll
         for (int e = 0; e < VecOf<DT>::N; ++e) w[e] = fmaxf(exp_p(zp[e]) - exp_q(zq[e]), 0.f);
     }
@@ -72,13 +72,13 @@ __device__ __forceinline__ void mass_batch(const DT *prow, const DT *qrow, int V
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
         float zp[N], pw[N];
-        unpack(rp[u], zp);
+        unpack<DT>(rp[u], zp);
 #pragma unroll
         for (int e = 0; e < N; ++e) pw[e] = ep(zp[e]);
         Pb += tree_sum<N>(pw);
         if (RESID) {
             float zq[N], w[N];
-            unpack(rq[u], zq);
+            unpack<DT>(rq[u], zq);
 #pragma unroll
             for (int e = 0; e < N; ++e) w[e] = fmaxf(pw[e] - eq(zq[e]), 0.f);
             Wb += tree_sum<N>(w);

@@ -95,6 +95,18 @@ static Scale make_scale(float temperature)
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+static bool dtype_ok(svip_dtype d) { return d == SVIP_F32 || d == SVIP_BF16 || d == SVIP_F16; }
+static int vec_of(svip_dtype d) { return d == SVIP_F32 ? 4 : 8; }       // logits per 16-byte vector
+
+// Calls f with a value of the storage type that d names (f is a generic lambda).
+template <typename F>
+static void by_dtype(svip_dtype d, F f)
+{
+    if (d == SVIP_BF16) f(bf16{});
+    else if (d == SVIP_F16) f(f16{});
+    else f(float{});
+}
+
 static svip_status check_launch()
 {
     return hipGetLastError() == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
@@ -112,11 +124,11 @@ static Profile g_prof;
 svip_status draft_step_call(const DraftCall &c)
 {
     if (!c.logits || (!c.greedy && !c.u_sample) || !c.token_out || !c.lse_out || !c.stop_out) return SVIP_ERR_NULL;
-    if (c.dtype != SVIP_F32 && c.dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (!dtype_ok(c.dtype)) return SVIP_ERR_DTYPE;
     if (c.B <= 0 || c.B > MAX_BATCH || c.V <= 0 || c.k_max < 1 || c.k_max > SVIP_MAX_K || c.step_j < 0 ||
         c.step_j >= c.k_max || c.io_stride < 1 || c.row_stride < c.V || (c.pos && c.pos_stride < c.V))
         return SVIP_ERR_SHAPE;
-    const int vec = c.dtype == SVIP_BF16 ? 8 : 4;
+    const int vec = vec_of(c.dtype);
     if (!aligned16(c.logits) || c.row_stride % vec != 0 || (c.pos && c.pos_stride % vec != 0)) return SVIP_ERR_ALIGN;
     if (!(c.temperature > 0.f) || !isfinite(c.temperature) || !(c.h >= 0.f)) return SVIP_ERR_PARAM;
 
@@ -149,30 +161,29 @@ svip_status draft_step_call(const DraftCall &c)
     a.part = w.part;
     hipStream_t st = static_cast<hipStream_t>(c.stream);
     const dim3 grid((unsigned)a.geo.ns * (unsigned)c.B);
-    if (c.greedy) {
-        if (c.dtype == SVIP_BF16) hipLaunchKernelGGL((k_draft_stats<bf16, true>), grid, dim3(WG), 0, st, a);
-        else hipLaunchKernelGGL((k_draft_stats<float, true>), grid, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_draft_finish_greedy, dim3(c.B), dim3(64), 0, st, a);
-    } else if (c.dtype == SVIP_BF16) {
-        hipLaunchKernelGGL((k_draft_stats<bf16, false>), grid, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_draft_finish<bf16>, dim3(c.B), dim3(WG), 0, st, a);
-    } else {
-        hipLaunchKernelGGL((k_draft_stats<float, false>), grid, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_draft_finish<float>, dim3(c.B), dim3(WG), 0, st, a);
-    }
+    by_dtype(c.dtype, [&](auto tag) {
+        using DT = decltype(tag);
+        if (c.greedy) {
+            hipLaunchKernelGGL((k_draft_stats<DT, true>), grid, dim3(WG), 0, st, a);
+            hipLaunchKernelGGL(k_draft_finish_greedy, dim3(c.B), dim3(64), 0, st, a);
+        } else {
+            hipLaunchKernelGGL((k_draft_stats<DT, false>), grid, dim3(WG), 0, st, a);
+            hipLaunchKernelGGL(k_draft_finish<DT>, dim3(c.B), dim3(WG), 0, st, a);
+        }
+    });
     return check_launch();
 }
 
 static svip_status verify_greedy_call(const VerifyCall &c)
 {
     if (!c.target || !c.draft_tokens || !c.draft_len || !c.n_accepted_out || !c.next_token_out) return SVIP_ERR_NULL;
-    if (c.dtype != SVIP_F32 && c.dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (!dtype_ok(c.dtype)) return SVIP_ERR_DTYPE;
     if (c.B <= 0 || c.B > MAX_BATCH || c.V <= 0 || c.k_max < 1 || c.k_max > SVIP_MAX_K || c.row_stride < c.V ||
         c.seq_stride_t < (long long)c.k_max * c.row_stride + c.V)
         return SVIP_ERR_SHAPE;
     const long long rows = (long long)c.B * (c.k_max + 1);
     if (rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;
-    const int vec = c.dtype == SVIP_BF16 ? 8 : 4;
+    const int vec = vec_of(c.dtype);
     if (!aligned16(c.target) || c.row_stride % vec != 0 || c.seq_stride_t % vec != 0) return SVIP_ERR_ALIGN;
     GreedyArgs a;
     a.geo = make_geo(c.V, vec, rows, false, env_int("SVIP_VERIFY_SLICES", 0));
@@ -195,8 +206,7 @@ static svip_status verify_greedy_call(const VerifyCall &c)
     a.flags = w.flags;
     hipStream_t st = static_cast<hipStream_t>(c.stream);
     const dim3 grid((unsigned)(rows * a.geo.ns));
-    if (c.dtype == SVIP_BF16) hipLaunchKernelGGL(k_argmax<bf16>, grid, dim3(WG), 0, st, a);
-    else hipLaunchKernelGGL(k_argmax<float>, grid, dim3(WG), 0, st, a);
+    by_dtype(c.dtype, [&](auto tag) { hipLaunchKernelGGL(k_argmax<decltype(tag)>, grid, dim3(WG), 0, st, a); });
     hipLaunchKernelGGL(k_accept_greedy, dim3(c.B), dim3(64), 0, st, a);
     return check_launch();
 }
@@ -207,7 +217,7 @@ svip_status verify_call(const VerifyCall &c)
     if (!c.target || !c.draft || !c.draft_tokens || !c.draft_len || !c.u_accept || !c.u_resample ||
         !c.n_accepted_out || !c.next_token_out)
         return SVIP_ERR_NULL;
-    if (c.dtype != SVIP_F32 && c.dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (!dtype_ok(c.dtype)) return SVIP_ERR_DTYPE;
     if (c.B <= 0 || c.B > MAX_BATCH || c.V <= 0 || c.k_max < 1 || c.k_max > SVIP_MAX_K || c.row_stride < c.V ||
         c.seq_stride_t < (long long)c.k_max * c.row_stride + c.V ||
         c.seq_stride_d < (long long)(c.k_max - 1) * c.row_stride + c.V)
@@ -215,7 +225,7 @@ svip_status verify_call(const VerifyCall &c)
     const int kd = c.draft_lse ? 0 : c.k_max;
     const long long stat_rows = (long long)c.B * (kd + c.k_max + 1);
     if (stat_rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;          // workgroups of the statistics pass
-    const int vec = c.dtype == SVIP_BF16 ? 8 : 4;
+    const int vec = vec_of(c.dtype);
     if (!aligned16(c.target) || !aligned16(c.draft) || c.row_stride % vec != 0 || c.seq_stride_t % vec != 0 ||
         c.seq_stride_d % vec != 0)
         return SVIP_ERR_ALIGN;
@@ -252,21 +262,17 @@ svip_status verify_call(const VerifyCall &c)
     const dim3 g_stats((unsigned)(stat_rows * a.geo.ns)), g_mass((unsigned)a.geo_s.ns * (unsigned)c.B);
     const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
     if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], st);
-    if (c.dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a);
-    else hipLaunchKernelGGL(k_verify_stats<float>, g_stats, dim3(WG), 0, st, a);
+    by_dtype(c.dtype, [&](auto tag) { hipLaunchKernelGGL(k_verify_stats<decltype(tag)>, g_stats, dim3(WG), 0, st, a); });
     if (timed) {
         (void)hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st);
         ++g_prof.used;
     }
-    if (c.dtype == SVIP_BF16) {
-        hipLaunchKernelGGL(k_accept<bf16>, dim3(c.B), dim3(64), 0, st, a);
-        hipLaunchKernelGGL(k_resid_mass<bf16>, g_mass, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_resid_finish<bf16>, dim3(c.B), dim3(WG), 0, st, a);
-    } else {
-        hipLaunchKernelGGL(k_accept<float>, dim3(c.B), dim3(64), 0, st, a);
-        hipLaunchKernelGGL(k_resid_mass<float>, g_mass, dim3(WG), 0, st, a);
-        hipLaunchKernelGGL(k_resid_finish<float>, dim3(c.B), dim3(WG), 0, st, a);
-    }
+    by_dtype(c.dtype, [&](auto tag) {
+        using DT = decltype(tag);
+        hipLaunchKernelGGL(k_accept<DT>, dim3(c.B), dim3(64), 0, st, a);
+        hipLaunchKernelGGL(k_resid_mass<DT>, g_mass, dim3(WG), 0, st, a);
+        hipLaunchKernelGGL(k_resid_finish<DT>, dim3(c.B), dim3(WG), 0, st, a);
+    });
     return check_launch();
 }
 
@@ -384,14 +390,14 @@ svip_status svip_pair_stats(const void *target_logits, const void *draft_logits,
                             size_t workspace_bytes, void *hip_stream)
 {
     if (!target_logits || !draft_logits || !draft_len || !stats_out) return SVIP_ERR_NULL;
-    if (dtype != SVIP_F32 && dtype != SVIP_BF16) return SVIP_ERR_DTYPE;
+    if (!dtype_ok(dtype)) return SVIP_ERR_DTYPE;
     if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K || row_stride < V ||
         seq_stride_t < (long long)(k_max - 1) * row_stride + V || seq_stride_d < (long long)(k_max - 1) * row_stride + V)
         return SVIP_ERR_SHAPE;
     const int kd = draft_lse ? 0 : k_max;
     const long long stat_rows = (long long)B * (kd + k_max + 1), pos = (long long)B * k_max;
     if (stat_rows * MAX_SLICES > 0x7FFFFFFFLL) return SVIP_ERR_SHAPE;
-    const int vec = dtype == SVIP_BF16 ? 8 : 4;
+    const int vec = vec_of(dtype);
     if (!aligned16(target_logits) || !aligned16(draft_logits) || row_stride % vec != 0 ||
         seq_stride_t % vec != 0 || seq_stride_d % vec != 0)
         return SVIP_ERR_ALIGN;
@@ -435,11 +441,9 @@ svip_status svip_pair_stats(const void *target_logits, const void *draft_logits,
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 g_stats((unsigned)(stat_rows * a.v.geo.ns)), g_pos((unsigned)((pos + 63) / 64)),
         g_sums((unsigned)(pos * a.geo2.ns));
-    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_verify_stats<bf16>, g_stats, dim3(WG), 0, st, a.v);
-    else hipLaunchKernelGGL(k_verify_stats<float>, g_stats, dim3(WG), 0, st, a.v);
+    by_dtype(dtype, [&](auto tag) { hipLaunchKernelGGL(k_verify_stats<decltype(tag)>, g_stats, dim3(WG), 0, st, a.v); });
     hipLaunchKernelGGL(k_pair_L, g_pos, dim3(64), 0, st, a);
-    if (dtype == SVIP_BF16) hipLaunchKernelGGL(k_pair_sums<bf16>, g_sums, dim3(WG), 0, st, a);
-    else hipLaunchKernelGGL(k_pair_sums<float>, g_sums, dim3(WG), 0, st, a);
+    by_dtype(dtype, [&](auto tag) { hipLaunchKernelGGL(k_pair_sums<decltype(tag)>, g_sums, dim3(WG), 0, st, a); });
     hipLaunchKernelGGL(k_pair_finish, g_pos, dim3(64), 0, st, a);
     return check_launch();
 }

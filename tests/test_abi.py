@@ -76,7 +76,7 @@ def test_host_checks_reject_before_any_gpu_call():
 
     assert verify(t=None) == 1 and verify(d=None) == 1 and verify(tok=None) == 1 and verify(dl=None) == 1
     assert verify(ua=None) == 1 and verify(ur=None) == 1 and verify(na=None) == 1 and verify(nt=None) == 1
-    assert verify(dtype=2) == 3
+    assert verify(dtype=3) == 3
     assert verify(B=0) == 2 and verify(k=0) == 2 and verify(V=0) == 2 and verify(st_t=4 * V) == 2
     assert verify(st_d=2 * V) == 2 and verify(rs=V - 8) == 2 and verify(B=(1 << 20) + 1) == 2
     assert verify(t=p + 8) == 4 and verify(rs=V + 4, st_t=5 * (V + 4), st_d=4 * (V + 4)) == 4

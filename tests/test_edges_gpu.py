@@ -35,12 +35,12 @@ def _make(B, k, V, dtype, seed, scale=2.0, noise=1.0):
     return draft, target, u[0], u[1], u[2][:, 0].contiguous()
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("V", [1, 2, 5, 8, 9, 1023, 2049, 4097, 16385, 40003])
 def test_ragged_vocab_sizes(svip, V, dtype):
     """V that is not a multiple of the vector, the tile or the slice; padding is poisoned."""
     B, k = 3, 4
-    mult = 8 if dtype == torch.bfloat16 else 4
+    mult = 4 if dtype == torch.float32 else 8
     draft, target, us, ua, ur = _make(B, k, V, dtype, seed=V)
     r = Round(svip, draft, target, us, ua, ur, 1.0, 1.5)
     r.draft = _padded(draft, dtype, mult)
@@ -60,7 +60,7 @@ def test_long_rows_take_several_sampler_batches(svip, dtype, V):
     """Rows longer than 64 slices x 8 tiles: the sampler scans more than one batch per slice."""
     B, k = 2, 2
     draft, target, us, ua, ur = _make(B, k, V, dtype, seed=5, scale=1.0)
-    mult = 8 if dtype == torch.bfloat16 else 4
+    mult = 4 if dtype == torch.float32 else 8
     r = Round(svip, draft, target, us, ua, ur, 1.0, 3.0)
     r.draft = _padded(draft, dtype, mult)
     r.target = _padded(target, dtype, mult)
@@ -94,7 +94,7 @@ def test_masked_vocab_and_degenerate_rows(svip):
     us, ua, ur = u[0], u[1], u[2][:, 0].contiguous()
     us[0, 0] = 0.0
     us[0, 3] = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
-    for dtype in (torch.float32, torch.bfloat16):
+    for dtype in (torch.float32, torch.bfloat16, torch.float16):
         d, t = draft.to(dtype), target.to(dtype)
         r = Round(svip, d, t, us, ua, ur, 1.0, 0.3)
         r.draft_all(chain=False)
@@ -224,7 +224,7 @@ def test_large_batch_of_short_rows(svip):
     _say(f"B={B}: chain {st} verify {sv}")
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 def test_small_entropies_keep_their_relative_accuracy(svip, dtype):
     """Confident rows: one logit far above the rest, H from 5e-2 down to 1e-8.  The row maximum has
     weight exactly 1 on the GPU, so the entropy comes from the tail alone and stays accurate to REL."""

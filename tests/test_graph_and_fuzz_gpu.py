@@ -75,7 +75,7 @@ def test_graph_replays_match_eager_runs(svip):
 
 
 def _case(rng):
-    dtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+    dtype = [torch.bfloat16, torch.float32, torch.float16][int(rng.integers(0, 3))]
     B = int(rng.integers(1, 9))
     k = int(rng.integers(1, 7))
     V = int(rng.choice([3, 17, 255, 1000, 2048, 2049, 6007, 12288, 33000]))
@@ -104,7 +104,7 @@ def test_seeded_shapes_round(svip, seed):
         target[:, :, mask] = float("-inf")
     us, ua = torch.rand(B, k, generator=g), torch.rand(B, k, generator=g)
     ur = torch.rand(B, generator=g)
-    mult = 8 if dtype == torch.bfloat16 else 4
+    mult = 4 if dtype == torch.float32 else 8
     Vp = (V + mult - 1) // mult * mult
 
     def padded(x):

@@ -97,7 +97,8 @@ def test_greedy_draft_step_matches_oracle(svip, name, rows):
 
 @pytest.mark.parametrize("V,dtype", [(1, torch.float32), (5, torch.bfloat16), (2047, torch.bfloat16),
                                      (2049, torch.bfloat16), (4100, torch.float32), (32003, torch.float32),
-                                     (50257, torch.bfloat16), (262147, torch.bfloat16)])
+                                     (50257, torch.bfloat16), (262147, torch.bfloat16), (4100, torch.float16),
+                                     (50257, torch.float16)])
 def test_greedy_ties_and_ragged_vocab(svip, V, dtype):
     """Equal maxima anywhere in the row (bf16 rows have many): the smallest index wins, in the
     draft step and in verification; ragged V exercises the checked last tile."""

@@ -115,7 +115,7 @@ def test_pair_stats_match_oracle(svip, name, rows, over, lse_mode):
     assert st["n"] == int(glen.sum())
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("V", [1, 2, 9, 1023, 2049, 4097, 40003, 262147])
 def test_pair_stats_ragged_vocab(svip, V, dtype):
     gen = torch.Generator().manual_seed(300 + V)
