@@ -49,7 +49,7 @@ static int env_int(const char *name, int dflt)
 
 // Slices per row: enough workgroups to fill 256 CUs several times over, at most MAX_SLICES,
 // and (want_one_batch) slices of at most LOCATE_UNROLL tiles so the sampler scans one batch.
-static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int forced_ns)
+static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int forced_ns, int min_tiles = 4)
 {
     Geo g;
     g.V = V;
@@ -58,7 +58,7 @@ static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int for
     long long ns;
     if (want_one_batch) {
         ns = (2048 + rows - 1) / rows;                // aim at >= 2048 workgroups ...
-        if (ns * 4 > g.ntiles) ns = g.ntiles / 4;     // ... of at least 4 tiles each
+        if (ns * min_tiles > g.ntiles) ns = g.ntiles / min_tiles;      // ... of at least min_tiles tiles each
         const long long need = (g.ntiles + LOCATE_UNROLL - 1) / LOCATE_UNROLL;
         if (ns < need) ns = need;
         // large batches are bound by bandwidth, not by latency: longer slices of an odd number of
@@ -233,7 +233,8 @@ svip_status verify_call(const VerifyCall &c)
 
     VerifyArgs a;
     a.geo = make_geo(c.V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    a.geo_s = make_geo(c.V, vec, c.B, true, env_int("SVIP_SAMPLE_SLICES", 0));
+    // the residual pass reads two rows per slice: half as many tiles per slice as the draft step
+    a.geo_s = make_geo(c.V, vec, c.B, true, env_int("SVIP_SAMPLE_SLICES", 0), 2);
     const size_t need = HEADER_BYTES + ws_rec_bytes(c.B) + ws_mass_bytes(c.B) +
                         (size_t)stat_rows * a.geo.ns * sizeof(Partial);
     if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
