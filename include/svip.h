@@ -81,6 +81,19 @@ const char *svip_status_string(int status);
  * to k_max draft positions over a vocabulary of V.  Pure host function; 0 on bad arguments. */
 size_t svip_workspace_bytes(int B, int k_max, int V);
 
+/* Bytes of workspace one particular call uses for these sizes (pure host function; 0 on bad
+ * arguments).  svip_workspace_bytes(B, k_max, V) is never smaller than any of them; the calls
+ * themselves check against these figures. */
+typedef enum {
+    SVIP_CALL_DRAFT_STEP = 0,            /* svip_draft_step, svip_draft_step_greedy */
+    SVIP_CALL_VERIFY = 1,                /* svip_verify with draft_lse given */
+    SVIP_CALL_VERIFY_RECOMPUTE = 2,      /* svip_verify with draft_lse == NULL */
+    SVIP_CALL_VERIFY_GREEDY = 3,         /* svip_verify_greedy */
+    SVIP_CALL_PAIR_STATS = 4,            /* svip_pair_stats with draft_lse given */
+    SVIP_CALL_PAIR_STATS_RECOMPUTE = 5   /* svip_pair_stats with draft_lse == NULL */
+} svip_call;
+size_t svip_workspace_needed(int call, svip_dtype dtype, int B, int k_max, int V);
+
 /* Zero the sticky flag word (enqueued on the stream).  Call once after allocating a
  * workspace; the two calls below only ever set bits. */
 svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream);

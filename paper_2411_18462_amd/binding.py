@@ -16,7 +16,7 @@ FLAG_BAD_DRAFT_LEN = 2
 _DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 
 # every symbol include/svip.h declares
-EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_reset",
+EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_needed", "svip_workspace_reset",
            "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_draft_step_greedy",
            "svip_verify_greedy", "svip_pair_stats", "svip_loop_workspace_bytes", "svip_loop_init", "svip_loop_run",
            "svip_profile_begin", "svip_profile_end")
@@ -73,6 +73,8 @@ def load():
     lib.svip_verify_greedy.argtypes = [vp, i, i, i, i, ll, ll, vp, vp, vp, vp, vp, sz, vp]
     lib.svip_pair_stats.restype = i
     lib.svip_pair_stats.argtypes = [vp, vp, i, i, i, i, ll, ll, ll, f, vp, vp, f, vp, vp, sz, vp]
+    lib.svip_workspace_needed.restype = sz
+    lib.svip_workspace_needed.argtypes = [i, i, i, i, i]
     lib.svip_loop_workspace_bytes.restype = sz
     lib.svip_loop_workspace_bytes.argtypes = [i, i, i]
     lib.svip_loop_init.restype = i
@@ -122,6 +124,11 @@ def _col(t, B, dtype, name, stride=None):
 
 def workspace_bytes(B: int, k_max: int, V: int) -> int:
     return int(load().svip_workspace_bytes(B, k_max, V))
+
+
+def workspace_needed(call: int, dtype, B: int, k_max: int, V: int) -> int:
+    """svip_workspace_needed; dtype a torch dtype, call one of the SVIP_CALL_* numbers (0..5)."""
+    return int(load().svip_workspace_needed(int(call), _DTYPES[dtype], B, k_max, V))
 
 
 def new_workspace(B: int, k_max: int, V: int, device="cuda", stream=None) -> torch.Tensor:

@@ -119,6 +119,37 @@ struct Profile {
 };
 static Profile g_prof;
 
+// ---- workspace each call needs (its own geometry; svip_workspace_bytes bounds them all) -------
+
+static size_t need_draft(int B, int V, int vec)
+{
+    const Geo g = make_geo(V, vec, B, true, env_int("SVIP_DRAFT_SLICES", 0));
+    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + (size_t)B * g.ns * sizeof(Partial);
+}
+static size_t need_verify_greedy(int B, int k, int V, int vec)
+{
+    const long long rows = (long long)B * (k + 1);
+    const Geo g = make_geo(V, vec, rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + (size_t)rows * g.ns * sizeof(unsigned long long);
+}
+static size_t need_verify(int B, int k, int V, int vec, bool recompute_lse)
+{
+    const long long stat_rows = (long long)B * ((recompute_lse ? k : 0) + k + 1);
+    const Geo g = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + (size_t)stat_rows * g.ns * sizeof(Partial);
+}
+static size_t need_pair(int B, int k, int V, int vec, bool recompute_lse, size_t *part_bytes, size_t *L_bytes)
+{
+    const long long stat_rows = (long long)B * ((recompute_lse ? k : 0) + k + 1), pos = (long long)B * k;
+    const Geo g = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    const Geo g2 = make_geo(V, vec, pos, false, env_int("SVIP_PAIR_SLICES", 0));
+    const size_t pb = align256((size_t)stat_rows * g.ns * sizeof(Partial));
+    const size_t lb = align256((size_t)pos * 2 * sizeof(double));
+    if (part_bytes) *part_bytes = pb;
+    if (L_bytes) *L_bytes = lb;
+    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + pb + lb + (size_t)pos * g2.ns * 3 * sizeof(double);
+}
+
 // ---- the calls behind the entry points ---------------------------------------------------------
 
 svip_status draft_step_call(const DraftCall &c)
@@ -134,8 +165,7 @@ svip_status draft_step_call(const DraftCall &c)
 
     DraftArgs a;
     a.geo = make_geo(c.V, vec, c.B, true, env_int("SVIP_DRAFT_SLICES", 0));
-    const size_t need = HEADER_BYTES + ws_rec_bytes(c.B) + ws_mass_bytes(c.B) +
-                        (size_t)c.B * a.geo.ns * sizeof(Partial);
+    const size_t need = need_draft(c.B, c.V, vec);
     if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
         return SVIP_ERR_WORKSPACE;
     const Workspace w = carve(c.workspace, c.B);
@@ -187,8 +217,7 @@ static svip_status verify_greedy_call(const VerifyCall &c)
     if (!aligned16(c.target) || c.row_stride % vec != 0 || c.seq_stride_t % vec != 0) return SVIP_ERR_ALIGN;
     GreedyArgs a;
     a.geo = make_geo(c.V, vec, rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    const size_t need = HEADER_BYTES + ws_rec_bytes(c.B) + ws_mass_bytes(c.B) +
-                        (size_t)rows * a.geo.ns * sizeof(unsigned long long);
+    const size_t need = need_verify_greedy(c.B, c.k_max, c.V, vec);
     if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
         return SVIP_ERR_WORKSPACE;
     const Workspace w = carve(c.workspace, c.B);
@@ -235,8 +264,7 @@ svip_status verify_call(const VerifyCall &c)
     a.geo = make_geo(c.V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
     // the residual pass reads two rows per slice: half as many tiles per slice as the draft step
     a.geo_s = make_geo(c.V, vec, c.B, true, env_int("SVIP_SAMPLE_SLICES", 0), 2);
-    const size_t need = HEADER_BYTES + ws_rec_bytes(c.B) + ws_mass_bytes(c.B) +
-                        (size_t)stat_rows * a.geo.ns * sizeof(Partial);
+    const size_t need = need_verify(c.B, c.k_max, c.V, vec, kd != 0);
     if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
         return SVIP_ERR_WORKSPACE;
     a.target = c.target;
@@ -311,6 +339,21 @@ size_t svip_workspace_bytes(int B, int k_max, int V)
     const size_t pos = (size_t)B * (size_t)k_max;
     return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + align256(parts * sizeof(Partial)) +
            align256(pos * 2 * sizeof(double)) + align256((pos + 8192) * 3 * sizeof(double));
+}
+
+size_t svip_workspace_needed(int call, svip_dtype dtype, int B, int k_max, int V)
+{
+    if (!dtype_ok(dtype) || B <= 0 || B > MAX_BATCH || k_max < 1 || k_max > SVIP_MAX_K || V <= 0) return 0;
+    const int vec = vec_of(dtype);
+    switch (call) {
+        case SVIP_CALL_DRAFT_STEP: return need_draft(B, V, vec);
+        case SVIP_CALL_VERIFY: return need_verify(B, k_max, V, vec, false);
+        case SVIP_CALL_VERIFY_RECOMPUTE: return need_verify(B, k_max, V, vec, true);
+        case SVIP_CALL_VERIFY_GREEDY: return need_verify_greedy(B, k_max, V, vec);
+        case SVIP_CALL_PAIR_STATS: return need_pair(B, k_max, V, vec, false, nullptr, nullptr);
+        case SVIP_CALL_PAIR_STATS_RECOMPUTE: return need_pair(B, k_max, V, vec, true, nullptr, nullptr);
+        default: return 0;
+    }
 }
 
 svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -408,10 +451,8 @@ svip_status svip_pair_stats(const void *target_logits, const void *draft_logits,
     a.v.geo = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
     a.v.geo_s = a.v.geo;
     a.geo2 = make_geo(V, vec, pos, false, env_int("SVIP_PAIR_SLICES", 0));
-    const size_t part_bytes = align256((size_t)stat_rows * a.v.geo.ns * sizeof(Partial));
-    const size_t L_bytes = align256((size_t)pos * 2 * sizeof(double));
-    const size_t need = HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + part_bytes + L_bytes +
-                        (size_t)pos * a.geo2.ns * 3 * sizeof(double);
+    size_t part_bytes, L_bytes;
+    const size_t need = need_pair(B, k_max, V, vec, kd != 0, &part_bytes, &L_bytes);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
         return SVIP_ERR_WORKSPACE;
     a.v.target = target_logits;

@@ -151,3 +151,28 @@ def test_host_checks_of_the_greedy_diagnostic_and_loop_calls():
     assert loop(seq_stride=19 * V) == (2, 2) and loop(out_stride=11) == (2, 2) and loop(rounds=0) == (2, 2)
     assert loop(gamma_inc=-1) == (6, 6) and loop(check_every=-1) == (6, 6)
     assert loop(workspace=None) == (5, 5) and loop(workspace_bytes=wsb) == (5, 5)
+
+
+def test_workspace_bytes_covers_every_call_for_every_shape():
+    """svip_workspace_bytes(B, k_max, V) must be enough for whatever slicing each call chooses."""
+    import itertools
+    import torch
+    lib = svip.load()
+    Bs = [1, 2, 3, 7, 16, 64, 100, 256, 1000, 4096, 1 << 20]
+    ks = [1, 2, 5, 16, 40, 64, 100, 1024]
+    Vs = [1, 2, 9, 255, 2048, 2049, 16384, 32000, 50257, 128256, 151936, 262147, 1 << 20]
+    worst = 0.0
+    for B, k, V in itertools.product(Bs, ks, Vs):
+        if B * k > (1 << 22):
+            continue
+        total = svip.workspace_bytes(B, k, V)
+        assert total > 0 and total % 256 == 0
+        for dtype in (torch.float32, torch.bfloat16, torch.float16):
+            for call in range(6):
+                need = svip.workspace_needed(call, dtype, B, k, V)
+                assert 0 < need <= total, (call, dtype, B, k, V, need, total)
+                worst = max(worst, need / total)
+    assert worst > 0.5                                    # the bound is not wildly loose either
+    assert lib.svip_workspace_needed(9, 1, 4, 4, 64) == 0 and lib.svip_workspace_needed(0, 7, 4, 4, 64) == 0
+    assert lib.svip_workspace_needed(0, 1, 0, 4, 64) == 0
+    assert lib.svip_loop_workspace_bytes(8, 40, 151936) > svip.workspace_bytes(8, 40, 151936)
