@@ -176,3 +176,17 @@ def test_workspace_bytes_covers_every_call_for_every_shape():
     assert lib.svip_workspace_needed(9, 1, 4, 4, 64) == 0 and lib.svip_workspace_needed(0, 7, 4, 4, 64) == 0
     assert lib.svip_workspace_needed(0, 1, 0, 4, 64) == 0
     assert lib.svip_loop_workspace_bytes(8, 40, 151936) > svip.workspace_bytes(8, 40, 151936)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/svip.h must compile as C99 on its own (the boundary is a C ABI)."""
+    import subprocess
+    src = tmp_path / "use_svip.c"
+    src.write_text('#include "svip.h"\n'
+                   "int main(void) {\n"
+                   "    svip_loop_config c;\n"
+                   "    (void)c;\n"
+                   "    return (int)svip_workspace_bytes(0, 0, 0) + (SVIP_PAIR_NSTAT == 8 ? 0 : 1) + (int)SVIP_CALL_PAIR_STATS - 4;\n"
+                   "}\n")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           "-c", str(src), "-o", str(tmp_path / "use_svip.o")])
