@@ -300,9 +300,10 @@ svip_status svip_loop_run(const svip_loop_config *config /* host */, int first_r
 
 /*
  * Timing hook for benchmarks: between svip_profile_begin and svip_profile_end every
- * svip_verify call brackets its statistics kernel (the pass that streams the target rows,
- * the dominant kernel of the path) with HIP events on the call's stream, for at most
- * max_samples calls.  svip_profile_end waits for those events, returns the summed kernel
+ * svip_verify call launches its statistics kernel (the pass that streams the target rows,
+ * the dominant kernel of the path) with a start and a stop HIP event attached to the launch
+ * (hipExtLaunchKernel), which take the kernel's own begin and end on the call's stream, for at
+ * most max_samples calls.  svip_profile_end waits for those events, returns the summed kernel
  * time in milliseconds and the number of samples through host pointers, and releases the
  * events.  Process-wide state: not for concurrent use from several threads.
  */

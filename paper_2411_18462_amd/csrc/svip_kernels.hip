@@ -20,6 +20,7 @@
 // each small kernel issues all of its independent loads before the first dependent one, because
 // at small batches a step is bound by round trips to memory rather than by bandwidth.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -290,11 +291,14 @@ svip_status verify_call(const VerifyCall &c)
     hipStream_t st = static_cast<hipStream_t>(c.stream);
     const dim3 g_stats((unsigned)(stat_rows * a.geo.ns)), g_mass((unsigned)a.geo_s.ns * (unsigned)c.B);
     const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
-    if (timed) (void)hipEventRecord(g_prof.ev[2 * g_prof.used], st);
-    by_dtype(c.dtype, [&](auto tag) { hipLaunchKernelGGL(k_verify_stats<decltype(tag)>, g_stats, dim3(WG), 0, st, a); });
-    if (timed) {
-        (void)hipEventRecord(g_prof.ev[2 * g_prof.used + 1], st);
+    if (timed) {        // the launch itself carries the two events: they take the kernel's own start and end
+        hipEvent_t e0 = g_prof.ev[2 * g_prof.used], e1 = g_prof.ev[2 * g_prof.used + 1];
+        by_dtype(c.dtype, [&](auto tag) {
+            hipExtLaunchKernelGGL(k_verify_stats<decltype(tag)>, g_stats, dim3(WG), 0, st, e0, e1, 0, a);
+        });
         ++g_prof.used;
+    } else {
+        by_dtype(c.dtype, [&](auto tag) { hipLaunchKernelGGL(k_verify_stats<decltype(tag)>, g_stats, dim3(WG), 0, st, a); });
     }
     by_dtype(c.dtype, [&](auto tag) {
         using DT = decltype(tag);
