@@ -168,3 +168,33 @@ def test_pair_stats_full_size(svip):
     _say(f"  {st}")
     # properties that hold for every position: both lower bounds stay below beta
     assert (g[..., 0] >= g[..., 4] - 1e-4).all() and (g[..., 0] >= g[..., 5] - 1e-4).all()
+
+
+def test_pair_stats_and_greedy_are_bitwise_deterministic(svip):
+    """Same inputs, different workspaces and a busy device in between: identical bits (no floating-point
+    atomics, fixed combine order)."""
+    w = si.workload("cfg2")
+    d = si.gen_batch(w, seed=8)
+    B, k, V = d["draft"].shape
+    zq, zp = d["draft"].cuda(), d["target"].cuda()
+    glen = torch.full((B,), k, dtype=torch.int32).cuda()
+    outs = []
+    for rep in range(3):
+        stats = torch.empty(B, k, svip.PAIR_NSTAT, device="cuda")
+        svip.pair_stats(zp, zq, temperature=0.9, draft_len=glen, c=0.2, stats_out=stats, workspace=svip.new_workspace(B, k, V))
+        tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+        ent = torch.zeros(B, device="cuda")
+        lse = torch.zeros(B, dtype=torch.float64, device="cuda")
+        stop = torch.zeros(B, dtype=torch.uint8, device="cuda")
+        svip.draft_step(zq[:, 3], greedy=True, temperature=0.9, h=1.0, step_j=3, k_max=k, token_out=tok,
+                        entropy_out=ent, lse_out=lse, stop_out=stop, workspace=svip.new_workspace(B, k, V))
+        na = torch.zeros(B, dtype=torch.int32, device="cuda")
+        nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+        svip.verify_greedy(zp, draft_tokens=torch.zeros(B, k, dtype=torch.int32, device="cuda"), draft_len=glen,
+                           n_accepted_out=na, next_token_out=nx, workspace=svip.new_workspace(B, k, V))
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (stats, tok, ent, lse, stop, na, nx)])
+        torch.randn(1 << 22, device="cuda").sum().item()
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
