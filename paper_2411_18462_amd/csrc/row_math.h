@@ -1,15 +1,17 @@
 // Per-row building blocks of the SVIP kernels: 128-bit logit loads, the scaled exponential,
 // streaming softmax statistics of a row slice, and the in-slice inverse-CDF search.
 //
-// Geometry.  A row of V logits is cut into vectors of 16 bytes (8 bf16 / 4 fp32), tiles of
+// Geometry.  A row of V logits is cut into vectors of 16 bytes (8 bf16 or fp16 / 4 fp32), tiles of
 // WG consecutive vectors (one per thread, so a wave reads 1 KiB contiguous), and `ns` slices
 // of `tps` consecutive tiles.  One workgroup handles one slice of one row.
 //
-// Arithmetic.  With c = log2(e)/T split into fp32 hi + lo parts, a logit z contributes
-// exp2((z - m) * c) relative to a reference m (statistics) or exp2(z * c - L) with
-// L = logsumexp * log2(e) (probabilities).  Both products use the hi/lo split so that the
-// rounding of c does not bias every term of a row in the same direction.  Per-element work
-// is fp32 (v_exp_f32); everything that combines partial sums is fp64.
+// Arithmetic.  With c = log2(e)/T split into two fp32 parts, a logit z contributes
+// exp2((z - m) * c) relative to the running maximum m (draft statistics: the subtraction comes
+// first, so the maximum has weight exactly 1), exp2(z * c - ref) relative to a reference next to
+// m * c (the logsumexp-only pass of verification, two fused multiply-adds per logit), or
+// exp2(z * c - L) with L = logsumexp * log2(e) (probabilities).  The split keeps the rounding of c
+// from biasing every term of a row in the same direction.  Per-element work is fp32 (v_exp_f32);
+// everything that combines partial sums is fp64.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>

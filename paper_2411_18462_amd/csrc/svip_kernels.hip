@@ -4,7 +4,7 @@
 // svip_draft_step  =  k_draft_stats    grid (slices, rows)       per-slice (m, S, t) of every active row
 //                     k_draft_finish   grid (rows)               merge, entropy, stop test, inverse CDF
 //   (greedy)          k_draft_stats<ARG> + k_draft_finish_greedy     token = first maximum, no search
-// svip_verify      =  k_verify_stats   grid (slices, stat rows)  per-slice (m, S) of every needed row
+// svip_verify      =  k_verify_stats   grid (slices, stat rows)  per-slice (reference, sum) of every needed row
 //                     k_accept         grid (sequences), 1 wave  p/q test, ballot scan for the first rejection
 //                     k_resid_mass     grid (slices, sequences)  slice masses of the residual / bonus row
 //                     k_resid_finish   grid (sequences)          inverse CDF of the residual / bonus row
