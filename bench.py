@@ -43,6 +43,8 @@ def parse():
                     help="sequences in the oracle sample (0 = four batches of the workload, ~15 s of CPU work)")
     ap.add_argument("--headline-only", action="store_true",
                     help="only the timed headline region (used for the rocprofv3 summaries under profiles/)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline: a table over batch sizes, vocabularies and draft lengths (bf16)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain device copies of 256 MiB (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -210,6 +212,61 @@ def loop_policies(svip, si, dev, max_new=96, gamma_max=40, draft_cost=0.1):
     return res
 
 
+def sweep(svip, dev):
+    """Draft step and verify over B x V x k cells with random bf16 logits of the workloads' shape
+    (target = draft + noise); every position drafted.  One dict per cell."""
+    import torch
+    g = torch.Generator(device=dev).manual_seed(0)
+    cells = [(B, V, 16) for B in (1, 8, 64, 256) for V in (32000, 128256, 151936)] + \
+            [(64, 128256, 4), (64, 128256, 64), (8, 151936, 64)]
+    out = []
+    for B, V, k in cells:
+        zq = torch.randn(B, k, V, device=dev, generator=g).to(torch.bfloat16)
+        zp = torch.cat([zq.float() + 1.5 * torch.randn(B, k, V, device=dev, generator=g),
+                        torch.randn(B, 1, V, device=dev, generator=g)], 1).to(torch.bfloat16)
+        us, ua, ur = (torch.rand(B, k, device=dev, generator=g), torch.rand(B, k, device=dev, generator=g),
+                      torch.rand(B, device=dev, generator=g))
+        w = type("W", (), {"T": 1.0})()
+        r = RoundBuffers(svip, w, zq, zp, us, ua, ur)
+        r.step(99.0)
+        torch.cuda.synchronize()
+        r.capture(99.0)
+        n = 20
+        for _ in range(3):
+            r.graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            r.graph.replay()
+        torch.cuda.synchronize()
+        t_draft = (time.perf_counter() - t0) / n
+        gv = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gv):
+            r.verify()
+        gv.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            gv.replay()
+        torch.cuda.synchronize()
+        t_verify = (time.perf_counter() - t0) / n
+        svip.profile_begin(n)
+        for _ in range(n):
+            r.verify()
+        torch.cuda.synchronize()
+        ms, cnt = svip.profile_end()
+        row_bytes = V * 2
+        out.append({"B": B, "V": V, "k": k,
+                    "draft_step_us": 1e6 * t_draft / k, "draft_GBps": B * row_bytes / (t_draft / k) / 1e9,
+                    "verify_us": 1e6 * t_verify, "verify_GBps": B * (k + 2) * row_bytes / t_verify / 1e9,
+                    "k_verify_stats_us": 1e3 * ms / cnt,
+                    "k_verify_stats_GBps": B * (k + 1) * row_bytes / (ms / cnt * 1e-3) / 1e9,
+                    "rows_per_s": B * (2 * k + 1) / (t_draft + t_verify)})
+        del r, zq, zp
+        torch.cuda.empty_cache()
+    return out
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the statistics kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE scaled by a plain copy of known size), or None if there is none."""
@@ -236,6 +293,10 @@ def main():
 
     svip.load()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if a.sweep:
+        print(json.dumps({"metric": "draft+verify sweep (bf16, every position drafted, repeated over the same buffers)",
+                          "n_gpus": 1, "data": "synthetic", "sweep": sweep(svip, torch.device("cuda:0"))}))
+        return
     w = si.workload(a.workload)
     t_gen = time.perf_counter()
     batch = si.gen_batch(w, seed=0)
