@@ -11,6 +11,8 @@ SOURCES = [os.path.join(HERE, "csrc", "svip_kernels.hip"), os.path.join(HERE, "c
 HEADERS = sorted(os.path.join(HERE, "csrc", f) for f in os.listdir(os.path.join(HERE, "csrc")) if f.endswith(".h")) + \
     [os.path.join(ROOT, "include", "svip.h")]
 LIB = os.path.join(HERE, "libsvip.so")
+EXAMPLE_SRC = os.path.join(HERE, "examples", "round_from_file.cpp")
+EXAMPLE_BIN = os.path.join(HERE, "examples", "round_from_file")
 
 # packed-fp32 instructions are switched off for all device code of this library
 HIPCC_FLAGS = [
@@ -35,14 +37,33 @@ def build(verbose: bool = False) -> str:
     if verbose and out.strip():
         print(out)
     os.replace(tmp, LIB)
+    build_example(verbose)
     return LIB
+
+
+def build_example(verbose: bool = False) -> str:
+    """The C-ABI example program (plain HIP host code linked against libsvip.so, found at run time
+    through an rpath relative to the executable)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = EXAMPLE_BIN + f".tmp{os.getpid()}"
+    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-I" + os.path.join(ROOT, "include"), EXAMPLE_SRC,
+           "-L" + HERE, "-lsvip", "-Wl,-rpath,$ORIGIN/..", "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed on the example:\n" + proc.stdout)
+    os.replace(tmp, EXAMPLE_BIN)
+    return EXAMPLE_BIN
 
 
 def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+    if not os.path.exists(EXAMPLE_BIN):
+        return True
+    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS + [EXAMPLE_SRC])
 
 
 if __name__ == "__main__":

@@ -125,3 +125,41 @@ def test_seeded_shapes_round(svip, seed):
         r2.verify(lse=mode)
         check_verify(draft, target, T, np.where(g_tok < 0, 0, g_tok).astype(np.int64), g_dl.astype(np.int64), ua, ur, r2)
     assert svip.workspace_flags(r2.ws) == 0
+
+
+def test_c_abi_example_program_matches_the_binding(svip, tmp_path):
+    """The example program uses nothing but hipMalloc and the C ABI; on the same problem it must print
+    exactly what the Python binding computes (and that has been checked against the oracle above)."""
+    import json
+    import os
+    import struct
+    import subprocess
+    from paper_2411_18462_amd import build as svip_build
+    exe = svip_build.EXAMPLE_BIN
+    if not os.path.exists(exe):            # normally built together with the library
+        svip_build.build_example()
+    B, k, V, T, h = 3, 5, 5000, 0.9, 2.0
+    g = torch.Generator().manual_seed(77)
+    draft = 2.0 * torch.randn(B, k, V, generator=g)
+    draft[:, :, 123] += 7.0
+    target = torch.cat([draft, 2.0 * torch.randn(B, 1, V, generator=g)], 1) + 0.8 * torch.randn(B, k + 1, V, generator=g)
+    us, ua, ur = torch.rand(B, k, generator=g), torch.rand(B, k, generator=g), torch.rand(B, generator=g)
+    path = tmp_path / "problem.bin"
+    with open(path, "wb") as f:
+        f.write(struct.pack("<iiiff", B, k, V, T, h))
+        for t in (draft, target, us, ua, ur):
+            f.write(t.contiguous().numpy().astype("<f4").tobytes())
+    p = subprocess.run([exe, str(path)], capture_output=True, text=True, timeout=120)
+    assert p.returncode == 0, p.stderr
+    got = json.loads(p.stdout)
+    r = Round(svip, draft, target, us, ua, ur, T, h)
+    r.tokens.fill_(-1)
+    r.draft_all(chain=True)
+    r.verify(lse="given")
+    assert got["flags"] == 0
+    assert got["draft_len"] == r.draft_len.cpu().tolist()
+    assert got["n_accepted"] == r.n_accepted.cpu().tolist()
+    assert got["next_token"] == r.next_token.cpu().tolist()
+    assert got["tokens"] == r.tokens.cpu().flatten().tolist()
+    tokens, dl, lse, mh, ms = oracle_chain(draft, T, h, us)
+    check_chain(np.array(got["tokens"]).reshape(B, k), np.array(got["draft_len"]), tokens, dl, mh, ms)
