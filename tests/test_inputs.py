@@ -66,3 +66,25 @@ def test_target_is_perturbed_draft():
     d = (s["target"][: w.k].float() - s["draft"].float()).numpy()
     assert abs(d.std() - w.noise) < 0.05 and abs(d.mean()) < 0.02
     assert np.isfinite(s["target"].float().numpy()).all()
+
+
+def test_traces_for_the_decoding_loop():
+    """gen_trace: shapes, determinism, per-sequence seeds, and the acceptance split of the loop
+    workload (the models agree on low-entropy rows, disagree on high-entropy ones)."""
+    w = si.workload("cfg4_loop", V=4096)
+    tr = si.gen_trace(w, 40, rounds=7, gamma_max=5, seed=2, rows=[0, 3])
+    assert tr["draft"].shape == (2, 40, 4096) == tr["target"].shape and tr["draft"].dtype == torch.bfloat16
+    assert tr["u_sample"].shape == (7, 2, 5) == tr["u_accept"].shape and tr["u_resample"].shape == (7, 2)
+    for u in (tr["u_sample"], tr["u_accept"], tr["u_resample"]):
+        assert u.dtype == torch.float32 and (u >= 0).all() and (u < 1).all()
+    again = si.gen_trace(w, 40, rounds=7, gamma_max=5, seed=2, rows=[3])
+    assert torch.equal(again["draft"][0], tr["draft"][1]) and torch.equal(again["target"][0], tr["target"][1])
+    assert not torch.equal(tr["draft"][0], tr["draft"][1])
+    tr = si.gen_trace(w, 40, rounds=1, gamma_max=5, seed=2, rows=list(range(6)))
+    beta = {"low": [], "high": []}
+    for b in range(6):
+        for n in range(40):
+            st = oracle.pair_stats(tr["target"][b, n].double().numpy(), tr["draft"][b, n].double().numpy(), w.T)
+            beta[tr["types"][b][n]].append(st["beta"])
+    assert len(beta["low"]) > 20 and len(beta["high"]) > 10
+    assert np.mean(beta["low"]) > np.mean(beta["high"]) + 0.2
