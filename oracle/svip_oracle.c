@@ -18,8 +18,11 @@
  *     claims in Section 1 -- the p - q direction is the one that does
  *   - bonus token x ~ p(.|all drafts) if nothing rejected  Algorithm 1, last "Sample" step
  *   - greedy decoding: accept iff argmax p = x, correct with argmax p   Algorithms 3 and 5
- * plus the diagnostics of Section 2.2: beta = sum min(p,q) (Eq. beta), KL(q||p) and
- * the cross entropy H_{q,p} (Eq. pinsker / beta-bound).
+ * plus the diagnostics of Section 2.2 and Appendix B: beta = sum min(p,q) (Eq. beta), KL(q||p),
+ * the cross entropy H_{q,p} (Eq. pinsker / beta-bound), the oracle, Bretagnolle-Huber and
+ * approximation bounds (oracle_diagnostics), and the whole decoding loop over logit traces with
+ * the SVIP, Constant and Heuristic draft-length rules (oracle_generate: Algorithm 1, Algorithm 6,
+ * Section 3).
  *
  * Conventions (stated where the paper is silent):
  *   - entropy in nats; logits are divided by the temperature T before the softmax
