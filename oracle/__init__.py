@@ -74,6 +74,8 @@ def _load():
             _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_long, ctypes.c_long, ctypes.c_double,
             ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_long, _D, _D, _D, ctypes.c_long, ctypes.c_int,
             ctypes.c_long, _L, _L, _L, _D]
+        lib.oracle_warp_row.restype = ctypes.c_long
+        lib.oracle_warp_row.argtypes = [_D, ctypes.c_long, ctypes.c_double, ctypes.c_long, ctypes.c_double, _U8, _D]
         lib.oracle_sd_position_trials.restype = None
         lib.oracle_sd_position_trials.argtypes = [
             _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_ulonglong, ctypes.c_int, _L, _L]
@@ -283,6 +285,16 @@ def generate(zp, zq, T, n0, max_new, h, gamma0, gamma_max, inc, dec, us=None, ua
         int(inc), int(dec), _p(us, _D), _p(ua, _D), _p(ur, _D), us.shape[1], int(bool(greedy)), R,
         _p(out, _L), ctypes.byref(n_out), _p(log, _L), ctypes.byref(mm))
     return GenerateResult(out[:n_out.value].copy(), log[:rounds].copy(), mm.value)
+
+
+def warp_row(z, T: float = 1.0, top_k: int = 0, top_p: float = 1.0):
+    """(keep[V] bool, margin) of top-k followed by top-p filtering of one row; see oracle_warp_row."""
+    z = _f64(z).ravel()
+    keep = np.zeros(z.size, np.uint8)
+    m = ctypes.c_double(0.0)
+    n = _load().oracle_warp_row(_p(z, _D), z.size, float(T), int(top_k), float(top_p), _p(keep, _U8), ctypes.byref(m))
+    assert n == int(keep.sum())
+    return keep.astype(bool), m.value
 
 
 def sd_position_trials(p, q, N: int, seed: int, resid_sign: int = +1):

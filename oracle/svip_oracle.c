@@ -418,6 +418,71 @@ long oracle_generate(const double *zp, const double *zq, long L, long V, double 
     return rounds;
 }
 
+/* ---- top-k / top-p filtering of a row (not in the paper; a variant of the same scan) ---- */
+
+/*
+ * Which tokens survive top-k followed by top-p filtering of q = softmax(z / T)?  Both filters
+ * are thresholds on the logit VALUE, so equal logits are kept or dropped together:
+ *   top-k  (0 < top_k < V): tau_k = the top_k-th largest logit (with multiplicity); keep z >= tau_k.
+ *   top-p  (0 < top_p < 1): among the tokens kept so far, with Z their total probability, walk the
+ *          distinct logit values downwards and stop at the first value v whose cumulative
+ *          probability  sum_{z >= v} q  reaches top_p * Z; keep z >= v.
+ * top_k <= 0 or >= V and top_p >= 1 switch the respective filter off.  keep[i] = 1 for survivors.
+ * Returns the number kept; *margin = distance of the top-p decision from its threshold, as a
+ * fraction of Z (INFINITY when top-p is off).
+ */
+typedef struct { double z; long i; } oracle_zi;
+static int oracle_cmp_desc(const void *a, const void *b)
+{
+    const oracle_zi *x = (const oracle_zi *)a, *y = (const oracle_zi *)b;
+    if (x->z > y->z) return -1;
+    if (x->z < y->z) return 1;
+    return x->i < y->i ? -1 : (x->i > y->i ? 1 : 0);
+}
+long oracle_warp_row(const double *z, long V, double T, long top_k, double top_p,
+                     unsigned char *keep, double *margin)
+{
+    double *q = (double *)malloc(sizeof(double) * (size_t)V);
+    oracle_zi *s = (oracle_zi *)malloc(sizeof(oracle_zi) * (size_t)V);
+    oracle_softmax_row(z, V, T, q);
+    for (long i = 0; i < V; ++i) { s[i].z = z[i]; s[i].i = i; }
+    qsort(s, (size_t)V, sizeof(oracle_zi), oracle_cmp_desc);
+    long n = V;                                   /* survivors are s[0 .. n) */
+    if (top_k > 0 && top_k < V) {
+        const double tau = s[top_k - 1].z;
+        n = top_k;
+        while (n < V && s[n].z == tau) ++n;       /* the whole tie group of the k-th value */
+    }
+    double mar = INFINITY;
+    if (top_p < 1.0) {
+        double Z = 0.0;
+        for (long r = 0; r < n; ++r) Z += q[s[r].i];
+        const double target = top_p * Z;
+        double cum = 0.0;
+        long r = 0, cut = n;
+        while (r < n) {
+            long e = r;
+            double grp = 0.0;
+            while (e < n && s[e].z == s[r].z) { grp += q[s[e].i]; ++e; }
+            const double before = cum;
+            cum += grp;
+            if (cum >= target) {
+                double lo = (target - before) / Z, hi = (cum - target) / Z;
+                mar = lo < hi ? lo : hi;
+                cut = e;
+                break;
+            }
+            r = e;
+        }
+        n = cut;
+    }
+    for (long i = 0; i < V; ++i) keep[i] = 0;
+    for (long r = 0; r < n; ++r) keep[s[r].i] = 1;
+    if (margin) *margin = mar;
+    free(q); free(s);
+    return n;
+}
+
 /* ---- brute-force law of one speculative position (Algorithms 2 + 4) ------------ */
 
 /*

@@ -598,3 +598,62 @@ def test_loop_greedy_and_limits():
     # max_new is tested at the start of a round only
     r = oracle.generate(zq, zq, 1.0, 0, 6, np.inf, 4, 4, 0, 0, greedy=True)
     assert r.log.shape[0] == 2 and r.tokens.size == 10
+
+
+# ---------------------------------------------------------------- top-k / top-p filtering (a variant, not in the paper)
+
+def test_warp_hand_worked_and_switches():
+    z = np.log(np.array([0.1, 0.5, 0.2, 0.2]))
+    keep, m = oracle.warp_row(z)                               # both filters off
+    assert keep.all() and m == math.inf
+    assert oracle.warp_row(z, top_k=4)[0].all() and oracle.warp_row(z, top_k=9)[0].all()
+    assert oracle.warp_row(z, top_k=1)[0].tolist() == [False, True, False, False]
+    assert oracle.warp_row(z, top_k=2)[0].tolist() == [False, True, True, True]      # the tie at 0.2 stays together
+    assert oracle.warp_row(z, top_k=3)[0].tolist() == [False, True, True, True]
+    keep, m = oracle.warp_row(z, top_p=0.6)                    # 0.5 < 0.6 <= 0.9
+    assert keep.tolist() == [False, True, True, True] and abs(m - 0.1) < 1e-12
+    keep, m = oracle.warp_row(z, top_p=0.45)
+    assert keep.tolist() == [False, True, False, False] and abs(m - 0.05) < 1e-12
+    keep, m = oracle.warp_row(z, top_p=0.95)
+    assert keep.all() and abs(m - 0.05) < 1e-12
+    # top-k first, then top-p on the renormalised survivors: {0.5, 0.2, 0.2} / 0.9, target 0.5 -> {0.5} has 0.556
+    keep, m = oracle.warp_row(z, top_k=2, top_p=0.5)
+    assert keep.tolist() == [False, True, False, False] and abs(m - (0.5 / 0.9 - 0.5)) < 1e-12
+    # temperature changes the nucleus, not the top-k set
+    assert oracle.warp_row(z, T=3.0, top_k=1)[0].tolist() == [False, True, False, False]
+    assert oracle.warp_row(z, T=5.0, top_p=0.6)[0].sum() == 3 and oracle.warp_row(z, T=0.2, top_p=0.6)[0].sum() == 1
+
+
+def test_warp_against_sorting_with_library_routines():
+    rng = _rng(41)
+    for trial in range(300):
+        V = int(rng.integers(1, 60))
+        z = np.round(rng.normal(0, 2, V), int(rng.integers(0, 3)))          # coarse rounding makes ties
+        if rng.random() < 0.3:
+            z[rng.random(V) < 0.3] = -np.inf
+            z[int(rng.integers(0, V))] = 0.0
+        T = float(rng.choice([0.5, 1.0, 2.0]))
+        k = int(rng.integers(0, V + 3))
+        p_ = float(rng.choice([1.0, 0.9, 0.5, 0.1]))
+        keep, margin = oracle.warp_row(z, T, k, p_)
+        q = scipy.special.softmax(z / T)
+        kept = np.ones(V, bool)
+        if 0 < k < V:
+            kept = z >= np.sort(z)[::-1][k - 1]
+        if p_ < 1.0:
+            Zk = q[kept].sum()
+            vals = np.unique(z[kept])[::-1]
+            for v in vals:
+                if q[kept & (z >= v)].sum() >= p_ * Zk - 1e-15:
+                    break
+            if margin > 1e-12:
+                assert (keep == (kept & (z >= v))).all()
+                # minimal: without its lowest value the set falls short of top_p
+                higher = kept & (z > v)
+                assert q[higher].sum() < p_ * Zk
+                assert q[keep].sum() >= p_ * Zk - 1e-15
+        else:
+            assert (keep == kept).all() and margin == math.inf
+        # survivors are the largest logits: nothing dropped exceeds anything kept
+        if keep.any() and (~keep).any():
+            assert z[~keep].max() < z[keep].min()
