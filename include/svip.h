@@ -17,6 +17,7 @@
  *   svip_loop_init, svip_loop_run   the decoding loop over logit traces with the draft-length
  *                    policies the paper compares (Algorithm 1, Algorithm 6, Section 3)
  *   svip_pair_stats  acceptance diagnostics per drafted position (Section 2.2, Appendix B)
+ *   svip_warp_logits top-k / top-p filtering of logits rows ahead of those calls (not in the paper)
  *   svip_draft_step_greedy, svip_verify_greedy    the same two steps under greedy decoding
  *                                                       (Algorithm 3 Verify, Algorithm 5 Correct)
  *
@@ -297,6 +298,36 @@ svip_status svip_loop_init(const svip_loop_config *config /* host */);
  * executed and the sequences still running. */
 svip_status svip_loop_run(const svip_loop_config *config /* host */, int first_round, int max_rounds,
                           int *rounds_run_host, int *running_host);
+
+/*
+ * Top-k followed by top-p (nucleus) filtering of logits rows, for callers that sample from a
+ * truncated distribution.  The paper's algorithms draw from the full softmax (Algorithms 1, 2
+ * and 4); this call is a variant of their sampling rows that the paper does not cover: it writes
+ * a copy of the rows in which every filtered-out logit is -inf, and svip_draft_step,
+ * svip_verify and svip_pair_stats treat -inf logits as tokens of probability zero, so the
+ * filtered rows can be handed to them unchanged (filter draft and target rows alike and the
+ * accept / residual rule of Algorithms 2 and 4 stays exact for the truncated distributions).
+ *
+ * With q = softmax(z / temperature) of a row, both filters are thresholds on the logit VALUE
+ * (equal logits are kept or dropped together):
+ *   top_k  (0 < top_k < V): keep z >= the top_k-th largest logit of the row;
+ *   top_p  (0 < top_p < 1): among the survivors, with Z their total probability, go down the
+ *          distinct logit values and keep everything down to the first value at which the
+ *          cumulative probability reaches top_p * Z.
+ * top_k == 0 or >= V, and top_p >= 1, switch the respective filter off.  Probabilities are
+ * fp32 exponentials summed exactly as 64-bit fixed-point numbers (2^-44 units for V <= 2^18);
+ * a top-p decision closer than about 1e-6 * Z to its threshold may differ from an exact
+ * evaluation.  Top-k decisions are exact.  Results do not depend on thread scheduling.
+ *
+ * logits_in, logits_out: device, B sequences of n_rows rows, row (b, j) at element offset
+ * b * seq_stride + j * row_stride in both; they may be the same buffer (in place), and must
+ * not overlap otherwise.  kept_out: device [B * n_rows], survivors per row, or NULL.
+ * No workspace.  Enqueues on hip_stream and returns; errors as for the other calls
+ * (SVIP_ERR_PARAM: temperature, top_k < 0, top_p <= 0 or NaN).
+ */
+svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype dtype, int B, int n_rows,
+                             int V, long long seq_stride, long long row_stride, float temperature,
+                             int top_k, double top_p, int *kept_out, void *hip_stream);
 
 /*
  * Timing hook for benchmarks: between svip_profile_begin and svip_profile_end every

@@ -18,7 +18,7 @@ _DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 # every symbol include/svip.h declares
 EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_needed", "svip_workspace_reset",
            "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_draft_step_greedy",
-           "svip_verify_greedy", "svip_pair_stats", "svip_loop_workspace_bytes", "svip_loop_init", "svip_loop_run",
+           "svip_verify_greedy", "svip_pair_stats", "svip_warp_logits", "svip_loop_workspace_bytes", "svip_loop_init", "svip_loop_run",
            "svip_profile_begin", "svip_profile_end")
 
 
@@ -73,6 +73,8 @@ def load():
     lib.svip_verify_greedy.argtypes = [vp, i, i, i, i, ll, ll, vp, vp, vp, vp, vp, sz, vp]
     lib.svip_pair_stats.restype = i
     lib.svip_pair_stats.argtypes = [vp, vp, i, i, i, i, ll, ll, ll, f, vp, vp, f, vp, vp, sz, vp]
+    lib.svip_warp_logits.restype = i
+    lib.svip_warp_logits.argtypes = [vp, vp, i, i, i, i, ll, ll, f, i, ctypes.c_double, vp, vp]
     lib.svip_workspace_needed.restype = sz
     lib.svip_workspace_needed.argtypes = [i, i, i, i, i]
     lib.svip_loop_workspace_bytes.restype = sz
@@ -235,6 +237,28 @@ def pair_stats(target_logits, draft_logits, *, temperature, draft_len, c, stats_
         _ptr(draft_len, torch.int32, "draft_len"), _ptr(draft_lse, torch.float64, "draft_lse"), float(c),
         _ptr(stats_out, torch.float32, "stats_out"), _ptr(workspace, torch.uint8, "workspace"),
         workspace.numel(), _stream(stream)))
+
+
+def warp_logits(logits, *, temperature, top_k=0, top_p=1.0, out=None, kept_out=None, stream=None):
+    """svip_warp_logits.  logits [B, rows, V] (unit stride along V); out has the same shape and strides
+    (default: in place).  Returns out."""
+    if logits.dim() != 3 or logits.dtype not in _DTYPES:
+        raise ValueError("logits must be [B, rows, V] of float32, bfloat16 or float16")
+    out = logits if out is None else out
+    if out.shape != logits.shape or out.stride() != logits.stride() or out.dtype != logits.dtype:
+        raise ValueError("out must match logits in shape, strides and dtype")
+    if logits.stride(2) != 1:
+        raise ValueError("logits need unit stride along V")
+    B, n, V = logits.shape
+    row_stride = logits.stride(1) if n > 1 else max(V, logits.stride(1))
+    seq_stride = logits.stride(0) if B > 1 else n * row_stride
+    if kept_out is not None and (kept_out.numel() != B * n or not kept_out.is_contiguous()):
+        raise ValueError(f"kept_out must be contiguous with {B * n} elements")
+    _check(load().svip_warp_logits(
+        _ptr(logits, None, "logits"), _ptr(out, None, "out"), _DTYPES[logits.dtype], B, n, V, seq_stride,
+        row_stride, float(temperature), int(top_k), float(top_p), _ptr(kept_out, torch.int32, "kept_out"),
+        _stream(stream)))
+    return out
 
 
 def verify(target_logits, draft_logits, *, temperature, draft_tokens, draft_len, u_accept,

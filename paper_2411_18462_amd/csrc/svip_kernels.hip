@@ -15,6 +15,8 @@
 //                     k_pair_sums      grid (slices, positions)  sum min(p,q), sum q log(q/p), sum q log q
 //                     k_pair_finish    one thread per position   beta, KL, cross entropy, the bounds
 //
+// svip_warp_logits =  k_warp           grid (rows), 1024 threads  top-k / top-p thresholds by radix select, masked copy
+//
 // The passes are bound by HBM reads of the logits; there is no dense contraction, hence no MFMA.
 // Kernels of one call are ordered by the stream only (no spinning, no device-side waits), and
 // each small kernel issues all of its independent loads before the first dependent one, because
@@ -35,6 +37,7 @@
 #include "greedy_kernels.h"
 #include "verify_kernels.h"
 #include "pair_kernels.h"
+#include "warp_kernels.h"
 
 namespace svip {
 
@@ -429,6 +432,42 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
                        u_resample, n_accepted_out, next_token_out, accept_prob_out, workspace,
                        workspace_bytes, hip_stream};
     return verify_call(c);
+}
+
+svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype dtype, int B, int k_max, int V,
+                             long long seq_stride, long long row_stride, float temperature, int top_k,
+                             double top_p, int *kept_out, void *hip_stream)
+{
+    if (!logits_in || !logits_out) return SVIP_ERR_NULL;
+    if (!dtype_ok(dtype)) return SVIP_ERR_DTYPE;
+    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K + 1 || row_stride < V ||
+        seq_stride < (long long)(k_max - 1) * row_stride + V)
+        return SVIP_ERR_SHAPE;
+    const int vec = vec_of(dtype);
+    if (!aligned16(logits_in) || !aligned16(logits_out) || row_stride % vec != 0 || seq_stride % vec != 0)
+        return SVIP_ERR_ALIGN;
+    if (!(temperature > 0.f) || !isfinite(temperature) || top_k < 0 || !(top_p > 0.0)) return SVIP_ERR_PARAM;
+
+    WarpArgs a;
+    a.in = logits_in;
+    a.out = logits_out;
+    a.seq_stride = seq_stride;
+    a.row_stride = row_stride;
+    a.k = k_max;
+    a.V = V;
+    a.sc = make_scale(temperature);
+    a.top_k = top_k;
+    a.top_p = top_p;
+    // weights <= 1 in units of 2^-shift: V of them must stay below 2^62
+    int lg = 0;
+    while ((1ll << lg) < (long long)V) ++lg;
+    const int shift = 62 - lg < 44 ? 62 - lg : 44;
+    a.fix_scale = ldexpf(1.f, shift);
+    a.kept = kept_out;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const dim3 grid((unsigned)((long long)B * k_max));
+    by_dtype(dtype, [&](auto tag) { hipLaunchKernelGGL(k_warp<decltype(tag)>, grid, dim3(WARP_WG), 0, st, a); });
+    return check_launch();
 }
 
 svip_status svip_pair_stats(const void *target_logits, const void *draft_logits, svip_dtype dtype, int B,

@@ -131,6 +131,16 @@ def test_host_checks_of_the_greedy_diagnostic_and_loop_calls():
     assert pair(dtype=-1) == 3 and pair(V=0) == 2 and pair(st_t=3 * V) == 2 and pair(d=p + 2) == 4
     assert pair(T=float("nan")) == 6 and pair(c=-0.5) == 6 and pair(c=float("inf")) == 6 and pair(wsb=1024) == 5
 
+    def warp(**kw):
+        a = dict(i=p, o=p, dtype=1, B=2, n=5, V=V, ss=5 * V, rs=V, T=1.0, k=50, p_=0.9, kept=None, st=None)
+        a.update(kw)
+        return lib.svip_warp_logits(a["i"], a["o"], a["dtype"], a["B"], a["n"], a["V"], a["ss"], a["rs"], a["T"],
+                                    a["k"], a["p_"], a["kept"], a["st"])
+
+    assert warp(i=None) == 1 and warp(o=None) == 1 and warp(dtype=7) == 3 and warp(n=0) == 2 and warp(ss=4 * V) == 2
+    assert warp(o=p + 6) == 4 and warp(rs=V + 2, ss=6 * V) == 4 and warp(T=-1.0) == 6 and warp(k=-1) == 6
+    assert warp(p_=0.0) == 6 and warp(p_=float("nan")) == 6
+
     lwsb = lib.svip_loop_workspace_bytes(2, 4, V)
     assert lwsb > wsb and lwsb % 256 == 0 and lib.svip_loop_workspace_bytes(0, 4, V) == 0
 

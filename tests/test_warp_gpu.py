@@ -1,0 +1,159 @@
+"""Parity of svip_warp_logits (top-k then top-p filtering) with the oracle, through the C ABI.
+
+Top-k decisions are integer work and must match exactly; a top-p decision is compared where the oracle's
+margin to the threshold is at least MARGIN of the kept mass, and must be an upward-closed set otherwise.
+Kept logits keep their bits, dropped ones read -inf, padding between rows is neither read nor written.
+"""
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+import oracle
+import svip_inputs as si
+from helpers import MARGIN, REL
+
+pytestmark = pytest.mark.gpu
+
+PAD = 3.0e4
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _padded_buf(x, mult=8):
+    """x[..., V] inside a device buffer whose row stride is a multiple of `mult`; (buffer, view)."""
+    V = x.shape[-1]
+    Vp = (V + mult - 1) // mult * mult + mult
+    buf = torch.full(x.shape[:-1] + (Vp,), PAD, dtype=x.dtype)
+    buf[..., :V] = x
+    buf = buf.cuda()
+    return buf, buf[..., :V]
+
+
+def _rows(V, n, dtype, seed, ties=False, masked=False):
+    rng = np.random.default_rng(seed)
+    z = rng.normal(-2.0, 3.0, (2, n, V)).astype(np.float32)
+    z[:, ::2] *= 0.4                                      # flatter rows: larger nuclei
+    if ties:
+        z = np.round(z * 2) / 2
+    if masked:
+        z[rng.random(z.shape) < 0.4] = -np.inf
+        z[..., 0] = 0.5
+    return torch.from_numpy(z).to(dtype)
+
+
+def _check(svip, x_cpu, T, top_k, top_p, inplace=False):
+    B, n, V = x_cpu.shape
+    buf, src = _padded_buf(x_cpu)
+    kept = torch.full((B * n,), -1, dtype=torch.int32, device="cuda")
+    if inplace:
+        obuf, out = buf, svip.warp_logits(src, temperature=T, top_k=top_k, top_p=top_p, kept_out=kept)
+        assert out.data_ptr() == src.data_ptr()
+    else:
+        obuf, out = _padded_buf(torch.full_like(x_cpu, float("nan")))
+        svip.warp_logits(src, temperature=T, top_k=top_k, top_p=top_p, out=out, kept_out=kept)
+        assert torch.equal(src.cpu(), x_cpu)              # the input is untouched
+    torch.cuda.synchronize()
+    assert (obuf[..., V:] == PAD).all()                   # padding is not written
+    g = out.cpu().double().numpy()
+    z = x_cpu.double().numpy()
+    kept = kept.cpu().numpy()
+    n_margin = 0
+    for b in range(B):
+        for j in range(n):
+            keep, margin = oracle.warp_row(z[b, j], T, top_k, top_p)
+            gk = ~np.isneginf(g[b, j])                    # survivors with a finite logit
+            assert np.array_equal(g[b, j][gk], z[b, j][gk])
+            finite = ~np.isneginf(z[b, j])
+            if margin >= MARGIN:
+                assert np.array_equal(gk, keep & finite), (b, j, int(gk.sum()), int(keep.sum()), margin)
+                assert int(kept[b * n + j]) == int(keep.sum())
+            else:
+                # a cut this close to the threshold may fall one tie group to either side: the kept set
+                # must be the top of the row, reach top_p within 2 * MARGIN, and not overshoot by a group
+                n_margin += 1
+                vals = z[b, j][gk]
+                assert vals.size and (z[b, j][finite & ~gk] < vals.min()).all()
+                q = scipy.special.softmax(z[b, j] / T)
+                Z = q[oracle.warp_row(z[b, j], T, top_k, 1.0)[0]].sum()
+                assert q[gk].sum() >= (top_p - 2 * MARGIN) * Z
+                assert q[gk & (z[b, j] > vals.min())].sum() < (top_p + 2 * MARGIN) * Z
+    return n_margin
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("V", [1, 7, 1000, 4099, 32000])
+def test_top_k_is_exact(svip, dtype, V):
+    _say(f"warp top-k {dtype} V={V}")
+    x = _rows(V, 3, dtype, seed=V, ties=(V % 2 == 1))
+    for k in sorted({1, 2, min(50, V), max(V - 1, 1), V, V + 5}):
+        assert _check(svip, x, 1.0, k, 1.0) == 0
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("V,T", [(5, 1.0), (1000, 0.7), (4099, 1.0), (32000, 1.3), (128256, 1.0)])
+def test_top_p_matches_the_oracle_outside_the_margin(svip, dtype, V, T):
+    _say(f"warp top-p {dtype} V={V} T={T}")
+    x = _rows(V, 2, dtype, seed=100 + V)
+    in_margin = 0
+    for p in (0.05, 0.5, 0.9, 0.99, 0.9999):
+        in_margin += _check(svip, x, T, 0, p)
+    _say(f"  cuts inside the margin: {in_margin} of {5 * x.shape[0] * x.shape[1]}")
+    # a cut among tokens of probability below 2 * MARGIN is inside the margin by construction (large V,
+    # large top_p): those rows get the neighbour check; most of the rest must compare exactly
+    assert in_margin <= 3 * x.shape[0] * x.shape[1]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_top_k_then_top_p_with_ties_and_masks(svip, dtype):
+    _say(f"warp k+p {dtype}")
+    x = _rows(4099, 3, dtype, seed=7, ties=True, masked=True)
+    assert _check(svip, x, 0.8, 40, 0.9) <= 1
+    assert _check(svip, x, 0.8, 40, 0.9, inplace=True) <= 1
+    assert _check(svip, x, 1.0, 3000, 0.3, inplace=True) <= 1     # top-k reaches into the -inf tail
+    assert _check(svip, x, 1.0, 3000, 1.0) == 0
+    assert _check(svip, x, 1.0, 0, 1.0) == 0                       # both filters off: a copy
+
+
+def test_filtered_rows_feed_the_draft_step(svip):
+    """A draft step on rows filtered on the GPU equals the oracle's draft step on rows the oracle filtered."""
+    w = si.workload("cfg1")
+    d = si.gen_batch(w, seed=5)
+    draft = d["draft"]
+    B, k, V = draft.shape
+    T, top_k, top_p = w.T, 64, 0.95
+    z = draft.double().numpy()
+    zf = z.copy()
+    ok = np.ones((B, k), bool)
+    for b in range(B):
+        for j in range(k):
+            keep, margin = oracle.warp_row(z[b, j], T, top_k, top_p)
+            zf[b, j][~keep] = -np.inf
+            ok[b, j] = margin >= MARGIN
+    _, dev = _padded_buf(draft)
+    svip.warp_logits(dev, temperature=T, top_k=top_k, top_p=top_p)
+    ws = svip.new_workspace(B, k, V)
+    tok = torch.zeros(B, k, dtype=torch.int32, device="cuda")
+    ent = torch.zeros(B, k, dtype=torch.float32, device="cuda")
+    lse = torch.zeros(B, k, dtype=torch.float64, device="cuda")
+    stop = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    u = d["u_sample"].cuda().contiguous()
+    for j in range(k):
+        svip.draft_step(dev[:, j], temperature=T, h=1e9, step_j=j, k_max=k, u_sample=u[:, j], token_out=tok[:, j],
+                        entropy_out=ent[:, j], lse_out=lse[:, j], stop_out=stop, workspace=ws)
+    torch.cuda.synchronize()
+    checked = 0
+    for j in range(k):
+        r = oracle.draft_step(zf[:, j], T, 1e9, j, k, d["u_sample"][:, j].double().numpy())
+        for b in range(B):
+            if not ok[b, j]:
+                continue
+            if r.margin_s[b] >= MARGIN:
+                assert int(tok[b, j]) == int(r.token[b])
+                checked += 1
+            assert math.isclose(float(ent[b, j]), float(r.entropy[b]), rel_tol=REL, abs_tol=1e-6)
+    assert checked >= B * k // 2
