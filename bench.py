@@ -415,6 +415,22 @@ def main():
             "mean_oracle_bound": float(stats[..., 4].mean()),
         }
 
+        # top-k / top-p filtering of one round's rows ahead of the calls above (a variant the paper does not
+        # cover): one workgroup per row, out of place, same launch for draft and target rows
+        fd, ft = torch.empty_like(sets[0].draft), torch.empty_like(sets[0].target)
+
+        def filt(s, top_k, top_p):
+            svip.warp_logits(s.draft, temperature=w.T, top_k=top_k, top_p=top_p, out=fd)
+            svip.warp_logits(s.target, temperature=w.T, top_k=top_k, top_p=top_p, out=ft)
+
+        extra["filtering"] = {"rows": B * (2 * k + 1)}
+        for name, top_k, top_p in (("copy_only", 0, 1.0), ("top_k50", 50, 1.0), ("top_p0.9", 0, 0.9),
+                                   ("top_k50_top_p0.9", 50, 0.9)):
+            filt(sets[0], top_k, top_p)
+            t_f = phase(lambda s: filt(s, top_k, top_p), 10)
+            extra["filtering"][name] = {"us": 1e6 * t_f, "GBps_read_plus_write": 2 * B * (2 * k + 1) * V * esz / t_f / 1e9}
+        del fd, ft
+
         extra["loop_policies"] = loop_policies(svip, si, dev)
 
     out = {

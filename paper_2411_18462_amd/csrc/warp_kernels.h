@@ -18,6 +18,8 @@ namespace svip {
 constexpr int WARP_WG = 1024;              // threads of the workgroup that owns a row
 constexpr int WARP_WAVES = WARP_WG / 64;
 constexpr int WARP_BINS = 2048;            // histogram bins: digits of up to 11 bits
+constexpr int WARP_CAP = 8192;             // keys of one first-digit bin that fit the candidate list
+constexpr int DIGIT1_SHIFT = 21;           // first digit = top 11 bits of the key
 
 struct WarpArgs {
     const void *in;
@@ -33,20 +35,29 @@ struct WarpArgs {
 };
 
 struct WarpLds {
-    unsigned long long hist[WARP_BINS];
+    unsigned long long hist[WARP_BINS];    // mass per first digit
+    unsigned long long sub[WARP_BINS];     // measure per later digit while a bin is refined
+    unsigned cnt[WARP_BINS];               // keys per first digit
+    unsigned list[WARP_CAP];               // the keys of one first-digit bin
     unsigned long long wave_tot[WARP_WAVES];
     float wave_max[WARP_WAVES];
     int wave_kept[WARP_WAVES];
     unsigned digit;
+    unsigned n_list;
     unsigned long long rem;
+    unsigned long long acc;
 };
 
-// Order-preserving key of an fp32 value; -0 and +0 share a key.
+// Order-preserving key of an fp32 value (-0 and +0 share a key) and the value of a key.
 __device__ __forceinline__ unsigned value_key(float v)
 {
     unsigned u = __float_as_uint(v);
     u = u == 0x80000000u ? 0u : u;
     return u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ __forceinline__ float key_value(unsigned key)
+{
+    return __uint_as_float(key ^ ((key >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 
 template <int CTRL, int ROW_MASK>
@@ -78,26 +89,54 @@ __device__ __forceinline__ typename RawOf<DT>::type warp_load(const DT *row, int
     return load_raw_edge(row, vi, V);
 }
 
-// f(vector index, its N values) for every vector of the row, two loads in flight per thread.
+// f(vector index, its N values) for every vector of the row, four loads in flight per thread.
 template <typename DT, typename F>
 __device__ __forceinline__ void for_each_vector(const DT *row, int V, F f)
 {
-    constexpr int N = VecOf<DT>::N;
+    constexpr int N = VecOf<DT>::N, U = 4;
     const int nvec = (V + N - 1) / N;
-    for (int v0 = threadIdx.x; v0 < nvec; v0 += 2 * WARP_WG) {
-        const int v1 = v0 + WARP_WG;
-        const bool has1 = v1 < nvec;
-        const typename RawOf<DT>::type r0 = warp_load<DT>(row, v0, V);
-        const typename RawOf<DT>::type r1 = has1 ? warp_load<DT>(row, v1, V) : r0;
-        float z[N];
-        unpack<DT>(r0, z);
-        f(v0, z);
-        if (has1) {
-            unpack<DT>(r1, z);
-            f(v1, z);
+    for (int v0 = threadIdx.x; v0 < nvec; v0 += U * WARP_WG) {
+        typename RawOf<DT>::type r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * WARP_WG;
+            r[u] = warp_load<DT>(row, v < nvec ? v : v0, V);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + u * WARP_WG;
+            if (v < nvec) {
+                float z[N];
+                unpack<DT>(r[u], z);
+                f(v, z);
+            }
         }
     }
 }
+
+// Sources of candidate keys: the whole row, or the list of one first-digit bin.  f(key, value).
+template <typename DT>
+struct RowSource {
+    const DT *row;
+    int V;
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        for_each_vector<DT>(row, V, [&](int, const float(&z)[VecOf<DT>::N]) {
+#pragma unroll
+            for (int e = 0; e < VecOf<DT>::N; ++e) f(value_key(z[e]), z[e]);
+        });
+    }
+};
+struct ListSource {
+    const unsigned *list;
+    unsigned n;
+    template <typename F>
+    __device__ __forceinline__ void for_each(F f) const
+    {
+        for (unsigned i = threadIdx.x; i < n; i += WARP_WG) f(list[i], key_value(list[i]));
+    }
+};
 
 struct CountMeasure {
     __device__ __forceinline__ unsigned long long operator()(float) const { return 1ull; }
@@ -105,79 +144,112 @@ struct CountMeasure {
 struct MassMeasure {
     float m;
     Scale sc;
-    float fix_scale;
+    float fix_hi;              // fix_scale / 2^32
+    // w * fix_scale truncated to an integer; fix_scale = 2^s with s >= 32.  The float is split at
+    // 2^32 (both parts convert exactly), which is cheaper than a 64-bit conversion.
     __device__ __forceinline__ unsigned long long operator()(float z) const
     {
-        return (unsigned long long)(exp2_raw(scaled_diff(z, m, sc)) * fix_scale);
+        const float t = exp2_raw(scaled_diff(z, m, sc)) * fix_hi;          // = w * 2^(s - 32), < 2^13
+        const unsigned hi = (unsigned)t;
+        const unsigned lo = (unsigned)(__builtin_amdgcn_fractf(t) * 4294967296.0f);
+        return ((unsigned long long)hi << 32) | lo;
     }
 };
 
-// Radix select, going down from the largest key, over the keys >= floor_key of a row: the key v
-// with   measure(keys > v) < target <= measure(keys >= v).
-// With frac >= 0 the target is max(1, frac * total measure) (total taken from the first digit's
-// histogram).  If the total falls short of the target the lowest key (keep everything) results.
+// Going down from the highest digit over a histogram h[WARP_BINS] in LDS (filled and barriered
+// by the caller): the digit d with  sum(h above d) < target <= sum(h at and above d),  and
+// rem = target - sum(h above d), the share of the target that falls inside d.  With frac >= 0
+// the target is max(1, frac * sum(h)).  rem == 0: the histogram's total falls short of the target.
 // Every thread of the workgroup must call it; the result is uniform.
-template <typename DT, typename Measure>
-__device__ unsigned select_key(const DT *row, int V, unsigned floor_key, Measure measure,
-                               unsigned long long target, double frac, WarpLds &L)
+struct Crossing {
+    unsigned digit;
+    unsigned long long rem;
+};
+template <typename T>
+__device__ Crossing crossing(const T *h, unsigned long long target, double frac, WarpLds &L)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    unsigned prefix = 0;
-    int done = 0;                           // key bits fixed so far
+    // thread t owns the bins 2047 - 2t and 2046 - 2t: highest digits first
+    const int b0 = WARP_BINS - 1 - 2 * tid, b1 = b0 - 1;
+    const unsigned long long m0 = h[b0], m1 = h[b1];
+    const unsigned long long incl = wave_inclusive_sum_u64(m0 + m1);
+    if (lane == 63) L.wave_tot[wave] = incl;
+    if (tid == 0) {
+        L.digit = 0u;
+        L.rem = 0ull;
+    }
+    __syncthreads();
+    unsigned long long above = incl - (m0 + m1), total = 0ull;
+#pragma unroll
+    for (int w = 0; w < WARP_WAVES; ++w) {
+        const unsigned long long t = L.wave_tot[w];
+        above += w < wave ? t : 0ull;
+        total += t;
+    }
+    if (frac >= 0.0) {
+        target = (unsigned long long)llrint(frac * (double)total);
+        target = target ? target : 1ull;
+    }
+    if (above < target && target <= above + m0) {
+        L.digit = (unsigned)b0;
+        L.rem = target - above;
+    } else if (above + m0 < target && target <= above + m0 + m1) {
+        L.digit = (unsigned)b1;
+        L.rem = target - (above + m0);
+    }
+    __syncthreads();
+    Crossing c;
+    c.digit = L.digit;
+    c.rem = L.rem;
+    __syncthreads();                         // the next call rewrites digit, rem and wave_tot
+    return c;
+}
+
+// Digits two (11 bits) and three (10 bits) of the select inside first-digit bin d1, over the
+// candidates of src at or above floor_key: the key v of the bin with
+//   measure(keys of the bin > v) < target <= measure(keys of the bin >= v).
+template <typename Src, typename Measure>
+__device__ unsigned refine(const Src &src, unsigned floor_key, Measure measure, unsigned d1,
+                           unsigned long long target, WarpLds &L)
+{
+    const int tid = threadIdx.x;
+    unsigned prefix = d1;
+    int done = 11;
 #pragma unroll 1
-    for (int pass = 0; pass < 3; ++pass) {
-        const int bits = pass < 2 ? 11 : 10;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int bits = pass == 0 ? 11 : 10;
         const int shift = 32 - done - bits;
         const unsigned mask = (1u << bits) - 1u;
-        L.hist[tid] = 0ull;
-        L.hist[tid + WARP_WG] = 0ull;
+        L.sub[tid] = 0ull;
+        L.sub[tid + WARP_WG] = 0ull;
         __syncthreads();
-        for_each_vector<DT>(row, V, [&](int, const float(&z)[VecOf<DT>::N]) {
-#pragma unroll
-            for (int e = 0; e < VecOf<DT>::N; ++e) {
-                const unsigned key = value_key(z[e]);
-                const bool match = done == 0 || (key >> (32 - done)) == prefix;
-                if (key >= floor_key && match) atomicAdd(&L.hist[(key >> shift) & mask], measure(z[e]));
-            }
+        src.for_each([&](unsigned key, float z) {
+            if (key >= floor_key && (key >> (32 - done)) == prefix)
+                atomicAdd(&L.sub[(key >> shift) & mask], measure(z));
         });
         __syncthreads();
-        // thread t owns the bins 2047 - 2t and 2046 - 2t: highest digits first
-        const int b0 = WARP_BINS - 1 - 2 * tid, b1 = b0 - 1;
-        const unsigned long long m0 = L.hist[b0], m1 = L.hist[b1];
-        const unsigned long long incl = wave_inclusive_sum_u64(m0 + m1);
-        if (lane == 63) L.wave_tot[wave] = incl;
-        if (tid == 0) {
-            L.digit = 0u;
-            L.rem = 0ull;
-        }
-        __syncthreads();
-        unsigned long long above = incl - (m0 + m1), total = 0ull;
-#pragma unroll
-        for (int w = 0; w < WARP_WAVES; ++w) {
-            const unsigned long long t = L.wave_tot[w];
-            above += w < wave ? t : 0ull;
-            total += t;
-        }
-        if (pass == 0 && frac >= 0.0) {
-            target = (unsigned long long)llrint(frac * (double)total);
-            target = target ? target : 1ull;
-        }
-        if (above < target && target <= above + m0) {
-            L.digit = (unsigned)b0;
-            L.rem = target - above;
-        } else if (above + m0 < target && target <= above + m0 + m1) {
-            L.digit = (unsigned)b1;
-            L.rem = target - (above + m0);
-        }
-        __syncthreads();
-        const unsigned digit = L.digit;
-        const unsigned long long rem = L.rem;
-        if (rem == 0ull) return 0u;          // total < target: nothing to cut
-        prefix = (prefix << bits) | digit;
-        target = rem;
-        done += bits;             // (digit, rem are rewritten only after two more barriers)
+        const Crossing c = crossing(L.sub, target, -1.0, L);
+        prefix = (prefix << bits) | c.digit;
+        if (c.rem == 0ull) return prefix << (shift);       // cannot happen for a target taken from this bin
+        target = c.rem;
+        done += bits;
     }
     return prefix;
+}
+
+// The keys of first-digit bin d1 into L.list (the caller has checked that they fit).
+template <typename DT>
+__device__ void collect(const RowSource<DT> &rs, unsigned d1, WarpLds &L)
+{
+    if (threadIdx.x == 0) L.n_list = 0u;
+    __syncthreads();
+    rs.for_each([&](unsigned key, float) {
+        if ((key >> DIGIT1_SHIFT) == d1) {
+            const unsigned i = atomicAdd(&L.n_list, 1u);
+            if (i < (unsigned)WARP_CAP) L.list[i] = key;
+        }
+    });
+    __syncthreads();
 }
 
 template <typename DT> struct StoreBits;
@@ -234,20 +306,100 @@ __global__ __launch_bounds__(WARP_WG) void k_warp(WarpArgs a)
     DT *dst = static_cast<DT *>(a.out) + off;
     const int V = a.V;
 
+    const bool K = a.top_k > 0 && a.top_k < V, P = a.top_p < 1.0;
+    const RowSource<DT> rs{row, V};
     unsigned tau = 0u;                      // keep keys >= tau
-    if (a.top_k > 0 && a.top_k < V)
-        tau = select_key<DT>(row, V, 0u, CountMeasure{}, (unsigned long long)a.top_k, -1.0, L);
-    if (a.top_p < 1.0) {
+    if (K || P) {
+        // sweep 1: keys per first digit (top-k), row maximum (reference of the top-p weights)
         float m = neg_inf();
-        for_each_vector<DT>(row, V, [&](int, const float(&z)[N]) { m = vmax(m, tree_max<N>(z)); });
-        m = wave_max(m);
-        if (lane == 0) L.wave_max[wave] = m;
-        __syncthreads();
-        m = L.wave_max[0];
+        unsigned d_k = 0u;
+        unsigned long long k_rem = 0ull;
+        if (K) {
+            L.cnt[tid] = 0u;
+            L.cnt[tid + WARP_WG] = 0u;
+            __syncthreads();
+        }
+        for_each_vector<DT>(row, V, [&](int, const float(&z)[N]) {
+            if (P) m = vmax(m, tree_max<N>(z));
+            if (K) {
 #pragma unroll
-        for (int w = 1; w < WARP_WAVES; ++w) m = vmax(m, L.wave_max[w]);
-        const unsigned tau_p = select_key<DT>(row, V, tau, MassMeasure{m, a.sc, a.fix_scale}, 0ull, a.top_p, L);
-        tau = tau_p > tau ? tau_p : tau;
+                for (int e = 0; e < N; ++e) atomicAdd(&L.cnt[value_key(z[e]) >> DIGIT1_SHIFT], 1u);
+            }
+        });
+        if (P) {
+            m = wave_max(m);
+            if (lane == 0) L.wave_max[wave] = m;
+        }
+        __syncthreads();
+        if (P) {
+            m = L.wave_max[0];
+#pragma unroll
+            for (int w = 1; w < WARP_WAVES; ++w) m = vmax(m, L.wave_max[w]);
+        }
+        if (K) {
+            const Crossing c = crossing(L.cnt, (unsigned long long)a.top_k, -1.0, L);
+            d_k = c.digit;
+            k_rem = c.rem;
+        }
+        const MassMeasure mass{m, a.sc, a.fix_scale * (1.0f / 4294967296.0f)};
+
+        // sweep 2: mass per first digit from d_k upwards (top-p), the keys of bin d_k (top-k)
+        const bool listA = K && L.cnt[d_k] <= (unsigned)WARP_CAP;
+        if (P) {
+            L.hist[tid] = 0ull;
+            L.hist[tid + WARP_WG] = 0ull;
+        }
+        if (tid == 0) L.n_list = 0u;
+        __syncthreads();
+        if (P || listA) {
+            rs.for_each([&](unsigned key, float z) {
+                const unsigned d = key >> DIGIT1_SHIFT;
+                if (P && d >= d_k) atomicAdd(&L.hist[d], mass(z));
+                if (listA && d == d_k) {
+                    const unsigned i = atomicAdd(&L.n_list, 1u);
+                    if (i < (unsigned)WARP_CAP) L.list[i] = key;
+                }
+            });
+        }
+        __syncthreads();
+        const ListSource ls{L.list, listA ? L.n_list : 0u};
+        if (K) tau = listA ? refine(ls, 0u, CountMeasure{}, d_k, k_rem, L) : refine(rs, 0u, CountMeasure{}, d_k, k_rem, L);
+        if (P) {
+            if (K) {
+                // bin d_k counts only with its keys >= tau
+                if (tid == 0) L.acc = 0ull;
+                __syncthreads();
+                unsigned long long mine = 0ull;
+                const auto add = [&](unsigned key, float z) {
+                    if ((key >> DIGIT1_SHIFT) == d_k && key >= tau) mine += mass(z);
+                };
+                if (listA) ls.for_each(add);
+                else rs.for_each(add);
+                mine = wave_reduce(mine, OpSum{});
+                if (lane == 0 && mine) atomicAdd(&L.acc, mine);
+                __syncthreads();
+                if (tid == 0) L.hist[d_k] = L.acc;
+                __syncthreads();
+            }
+            const Crossing c = crossing(L.hist, 0ull, a.top_p, L);
+            unsigned tau_p = 0u;
+            if (c.rem != 0ull) {
+                if (K && c.digit == d_k) {
+                    tau_p = listA ? refine(ls, tau, mass, d_k, c.rem, L) : refine(rs, tau, mass, d_k, c.rem, L);
+                } else {
+                    // sweep 3; a bin too crowded for the list is refined by sweeps over the row instead
+                    const bool fits = !K || L.cnt[c.digit] <= (unsigned)WARP_CAP;
+                    if (fits) collect<DT>(rs, c.digit, L);
+                    if (fits && L.n_list <= (unsigned)WARP_CAP) {
+                        const ListSource lp{L.list, L.n_list};
+                        tau_p = refine(lp, tau, mass, c.digit, c.rem, L);
+                    } else {
+                        tau_p = refine(rs, tau, mass, c.digit, c.rem, L);
+                    }
+                }
+            }
+            tau = tau_p > tau ? tau_p : tau;
+        }
     }
 
     int kept = 0;

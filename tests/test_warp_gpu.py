@@ -119,6 +119,22 @@ def test_top_k_then_top_p_with_ties_and_masks(svip, dtype):
     assert _check(svip, x, 1.0, 0, 1.0) == 0                       # both filters off: a copy
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_crowded_bin_is_refined_by_row_sweeps(svip, dtype):
+    """More keys in one first-digit bin than the candidate list holds: the thresholds inside the crowd
+    (values that differ only in their low bits) come from sweeps over the row."""
+    _say(f"warp crowded {dtype}")
+    rng = np.random.default_rng(17)
+    V = 40000
+    z = rng.normal(0.0, 2.0, (1, 3, V)).astype(np.float32)
+    crowd = rng.permutation(V)[:20000]
+    step = 2.0 ** -20 if dtype == torch.float32 else 2.0 ** -7
+    z[0, :, crowd] = (1.0 + step * rng.integers(0, 8, (20000, 1))).astype(np.float32)
+    x = torch.from_numpy(z).to(dtype)
+    for top_k, top_p in ((15000, 1.0), (0, 0.7), (15000, 0.8), (30, 0.99), (25000, 0.999), (0, 0.97)):
+        _check(svip, x, 1.0, top_k, top_p)
+
+
 def test_filtered_rows_feed_the_draft_step(svip):
     """A draft step on rows filtered on the GPU equals the oracle's draft step on rows the oracle filtered."""
     w = si.workload("cfg1")
