@@ -319,7 +319,8 @@ svip_status svip_loop_run(const svip_loop_config *config /* host */, int first_r
  * a top-p decision closer than about 1e-6 * Z to its threshold may differ from an exact
  * evaluation.  Top-k decisions are exact.  Results do not depend on thread scheduling.
  *
- * logits_in, logits_out: device, B sequences of n_rows rows, row (b, j) at element offset
+ * logits_in, logits_out: device, B sequences of n_rows rows (any n_rows >= 1 with B * n_rows < 2^31: a
+ * round's rows or a whole trace for the loop), row (b, j) at element offset
  * b * seq_stride + j * row_stride in both; they may be the same buffer (in place), and must
  * not overlap otherwise.  kept_out: device [B * n_rows], survivors per row, or NULL.
  * No workspace.  Enqueues on hip_stream and returns; errors as for the other calls

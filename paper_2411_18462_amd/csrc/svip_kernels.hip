@@ -440,7 +440,7 @@ svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype
 {
     if (!logits_in || !logits_out) return SVIP_ERR_NULL;
     if (!dtype_ok(dtype)) return SVIP_ERR_DTYPE;
-    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || k_max > SVIP_MAX_K + 1 || row_stride < V ||
+    if (B <= 0 || B > MAX_BATCH || V <= 0 || k_max < 1 || (long long)B * k_max > 0x7FFFFFFFLL || row_stride < V ||
         seq_stride < (long long)(k_max - 1) * row_stride + V)
         return SVIP_ERR_SHAPE;
     const int vec = vec_of(dtype);

@@ -173,3 +173,25 @@ def test_filtered_rows_feed_the_draft_step(svip):
                 checked += 1
             assert math.isclose(float(ent[b, j]), float(r.entropy[b]), rel_tol=REL, abs_tol=1e-6)
     assert checked >= B * k // 2
+
+
+def test_loop_over_filtered_traces(svip):
+    """Traces filtered on the GPU (top-k: exact) drive the decoding loop; the oracle's loop runs on the same
+    filtered traces after the rows it reads were checked against the oracle's own filter."""
+    from test_loop_gpu import POLICIES, _check as check_loop, _run as run_loop
+    w = si.workload("cfg2", noise=0.7)
+    L, used = 1100, 64                    # a trace longer than any round; the loop below reads rows < used
+    tr = dict(si.gen_trace(w, L, rounds=40, gamma_max=12, seed=12, rows=[0, 1, 2]))
+    for name in ("draft", "target"):
+        x = tr[name]
+        got = svip.warp_logits(x.cuda(), temperature=w.T, top_k=40).cpu()
+        for b in range(x.shape[0]):
+            for j in list(range(used)) + list(range(used, L, 131)) + [L - 1]:
+                keep, _ = oracle.warp_row(x[b, j].double().numpy(), w.T, 40, 1.0)
+                assert np.array_equal(~torch.isinf(got[b, j]).numpy(), keep), (name, b, j)
+                assert torch.equal(got[b, j][torch.from_numpy(keep)], x[b, j][torch.from_numpy(keep)])
+        tr[name] = got[:, :used].contiguous()
+    res = run_loop(svip, tr, w, POLICIES["svip"], 40)
+    st = check_loop(res, tr, w, POLICIES["svip"], 40)
+    _say(f"  filtered loop {st}")
+    assert st["rounds"] >= 5
