@@ -464,6 +464,7 @@ svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype
     const int shift = 62 - lg < 44 ? 62 - lg : 44;
     a.fix_scale = ldexpf(1.f, shift);
     a.kept = kept_out;
+    a.no_shortcut = env_int("SVIP_WARP_NO_SHORTCUT", 0);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const dim3 grid((unsigned)((long long)B * k_max));
     by_dtype(dtype, [&](auto tag) { hipLaunchKernelGGL(k_warp<decltype(tag)>, grid, dim3(WARP_WG), 0, st, a); });

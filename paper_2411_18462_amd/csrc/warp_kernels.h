@@ -32,6 +32,7 @@ struct WarpArgs {
     double top_p;              // >= 1: filter off
     float fix_scale;           // weights in [0, 1] are summed as integers in units of 1 / fix_scale
     int *kept;                 // [rows] survivors per row, or nullptr
+    int no_shortcut;           // always take the histogram path (for tests and measurements)
 };
 
 struct WarpLds {
@@ -205,36 +206,121 @@ __device__ Crossing crossing(const T *h, unsigned long long target, double frac,
     return c;
 }
 
-// Digits two (11 bits) and three (10 bits) of the select inside first-digit bin d1, over the
-// candidates of src at or above floor_key: the key v of the bin with
-//   measure(keys of the bin > v) < target <= measure(keys of the bin >= v).
+// Remaining digits of a select (11, 11 and 10 bits, most significant first) over the candidates of
+// src at or above floor_key that carry `prefix` in their top `done` bits (done = 0: all, three
+// digits; done = 11: inside first-digit bin `prefix`, two digits): the key v among them with
+//   measure(candidates > v) < target <= measure(candidates >= v).
 template <typename Src, typename Measure>
-__device__ unsigned refine(const Src &src, unsigned floor_key, Measure measure, unsigned d1,
-                           unsigned long long target, WarpLds &L)
+__device__ unsigned select_digits(const Src &src, unsigned floor_key, Measure measure, unsigned prefix, int done,
+                                  unsigned long long target, WarpLds &L)
 {
     const int tid = threadIdx.x;
-    unsigned prefix = d1;
-    int done = 11;
 #pragma unroll 1
-    for (int pass = 0; pass < 2; ++pass) {
-        const int bits = pass == 0 ? 11 : 10;
+    while (done < 32) {
+        const int bits = done < 22 ? 11 : 10;
         const int shift = 32 - done - bits;
         const unsigned mask = (1u << bits) - 1u;
         L.sub[tid] = 0ull;
         L.sub[tid + WARP_WG] = 0ull;
         __syncthreads();
         src.for_each([&](unsigned key, float z) {
-            if (key >= floor_key && (key >> (32 - done)) == prefix)
+            if (key >= floor_key && (done == 0 || (key >> (32 - done)) == prefix))
                 atomicAdd(&L.sub[(key >> shift) & mask], measure(z));
         });
         __syncthreads();
         const Crossing c = crossing(L.sub, target, -1.0, L);
         prefix = (prefix << bits) | c.digit;
-        if (c.rem == 0ull) return prefix << (shift);       // cannot happen for a target taken from this bin
+        if (c.rem == 0ull) return prefix << shift;         // the candidates' measure falls short of the target
         target = c.rem;
         done += bits;
     }
     return prefix;
+}
+template <typename Src, typename Measure>
+__device__ unsigned refine(const Src &src, unsigned floor_key, Measure measure, unsigned d1,
+                           unsigned long long target, WarpLds &L)
+{
+    return select_digits(src, floor_key, measure, d1, 11, target, L);
+}
+
+// Sum over the workgroup of one 64-bit value per thread (uniform result; uses L.acc).
+__device__ unsigned long long wg_sum_u64(unsigned long long mine, WarpLds &L)
+{
+    if (threadIdx.x == 0) L.acc = 0ull;
+    __syncthreads();
+    mine = wave_reduce(mine, OpSum{});
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&L.acc, mine);
+    __syncthreads();
+    const unsigned long long r = L.acc;
+    __syncthreads();
+    return r;
+}
+
+// Shortcut for a small top_k: a pivot from an evenly spaced sample of the row (one vector per
+// thread), aimed at about three times top_k keys above it; one sweep puts every key >= pivot into
+// L.list.  If at least top_k and at most WARP_CAP keys arrive, the list holds the row's largest
+// keys, the row maximum among them, and both thresholds follow from the list alone -- with the
+// same integer arithmetic as the histogram path, hence the same result.  Returns false (nothing
+// decided) when the sample misjudges the row; the caller then takes the histogram path.
+template <typename DT>
+__device__ bool small_k_shortcut(const DT *row, int V, const WarpArgs &a, bool P, unsigned *tau_out, WarpLds &L)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int nvec = (V + N - 1) / N;
+    const int nsamp = nvec < WARP_WG ? nvec : WARP_WG;            // sampled vectors
+    const long long want = 3ll * a.top_k * ((long long)nsamp * N) / V + 8;
+    if (a.top_k > WARP_CAP / 4 || want > (long long)nsamp * N / 4) return false;
+    if (tid < nsamp) {
+        const int vi = (int)((long long)tid * nvec / nsamp);
+        float z[N];
+        unpack<DT>(warp_load<DT>(row, vi, V), z);
+#pragma unroll
+        for (int e = 0; e < N; ++e) L.list[tid * N + e] = value_key(z[e]);
+    }
+    __syncthreads();
+    const ListSource sample{L.list, (unsigned)(nsamp * N)};
+    const unsigned pivot = select_digits(sample, 0u, CountMeasure{}, 0u, 0, (unsigned long long)want, L);
+    if (tid == 0) L.n_list = 0u;
+    __syncthreads();
+    for_each_vector<DT>(row, V, [&](int, const float(&z)[N]) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            const unsigned key = value_key(z[e]);
+            if (key >= pivot) {
+                const unsigned i = atomicAdd(&L.n_list, 1u);
+                if (i < (unsigned)WARP_CAP) L.list[i] = key;
+            }
+        }
+    });
+    __syncthreads();
+    const unsigned n = L.n_list;
+    __syncthreads();
+    if (n < (unsigned)a.top_k || n > (unsigned)WARP_CAP) return false;
+    const ListSource ls{L.list, n};
+    unsigned tau = select_digits(ls, 0u, CountMeasure{}, 0u, 0, (unsigned long long)a.top_k, L);
+    if (P) {
+        float m = neg_inf();
+        ls.for_each([&](unsigned, float z) { m = vmax(m, z); });
+        m = wave_max(m);
+        if (lane == 0) L.wave_max[wave] = m;
+        __syncthreads();
+        m = L.wave_max[0];
+#pragma unroll
+        for (int w = 1; w < WARP_WAVES; ++w) m = vmax(m, L.wave_max[w]);
+        const MassMeasure mass{m, a.sc, a.fix_scale * (1.0f / 4294967296.0f)};
+        unsigned long long mine = 0ull;
+        ls.for_each([&](unsigned key, float z) { mine += key >= tau ? mass(z) : 0ull; });
+        const unsigned long long Zk = wg_sum_u64(mine, L);
+        unsigned long long target = (unsigned long long)llrint(a.top_p * (double)Zk);
+        target = target ? target : 1ull;
+        if (Zk >= target) {
+            const unsigned tau_p = select_digits(ls, tau, mass, 0u, 0, target, L);
+            tau = tau_p > tau ? tau_p : tau;
+        }
+    }
+    *tau_out = tau;
+    return true;
 }
 
 // The keys of first-digit bin d1 into L.list (the caller has checked that they fit).
@@ -309,7 +395,8 @@ __global__ __launch_bounds__(WARP_WG) void k_warp(WarpArgs a)
     const bool K = a.top_k > 0 && a.top_k < V, P = a.top_p < 1.0;
     const RowSource<DT> rs{row, V};
     unsigned tau = 0u;                      // keep keys >= tau
-    if (K || P) {
+    const bool decided = K && !a.no_shortcut && small_k_shortcut<DT>(row, V, a, P, &tau, L);
+    if (!decided && (K || P)) {
         // sweep 1: keys per first digit (top-k), row maximum (reference of the top-p weights)
         float m = neg_inf();
         unsigned d_k = 0u;

@@ -135,6 +135,36 @@ def test_crowded_bin_is_refined_by_row_sweeps(svip, dtype):
         _check(svip, x, 1.0, top_k, top_p)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+def test_small_k_shortcut_equals_the_histogram_path(svip, dtype, monkeypatch):
+    """For a small top_k the thresholds come from a sampled pivot and a candidate list; the result must be
+    bit for bit that of the histogram path (same integer arithmetic), also where the sample misleads."""
+    _say(f"warp shortcut {dtype}")
+    rng = np.random.default_rng(23)
+    V = 50000
+    z = rng.normal(-1.0, 2.5, (2, 4, V)).astype(np.float32)
+    z[0, 0] = np.sort(z[0, 0])                      # largest logits at the end: an evenly spaced sample still sees them
+    z[0, 1, :200] += 30.0                           # the top of the row is a cluster the sample can miss
+    z[0, 2] = np.round(z[0, 2])                     # heavy ties
+    z[1, 0, ::3] = -np.inf
+    x = torch.from_numpy(z).to(dtype)
+    buf, src = _padded_buf(x)
+    for top_k, top_p in ((1, 1.0), (50, 1.0), (50, 0.9), (300, 0.5), (2000, 0.99), (2048, 1.0), (5, 0.999)):
+        monkeypatch.delenv("SVIP_WARP_NO_SHORTCUT", raising=False)
+        k1 = torch.zeros(8, dtype=torch.int32, device="cuda")
+        a = svip.warp_logits(src, temperature=0.9, top_k=top_k, top_p=top_p, out=_padded_buf(torch.zeros_like(x))[1], kept_out=k1)
+        monkeypatch.setenv("SVIP_WARP_NO_SHORTCUT", "1")
+        k2 = torch.zeros(8, dtype=torch.int32, device="cuda")
+        b = svip.warp_logits(src, temperature=0.9, top_k=top_k, top_p=top_p, out=_padded_buf(torch.zeros_like(x))[1], kept_out=k2)
+        torch.cuda.synchronize()
+        bits = torch.int32 if dtype == torch.float32 else torch.int16
+        assert torch.equal(a.contiguous().view(bits), b.contiguous().view(bits)), (top_k, top_p)
+        assert torch.equal(k1, k2)
+    monkeypatch.delenv("SVIP_WARP_NO_SHORTCUT", raising=False)
+    _check(svip, x, 0.9, 50, 0.9)
+    _check(svip, x, 0.9, 300, 1.0)
+
+
 def test_filtered_rows_feed_the_draft_step(svip):
     """A draft step on rows filtered on the GPU equals the oracle's draft step on rows the oracle filtered."""
     w = si.workload("cfg1")
