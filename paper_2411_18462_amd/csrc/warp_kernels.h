@@ -256,8 +256,7 @@ __device__ unsigned long long wg_sum_u64(unsigned long long mine, WarpLds &L)
     return r;
 }
 
-// Shortcut for a small top_k: a pivot from an evenly spaced sample of the row (one vector per
-// thread), aimed at about three times top_k keys above it; one sweep puts every key >= pivot into
+// Shortcut for a small top_k: a pivot from a sample of the row (one vector per thread), aimed at about three times top_k keys above it; one sweep puts every key >= pivot into
 // L.list.  If at least top_k and at most WARP_CAP keys arrive, the list holds the row's largest
 // keys, the row maximum among them, and both thresholds follow from the list alone -- with the
 // same integer arithmetic as the histogram path, hence the same result.  Returns false (nothing
@@ -272,7 +271,8 @@ __device__ bool small_k_shortcut(const DT *row, int V, const WarpArgs &a, bool P
     const long long want = 3ll * a.top_k * ((long long)nsamp * N) / V + 8;
     if (a.top_k > WARP_CAP / 4 || want > (long long)nsamp * N / 4) return false;
     if (tid < nsamp) {
-        const int vi = (int)((long long)tid * nvec / nsamp);
+        // sixteen evenly spaced runs of 64 consecutive vectors: whole cache lines, spread over the row
+        const int vi = nvec <= WARP_WG ? tid : (int)((long long)(tid >> 6) * (nvec - 64) / 15) + (tid & 63);
         float z[N];
         unpack<DT>(warp_load<DT>(row, vi, V), z);
 #pragma unroll
