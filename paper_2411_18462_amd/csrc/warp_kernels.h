@@ -90,11 +90,11 @@ __device__ __forceinline__ typename RawOf<DT>::type warp_load(const DT *row, int
     return load_raw_edge(row, vi, V);
 }
 
-// f(vector index, its N values) for every vector of the row, four loads in flight per thread.
-template <typename DT, typename F>
+// f(vector index, its N values) for every vector of the row, U loads in flight per thread.
+template <typename DT, int U = 4, typename F>
 __device__ __forceinline__ void for_each_vector(const DT *row, int V, F f)
 {
-    constexpr int N = VecOf<DT>::N, U = 4;
+    constexpr int N = VecOf<DT>::N;
     const int nvec = (V + N - 1) / N;
     for (int v0 = threadIdx.x; v0 < nvec; v0 += U * WARP_WG) {
         typename RawOf<DT>::type r[U];
@@ -167,7 +167,7 @@ struct Crossing {
     unsigned long long rem;
 };
 template <typename T>
-__device__ Crossing crossing(const T *h, unsigned long long target, double frac, WarpLds &L)
+__device__ __forceinline__ Crossing crossing(const T *h, unsigned long long target, double frac, WarpLds &L)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     // thread t owns the bins 2047 - 2t and 2046 - 2t: highest digits first
@@ -211,7 +211,7 @@ __device__ Crossing crossing(const T *h, unsigned long long target, double frac,
 // digits; done = 11: inside first-digit bin `prefix`, two digits): the key v among them with
 //   measure(candidates > v) < target <= measure(candidates >= v).
 template <typename Src, typename Measure>
-__device__ unsigned select_digits(const Src &src, unsigned floor_key, Measure measure, unsigned prefix, int done,
+__device__ __forceinline__ unsigned select_digits(const Src &src, unsigned floor_key, Measure measure, unsigned prefix, int done,
                                   unsigned long long target, WarpLds &L)
 {
     const int tid = threadIdx.x;
@@ -237,14 +237,14 @@ __device__ unsigned select_digits(const Src &src, unsigned floor_key, Measure me
     return prefix;
 }
 template <typename Src, typename Measure>
-__device__ unsigned refine(const Src &src, unsigned floor_key, Measure measure, unsigned d1,
+__device__ __forceinline__ unsigned refine(const Src &src, unsigned floor_key, Measure measure, unsigned d1,
                            unsigned long long target, WarpLds &L)
 {
     return select_digits(src, floor_key, measure, d1, 11, target, L);
 }
 
 // Sum over the workgroup of one 64-bit value per thread (uniform result; uses L.acc).
-__device__ unsigned long long wg_sum_u64(unsigned long long mine, WarpLds &L)
+__device__ __forceinline__ unsigned long long wg_sum_u64(unsigned long long mine, WarpLds &L)
 {
     if (threadIdx.x == 0) L.acc = 0ull;
     __syncthreads();
@@ -254,88 +254,6 @@ __device__ unsigned long long wg_sum_u64(unsigned long long mine, WarpLds &L)
     const unsigned long long r = L.acc;
     __syncthreads();
     return r;
-}
-
-// Shortcut for a small top_k: a pivot from a sample of the row (one vector per thread), aimed at about three times top_k keys above it; one sweep puts every key >= pivot into
-// L.list.  If at least top_k and at most WARP_CAP keys arrive, the list holds the row's largest
-// keys, the row maximum among them, and both thresholds follow from the list alone -- with the
-// same integer arithmetic as the histogram path, hence the same result.  Returns false (nothing
-// decided) when the sample misjudges the row; the caller then takes the histogram path.
-template <typename DT>
-__device__ bool small_k_shortcut(const DT *row, int V, const WarpArgs &a, bool P, unsigned *tau_out, WarpLds &L)
-{
-    constexpr int N = VecOf<DT>::N;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int nvec = (V + N - 1) / N;
-    const int nsamp = nvec < WARP_WG ? nvec : WARP_WG;            // sampled vectors
-    const long long want = 3ll * a.top_k * ((long long)nsamp * N) / V + 8;
-    if (a.top_k > WARP_CAP / 4 || want > (long long)nsamp * N / 4) return false;
-    if (tid < nsamp) {
-        // sixteen evenly spaced runs of 64 consecutive vectors: whole cache lines, spread over the row
-        const int vi = nvec <= WARP_WG ? tid : (int)((long long)(tid >> 6) * (nvec - 64) / 15) + (tid & 63);
-        float z[N];
-        unpack<DT>(warp_load<DT>(row, vi, V), z);
-#pragma unroll
-        for (int e = 0; e < N; ++e) L.list[tid * N + e] = value_key(z[e]);
-    }
-    __syncthreads();
-    const ListSource sample{L.list, (unsigned)(nsamp * N)};
-    const unsigned pivot = select_digits(sample, 0u, CountMeasure{}, 0u, 0, (unsigned long long)want, L);
-    if (tid == 0) L.n_list = 0u;
-    __syncthreads();
-    for_each_vector<DT>(row, V, [&](int, const float(&z)[N]) {
-#pragma unroll
-        for (int e = 0; e < N; ++e) {
-            const unsigned key = value_key(z[e]);
-            if (key >= pivot) {
-                const unsigned i = atomicAdd(&L.n_list, 1u);
-                if (i < (unsigned)WARP_CAP) L.list[i] = key;
-            }
-        }
-    });
-    __syncthreads();
-    const unsigned n = L.n_list;
-    __syncthreads();
-    if (n < (unsigned)a.top_k || n > (unsigned)WARP_CAP) return false;
-    const ListSource ls{L.list, n};
-    unsigned tau = select_digits(ls, 0u, CountMeasure{}, 0u, 0, (unsigned long long)a.top_k, L);
-    if (P) {
-        float m = neg_inf();
-        ls.for_each([&](unsigned, float z) { m = vmax(m, z); });
-        m = wave_max(m);
-        if (lane == 0) L.wave_max[wave] = m;
-        __syncthreads();
-        m = L.wave_max[0];
-#pragma unroll
-        for (int w = 1; w < WARP_WAVES; ++w) m = vmax(m, L.wave_max[w]);
-        const MassMeasure mass{m, a.sc, a.fix_scale * (1.0f / 4294967296.0f)};
-        unsigned long long mine = 0ull;
-        ls.for_each([&](unsigned key, float z) { mine += key >= tau ? mass(z) : 0ull; });
-        const unsigned long long Zk = wg_sum_u64(mine, L);
-        unsigned long long target = (unsigned long long)llrint(a.top_p * (double)Zk);
-        target = target ? target : 1ull;
-        if (Zk >= target) {
-            const unsigned tau_p = select_digits(ls, tau, mass, 0u, 0, target, L);
-            tau = tau_p > tau ? tau_p : tau;
-        }
-    }
-    *tau_out = tau;
-    return true;
-}
-
-// The keys of first-digit bin d1 into L.list (the caller has checked that they fit).
-template <typename DT>
-__device__ void collect(const RowSource<DT> &rs, unsigned d1, WarpLds &L)
-{
-    if (threadIdx.x == 0) L.n_list = 0u;
-    __syncthreads();
-    rs.for_each([&](unsigned key, float) {
-        if ((key >> DIGIT1_SHIFT) == d1) {
-            const unsigned i = atomicAdd(&L.n_list, 1u);
-            if (i < (unsigned)WARP_CAP) L.list[i] = key;
-        }
-    });
-    __syncthreads();
 }
 
 template <typename DT> struct StoreBits;
@@ -379,9 +297,124 @@ __device__ __forceinline__ void store_vec(DT *p, const float (&z)[VecOf<DT>::N])
     }
 }
 
+// Shortcut for a small top_k: a pivot from a sample of the row (one vector per thread), aimed at
+// about three times top_k keys above it; one sweep puts every key >= pivot into L.list.  If at
+// least top_k keys arrive and all of them fit, the list holds the row's largest keys, the row
+// maximum among them, and both thresholds follow from the list alone -- with the same integer
+// arithmetic as the histogram path, hence the same result.
+// With `fused` (output is not the input, top_k <= 1024) the same sweep already writes the output:
+// -inf below the pivot, the logit itself at and above it, and the list also keeps the candidates'
+// indices (4096 of each); afterwards only the candidates below the final threshold are overwritten,
+// so the row is read once.
+// Returns 0: nothing decided (the sample misjudged the row; the caller takes the histogram path,
+// which rewrites the whole output), 1: *tau_out is the threshold, 2: output and *kept_out are done.
+template <typename DT, bool fused>
+__device__ __forceinline__ int small_k_shortcut(const DT *row, DT *dst, int V, const WarpArgs &a, bool P,
+                                             unsigned *tau_out, int *kept_out, WarpLds &L)
+{
+    constexpr int N = VecOf<DT>::N;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int nvec = (V + N - 1) / N;
+    const int nsamp = nvec < WARP_WG ? nvec : WARP_WG;            // sampled vectors
+    constexpr unsigned cap = fused ? WARP_CAP / 2 : WARP_CAP;
+    const long long want = 3ll * a.top_k * ((long long)nsamp * N) / V + 8;
+    if (a.top_k > (int)cap / 4 || want > (long long)nsamp * N / 4) return 0;
+    if (tid < nsamp) {
+        // sixteen evenly spaced runs of 64 consecutive vectors: whole cache lines, spread over the row
+        const int vi = nvec <= WARP_WG ? tid : (int)((long long)(tid >> 6) * (nvec - 64) / 15) + (tid & 63);
+        float z[N];
+        unpack<DT>(warp_load<DT>(row, vi, V), z);
+#pragma unroll
+        for (int e = 0; e < N; ++e) L.list[tid * N + e] = value_key(z[e]);
+    }
+    __syncthreads();
+    const ListSource sample{L.list, (unsigned)(nsamp * N)};
+    const unsigned pivot = select_digits(sample, 0u, CountMeasure{}, 0u, 0, (unsigned long long)want, L);
+    if (tid == 0) L.n_list = 0u;
+    __syncthreads();
+    for_each_vector<DT, 2>(row, V, [&](int vi, const float(&z)[N]) {
+        float o[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            const unsigned key = value_key(z[e]);
+            o[e] = key >= pivot ? z[e] : neg_inf();
+            if (key >= pivot) {
+                const unsigned i = atomicAdd(&L.n_list, 1u);
+                if (i < cap) {
+                    L.list[i] = key;
+                    if (fused) L.list[cap + i] = (unsigned)(vi * N + e);
+                }
+            }
+        }
+        if (fused) {
+            if ((vi + 1) * N <= V) {
+                store_vec<DT>(dst + (long long)vi * N, o);
+            } else {
+                #pragma unroll
+                for (int e = 0; e < N; ++e)
+                    if (vi * N + e < V) store_one<DT>(dst + (long long)vi * N + e, o[e]);
+            }
+        }
+    });
+    __syncthreads();
+    const unsigned n = L.n_list;
+    __syncthreads();
+    if (n < (unsigned)a.top_k || n > cap) return 0;
+    const ListSource ls{L.list, n};
+    unsigned tau = select_digits(ls, 0u, CountMeasure{}, 0u, 0, (unsigned long long)a.top_k, L);
+    if (P) {
+        float m = neg_inf();
+        ls.for_each([&](unsigned, float z) { m = vmax(m, z); });
+        m = wave_max(m);
+        if (lane == 0) L.wave_max[wave] = m;
+        __syncthreads();
+        m = L.wave_max[0];
+#pragma unroll
+        for (int w = 1; w < WARP_WAVES; ++w) m = vmax(m, L.wave_max[w]);
+        const MassMeasure mass{m, a.sc, a.fix_scale * (1.0f / 4294967296.0f)};
+        unsigned long long mine = 0ull;
+        ls.for_each([&](unsigned key, float z) { mine += key >= tau ? mass(z) : 0ull; });
+        const unsigned long long Zk = wg_sum_u64(mine, L);
+        unsigned long long target = (unsigned long long)llrint(a.top_p * (double)Zk);
+        target = target ? target : 1ull;
+        if (Zk >= target) {
+            const unsigned tau_p = select_digits(ls, tau, mass, 0u, 0, target, L);
+            tau = tau_p > tau ? tau_p : tau;
+        }
+    }
+    *tau_out = tau;
+    if (!fused) return 1;
+    // the sweep's stores are complete (every barrier since waited for them): drop the candidates below tau
+    unsigned long long kept = 0ull;
+    for (unsigned i = tid; i < n; i += WARP_WG) {
+        const unsigned idx = L.list[cap + i];
+        if (idx < (unsigned)V) {
+            if (L.list[i] >= tau) kept += 1ull;
+            else store_one<DT>(dst + idx, neg_inf());
+        }
+    }
+    *kept_out = (int)wg_sum_u64(kept, L);
+    return 2;
+}
+
+// The keys of first-digit bin d1 into L.list (the caller has checked that they fit).
+template <typename DT>
+__device__ __forceinline__ void collect(const RowSource<DT> &rs, unsigned d1, WarpLds &L)
+{
+    if (threadIdx.x == 0) L.n_list = 0u;
+    __syncthreads();
+    rs.for_each([&](unsigned key, float) {
+        if ((key >> DIGIT1_SHIFT) == d1) {
+            const unsigned i = atomicAdd(&L.n_list, 1u);
+            if (i < (unsigned)WARP_CAP) L.list[i] = key;
+        }
+    });
+    __syncthreads();
+}
+
 // grid (rows), WARP_WG threads.
 template <typename DT>
-__global__ __launch_bounds__(WARP_WG) void k_warp(WarpArgs a)
+__global__ __launch_bounds__(WARP_WG, 8) void k_warp(WarpArgs a)
 {
     constexpr int N = VecOf<DT>::N;
     __shared__ WarpLds L;
@@ -395,8 +428,12 @@ __global__ __launch_bounds__(WARP_WG) void k_warp(WarpArgs a)
     const bool K = a.top_k > 0 && a.top_k < V, P = a.top_p < 1.0;
     const RowSource<DT> rs{row, V};
     unsigned tau = 0u;                      // keep keys >= tau
-    const bool decided = K && !a.no_shortcut && small_k_shortcut<DT>(row, V, a, P, &tau, L);
-    if (!decided && (K || P)) {
+    int kept = 0;
+    int decided = 0;
+    if (K && !a.no_shortcut)
+        decided = a.in != a.out ? small_k_shortcut<DT, true>(row, dst, V, a, P, &tau, &kept, L)
+                                : small_k_shortcut<DT, false>(row, dst, V, a, P, &tau, &kept, L);
+    if (decided == 0 && (K || P)) {
         // sweep 1: keys per first digit (top-k), row maximum (reference of the top-p weights)
         float m = neg_inf();
         unsigned d_k = 0u;
@@ -489,7 +526,10 @@ __global__ __launch_bounds__(WARP_WG) void k_warp(WarpArgs a)
         }
     }
 
-    int kept = 0;
+    if (decided == 2) {
+        if (a.kept && tid == 0) a.kept[y] = kept;
+        return;
+    }
     for_each_vector<DT>(row, V, [&](int vi, const float(&z)[N]) {
         float o[N];
 #pragma unroll
@@ -501,7 +541,9 @@ __global__ __launch_bounds__(WARP_WG) void k_warp(WarpArgs a)
         if ((vi + 1) * N <= V) {
             store_vec<DT>(dst + (long long)vi * N, o);
         } else {
-            for (int e = 0; e < N && vi * N + e < V; ++e) store_one<DT>(dst + (long long)vi * N + e, o[e]);
+            #pragma unroll
+                for (int e = 0; e < N; ++e)
+                    if (vi * N + e < V) store_one<DT>(dst + (long long)vi * N + e, o[e]);
         }
     });
     if (a.kept) {
