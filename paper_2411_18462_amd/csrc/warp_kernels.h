@@ -8,8 +8,13 @@
 //   top-p   select on the MASS  of keys >= tau_k: the first value, going down, at which the
 //           cumulative softmax mass reaches top_p of the mass kept so far.
 // Masses are summed as 64-bit fixed-point integers, so a row's thresholds do not depend on the
-// order in which workgroup threads reach the histogram.  One workgroup owns a row and re-reads it
-// once per digit (the row stays in L2); HBM sees one read and one write of the row.
+// order in which workgroup threads reach the histogram.  One workgroup owns a row.  Only the first
+// digit is histogrammed over the whole row; the keys of the bin it selects go into a list in LDS
+// and the other digits are found there.  Every sweep over the row is a read from memory (the rows
+// in flight exceed L2), so the sweeps are few: count + maximum, mass + candidates, candidates of
+// the nucleus bin if it is another one, masked copy.  A small top_k skips the histograms: a pivot
+// from a sample, one sweep for the candidates above it (which also writes the output when that
+// is a different buffer), everything else on the list.
 #pragma once
 #include "row_math.h"
 
