@@ -302,39 +302,6 @@ __device__ __forceinline__ void store_vec(DT *p, const float (&z)[VecOf<DT>::N])
     }
 }
 
-// Vector vi of the output row: whole if it lies inside the row, element by element at its end.
-template <typename DT>
-__device__ __forceinline__ void store_masked(DT *dst, int vi, int V, const float (&o)[VecOf<DT>::N])
-{
-    constexpr int N = VecOf<DT>::N;
-    if ((vi + 1) * N <= V) {
-        store_vec<DT>(dst + (long long)vi * N, o);
-    } else {
-#pragma unroll
-        for (int e = 0; e < N; ++e)
-            if (vi * N + e < V) store_one<DT>(dst + (long long)vi * N + e, o[e]);
-    }
-}
-
-// After a sweep that wrote every candidate's logit to the output and listed (key, index) pairs in
-// L.list[0 .. n) and L.list[cap .. cap + n): overwrite the candidates below tau with -inf; returns
-// the survivors.  The sweep's stores precede these in every thread's order and a barrier lies
-// between, so the later store to the same address wins.
-template <typename DT>
-__device__ __forceinline__ int drop_candidates_below(DT *dst, int V, unsigned n, unsigned cap, unsigned tau,
-                                                     WarpLds &L)
-{
-    unsigned long long kept = 0ull;
-    for (unsigned i = threadIdx.x; i < n; i += WARP_WG) {
-        const unsigned idx = L.list[cap + i];
-        if (idx < (unsigned)V) {
-            if (L.list[i] >= tau) kept += 1ull;
-            else store_one<DT>(dst + idx, neg_inf());
-        }
-    }
-    return (int)wg_sum_u64(kept, L);
-}
-
 // Shortcut for a small top_k: a pivot from a sample of the row (one vector per thread), aimed at
 // about three times top_k keys above it; one sweep puts every key >= pivot into L.list.  If at
 // least top_k keys arrive and all of them fit, the list holds the row's largest keys, the row
@@ -384,7 +351,15 @@ __device__ __forceinline__ int small_k_shortcut(const DT *row, DT *dst, int V, c
                 }
             }
         }
-        if (fused) store_masked<DT>(dst, vi, V, o);
+        if (fused) {
+            if ((vi + 1) * N <= V) {
+                store_vec<DT>(dst + (long long)vi * N, o);
+            } else {
+                #pragma unroll
+                for (int e = 0; e < N; ++e)
+                    if (vi * N + e < V) store_one<DT>(dst + (long long)vi * N + e, o[e]);
+            }
+        }
     });
     __syncthreads();
     const unsigned n = L.n_list;
@@ -414,95 +389,16 @@ __device__ __forceinline__ int small_k_shortcut(const DT *row, DT *dst, int V, c
     }
     *tau_out = tau;
     if (!fused) return 1;
-    *kept_out = drop_candidates_below<DT>(dst, V, n, cap, tau, L);
-    return 2;
-}
-
-// Shortcut for top-p alone, along the same lines: the exact row maximum from one sweep, a pivot
-// from the sample at the value where the sample's own cumulative mass reaches (1 + top_p) / 2,
-// then one sweep that sums every logit's mass in registers (the exact integer Z of the histogram
-// path, without its atomics) and lists the keys >= pivot (writing the output as above when
-// `fused`).  If the listed mass reaches top_p * Z the nucleus lies inside the list and its
-// threshold follows from the list; otherwise the histogram path runs.  Same return values.
-// *m_out receives the row maximum whenever the function got that far (*have_m), for the caller's use.
-template <typename DT, bool fused>
-__device__ __forceinline__ int top_p_shortcut(const DT *row, DT *dst, int V, const WarpArgs &a,
-                                              unsigned *tau_out, int *kept_out, float *m_out, bool *have_m,
-                                              WarpLds &L)
-{
-    constexpr int N = VecOf<DT>::N;
-    constexpr unsigned cap = fused ? WARP_CAP / 2 : WARP_CAP;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int nvec = (V + N - 1) / N;
-    const int nsamp = nvec < WARP_WG ? nvec : WARP_WG;
-    if (nsamp * N < 1024) return 0;                     // a short row: nothing to gain
-    float m = neg_inf();
-    for_each_vector<DT>(row, V, [&](int, const float(&z)[N]) { m = vmax(m, tree_max<N>(z)); });
-    m = wave_max(m);
-    if (lane == 0) L.wave_max[wave] = m;
-    __syncthreads();
-    m = L.wave_max[0];
-#pragma unroll
-    for (int w = 1; w < WARP_WAVES; ++w) m = vmax(m, L.wave_max[w]);
-    *m_out = m;
-    *have_m = true;
-    const MassMeasure mass{m, a.sc, a.fix_scale * (1.0f / 4294967296.0f)};
-    if (tid < nsamp) {
-        const int vi = nvec <= WARP_WG ? tid : (int)((long long)(tid >> 6) * (nvec - 64) / 15) + (tid & 63);
-        float z[N];
-        unpack<DT>(warp_load<DT>(row, vi, V), z);
-#pragma unroll
-        for (int e = 0; e < N; ++e) L.list[tid * N + e] = value_key(z[e]);
-    }
-    __syncthreads();
-    const ListSource sample{L.list, (unsigned)(nsamp * N)};
-    unsigned long long mine = 0ull;
-    sample.for_each([&](unsigned, float z) { mine += mass(z); });
-    const unsigned long long Zs = wg_sum_u64(mine, L);
-    if (Zs == 0ull) return 0;
-    unsigned long long target_s = (unsigned long long)llrint(0.5 * (1.0 + a.top_p) * (double)Zs);
-    target_s = target_s ? target_s : 1ull;
-    const unsigned pivot = select_digits(sample, 0u, mass, 0u, 0, target_s, L);
-    // the sample's share above the pivot predicts the candidates of the row: leave early if they will not fit
-    mine = 0ull;
-    sample.for_each([&](unsigned key, float) { mine += key >= pivot ? 1ull : 0ull; });
-    const unsigned long long above = wg_sum_u64(mine, L);
-    if (above * (unsigned long long)V > (unsigned long long)(cap - cap / 4) * (unsigned long long)(nsamp * N)) return 0;
-    if (tid == 0) L.n_list = 0u;
-    __syncthreads();
-    mine = 0ull;
-    for_each_vector<DT, 2>(row, V, [&](int vi, const float(&z)[N]) {
-        float o[N];
-#pragma unroll
-        for (int e = 0; e < N; ++e) {
-            const unsigned key = value_key(z[e]);
-            mine += mass(z[e]);
-            o[e] = key >= pivot ? z[e] : neg_inf();
-            if (key >= pivot) {
-                const unsigned i = atomicAdd(&L.n_list, 1u);
-                if (i < cap) {
-                    L.list[i] = key;
-                    if (fused) L.list[cap + i] = (unsigned)(vi * N + e);
-                }
-            }
+    // the sweep's stores are complete (every barrier since waited for them): drop the candidates below tau
+    unsigned long long kept = 0ull;
+    for (unsigned i = tid; i < n; i += WARP_WG) {
+        const unsigned idx = L.list[cap + i];
+        if (idx < (unsigned)V) {
+            if (L.list[i] >= tau) kept += 1ull;
+            else store_one<DT>(dst + idx, neg_inf());
         }
-        if (fused) store_masked<DT>(dst, vi, V, o);
-    });
-    __syncthreads();
-    const unsigned n = L.n_list;
-    const unsigned long long Z = wg_sum_u64(mine, L);
-    if (n == 0u || n > cap) return 0;
-    const ListSource ls{L.list, n};
-    mine = 0ull;
-    ls.for_each([&](unsigned, float z) { mine += mass(z); });
-    const unsigned long long listed = wg_sum_u64(mine, L);
-    unsigned long long target = (unsigned long long)llrint(a.top_p * (double)Z);
-    target = target ? target : 1ull;
-    if (listed < target) return 0;                      // the nucleus reaches below the pivot
-    const unsigned tau = select_digits(ls, 0u, mass, 0u, 0, target, L);
-    *tau_out = tau;
-    if (!fused) return 1;
-    *kept_out = drop_candidates_below<DT>(dst, V, n, cap, tau, L);
+    }
+    *kept_out = (int)wg_sum_u64(kept, L);
     return 2;
 }
 
@@ -539,14 +435,9 @@ __global__ __launch_bounds__(WARP_WG, 8) void k_warp(WarpArgs a)
     unsigned tau = 0u;                      // keep keys >= tau
     int kept = 0;
     int decided = 0;
-    float m_known = neg_inf();
-    bool have_m = false;                    // the top-p shortcut may leave the row maximum behind
     if (K && !a.no_shortcut)
         decided = a.in != a.out ? small_k_shortcut<DT, true>(row, dst, V, a, P, &tau, &kept, L)
                                 : small_k_shortcut<DT, false>(row, dst, V, a, P, &tau, &kept, L);
-    else if (P && !a.no_shortcut)
-        decided = a.in != a.out ? top_p_shortcut<DT, true>(row, dst, V, a, &tau, &kept, &m_known, &have_m, L)
-                                : top_p_shortcut<DT, false>(row, dst, V, a, &tau, &kept, &m_known, &have_m, L);
     if (decided == 0 && (K || P)) {
         // sweep 1: keys per first digit (top-k), row maximum (reference of the top-p weights)
         float m = neg_inf();
@@ -557,26 +448,22 @@ __global__ __launch_bounds__(WARP_WG, 8) void k_warp(WarpArgs a)
             L.cnt[tid + WARP_WG] = 0u;
             __syncthreads();
         }
-        if (K || !have_m) {
-            for_each_vector<DT>(row, V, [&](int, const float(&z)[N]) {
-                if (P) m = vmax(m, tree_max<N>(z));
-                if (K) {
+        for_each_vector<DT>(row, V, [&](int, const float(&z)[N]) {
+            if (P) m = vmax(m, tree_max<N>(z));
+            if (K) {
 #pragma unroll
-                    for (int e = 0; e < N; ++e) atomicAdd(&L.cnt[value_key(z[e]) >> DIGIT1_SHIFT], 1u);
-                }
-            });
-            if (P) {
-                m = wave_max(m);
-                if (lane == 0) L.wave_max[wave] = m;
+                for (int e = 0; e < N; ++e) atomicAdd(&L.cnt[value_key(z[e]) >> DIGIT1_SHIFT], 1u);
             }
-            __syncthreads();
-            if (P) {
-                m = L.wave_max[0];
+        });
+        if (P) {
+            m = wave_max(m);
+            if (lane == 0) L.wave_max[wave] = m;
+        }
+        __syncthreads();
+        if (P) {
+            m = L.wave_max[0];
 #pragma unroll
-                for (int w = 1; w < WARP_WAVES; ++w) m = vmax(m, L.wave_max[w]);
-            }
-        } else {
-            m = m_known;
+            for (int w = 1; w < WARP_WAVES; ++w) m = vmax(m, L.wave_max[w]);
         }
         if (K) {
             const Crossing c = crossing(L.cnt, (unsigned long long)a.top_k, -1.0, L);
@@ -656,7 +543,13 @@ __global__ __launch_bounds__(WARP_WG, 8) void k_warp(WarpArgs a)
             o[e] = keep ? z[e] : neg_inf();
             kept += (keep && vi * N + e < V) ? 1 : 0;
         }
-        store_masked<DT>(dst, vi, V, o);
+        if ((vi + 1) * N <= V) {
+            store_vec<DT>(dst + (long long)vi * N, o);
+        } else {
+            #pragma unroll
+                for (int e = 0; e < N; ++e)
+                    if (vi * N + e < V) store_one<DT>(dst + (long long)vi * N + e, o[e]);
+        }
     });
     if (a.kept) {
         kept = wave_reduce(kept, OpSum{});
