@@ -149,7 +149,8 @@ def test_small_k_shortcut_equals_the_histogram_path(svip, dtype, monkeypatch):
     z[1, 0, ::3] = -np.inf
     x = torch.from_numpy(z).to(dtype)
     buf, src = _padded_buf(x)
-    for top_k, top_p in ((1, 1.0), (50, 1.0), (50, 0.9), (300, 0.5), (2000, 0.99), (2048, 1.0), (5, 0.999)):
+    for top_k, top_p in ((1, 1.0), (50, 1.0), (50, 0.9), (300, 0.5), (2000, 0.99), (2048, 1.0), (5, 0.999),
+                         (0, 0.9), (0, 0.3), (0, 0.999), (0, 0.05)):
         monkeypatch.delenv("SVIP_WARP_NO_SHORTCUT", raising=False)
         k1 = torch.zeros(8, dtype=torch.int32, device="cuda")
         a = svip.warp_logits(src, temperature=0.9, top_k=top_k, top_p=top_p, out=_padded_buf(torch.zeros_like(x))[1], kept_out=k1)
@@ -160,9 +161,17 @@ def test_small_k_shortcut_equals_the_histogram_path(svip, dtype, monkeypatch):
         bits = torch.int32 if dtype == torch.float32 else torch.int16
         assert torch.equal(a.contiguous().view(bits), b.contiguous().view(bits)), (top_k, top_p)
         assert torch.equal(k1, k2)
+        monkeypatch.delenv("SVIP_WARP_NO_SHORTCUT", raising=False)       # in place: the shortcut without the early write
+        k3 = torch.zeros(8, dtype=torch.int32, device="cuda")
+        c = svip.warp_logits(_padded_buf(x)[1], temperature=0.9, top_k=top_k, top_p=top_p, kept_out=k3)
+        torch.cuda.synchronize()
+        assert torch.equal(a.contiguous().view(bits), c.contiguous().view(bits)), (top_k, top_p, "in place")
+        assert torch.equal(k1, k3)
     monkeypatch.delenv("SVIP_WARP_NO_SHORTCUT", raising=False)
     _check(svip, x, 0.9, 50, 0.9)
     _check(svip, x, 0.9, 300, 1.0)
+    _check(svip, x, 0.9, 0, 0.9)
+    _check(svip, x, 0.9, 0, 0.9, inplace=True)
 
 
 def test_filtered_rows_feed_the_draft_step(svip):
