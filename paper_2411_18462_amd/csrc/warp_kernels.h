@@ -436,8 +436,9 @@ __global__ __launch_bounds__(WARP_WG, 8) void k_warp(WarpArgs a)
     int kept = 0;
     int decided = 0;
     if (K && !a.no_shortcut)
-        decided = a.in != a.out ? small_k_shortcut<DT, true>(row, dst, V, a, P, &tau, &kept, L)
-                                : small_k_shortcut<DT, false>(row, dst, V, a, P, &tau, &kept, L);
+        decided = a.in != a.out && a.top_k <= WARP_CAP / 8
+                      ? small_k_shortcut<DT, true>(row, dst, V, a, P, &tau, &kept, L)
+                      : small_k_shortcut<DT, false>(row, dst, V, a, P, &tau, &kept, L);
     if (decided == 0 && (K || P)) {
         // sweep 1: keys per first digit (top-k), row maximum (reference of the top-p weights)
         float m = neg_inf();
