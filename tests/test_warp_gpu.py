@@ -174,6 +174,30 @@ def test_small_k_shortcut_equals_the_histogram_path(svip, dtype, monkeypatch):
     _check(svip, x, 0.9, 0, 0.9, inplace=True)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_shapes_and_settings(svip, seed):
+    """Random vocabulary sizes (ragged tails), storage types, temperatures, filters, row kinds, in place or not."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = [torch.float32, torch.bfloat16, torch.float16][seed % 3]
+    V = int(rng.choice([3, 17, 255, 1025, 4097, 8191, 20011, 65537, 131075]))
+    n = 2 if V > 50000 else 3
+    z = rng.normal(rng.uniform(-4, 2), rng.uniform(0.3, 6.0), (1, n, V)).astype(np.float32)
+    kind = seed % 4
+    if kind == 1:
+        z = np.round(z)                                        # ties
+    elif kind == 2:
+        z[rng.random(z.shape) < 0.5] = -np.inf                 # masked vocabulary
+        z[..., int(rng.integers(0, V))] = 1.0
+    elif kind == 3:
+        z[0, :, : max(1, V // 100)] += 15.0                    # a cluster at the front of the row
+    x = torch.from_numpy(z).to(dtype)
+    top_k = int(rng.choice([0, 1, 5, 50, 700, 3000, V, V + 1]))
+    top_p = float(rng.choice([1.0, 0.999, 0.95, 0.9, 0.5, 0.1]))
+    T = float(rng.choice([0.6, 1.0, 1.7]))
+    _say(f"warp seeded {seed}: {dtype} V={V} kind={kind} top_k={top_k} top_p={top_p} T={T}")
+    _check(svip, x, T, top_k, top_p, inplace=bool(seed & 1))
+
+
 def test_filtered_rows_feed_the_draft_step(svip):
     """A draft step on rows filtered on the GPU equals the oracle's draft step on rows the oracle filtered."""
     w = si.workload("cfg1")
