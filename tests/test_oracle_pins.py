@@ -619,6 +619,10 @@ def test_warp_hand_worked_and_switches():
     # top-k first, then top-p on the renormalised survivors: {0.5, 0.2, 0.2} / 0.9, target 0.5 -> {0.5} has 0.556
     keep, m = oracle.warp_row(z, top_k=2, top_p=0.5)
     assert keep.tolist() == [False, True, False, False] and abs(m - (0.5 / 0.9 - 0.5)) < 1e-12
+    # the nucleus is measured against the mass top-k left (0.9), not against 1: 0.5 / 0.9 = 0.556 >= 0.55
+    keep, m = oracle.warp_row(z, top_k=2, top_p=0.55)
+    assert keep.tolist() == [False, True, False, False] and abs(m - (0.5 / 0.9 - 0.55)) < 1e-12
+    assert oracle.warp_row(z, top_p=0.55)[0].sum() == 3
     # temperature changes the nucleus, not the top-k set
     assert oracle.warp_row(z, T=3.0, top_k=1)[0].tolist() == [False, True, False, False]
     assert oracle.warp_row(z, T=5.0, top_p=0.6)[0].sum() == 3 and oracle.warp_row(z, T=0.2, top_p=0.6)[0].sum() == 1
