@@ -478,6 +478,7 @@ def main():
             "unit": "rows/s",
             "cores": threads,
             "kind": "oracle",
+            "rows_per_s_per_thread": rows / busy if busy > 0 else None,
             "sample": f"{nseq} sequences ({nseq / B:g} batches of the workload, seeds 0..) through the same round "
                       f"(chained draft steps + verify), {rows} rows, {wall:.1f} s wall, "
                       f"{busy:.1f} s summed thread time",
