@@ -119,7 +119,7 @@ def test_bitwise_determinism(svip):
 def test_full_size_round_as_benchmarked(svip, h):
     """BASELINE config 3 at full size (B = 64, V = 128256 bf16, k = 16), launched the way
     bench.py launches it (chained draft steps, then verify fed by the device buffers):
-    sampled sequences against the oracle, all sequences against size-independent properties."""
+    every sequence against the oracle and against size-independent properties."""
     w, d = _batch("cfg3")
     B, k, V = d["draft"].shape
     r = Round(svip, d["draft"], d["target"], d["u_sample"], d["u_accept"], d["u_resample"], w.T, h)
@@ -144,8 +144,8 @@ def test_full_size_round_as_benchmarked(svip, h):
     ref = torch.logsumexp(r.draft.float() / w.T, dim=-1).double().cpu().numpy()
     for b in range(B):
         assert np.allclose(lse[b, :dl[b]], ref[b, :dl[b]], rtol=0, atol=2e-5)
-    # sampled sequences against the oracle
-    rows = [0, 9, 23, 37, 50, 63]
+    # every sequence against the oracle
+    rows = list(range(B))            # the oracle does the whole batch in a few seconds
     sub = {key: d[key][rows] for key in ("draft", "target", "u_sample", "u_accept", "u_resample")}
     tokens, odl, olse, mh, ms = oracle_chain(sub["draft"], w.T, h, sub["u_sample"])
     cst = check_chain(tok, dl, tokens, odl, mh, ms, rows=rows)
@@ -160,4 +160,5 @@ def test_full_size_round_as_benchmarked(svip, h):
                      dl[b:b + 1].astype(np.int64), sub["u_accept"][n:n + 1], sub["u_resample"][n:n + 1], _One, stats=st)
     _say(f"full size h={h}: chain {cst}, verify {st}, "
          f"mean draft_len {dl.mean():.2f}, mean n_accepted {nacc.mean():.2f}")
-    assert cst["len_checked"] >= 4 and cst["tok_checked"] >= 5 and st["seqs"] == len(rows)
+    assert cst["len_checked"] >= B // 2 and cst["tok_checked"] >= B // 2 and st["seqs"] == len(rows)
+    assert cst["tok_excluded_diff"] <= 0.01 * (cst["tok_checked"] + cst["tok_excluded"]) and st["excluded_diff"] <= 2
