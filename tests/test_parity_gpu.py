@@ -43,6 +43,7 @@ def test_draft_step_every_position(svip, name, rows, over):
     ("cfg2", None, {}),
     ("cfg3", [10, 11, 12, 13], {}),
     ("cfg4", [2, 3, 4], {}),
+    ("cfg4", None, {"h": 4.0}),                 # the whole long-form batch, every one of its 64 positions drafted
     ("cfg2", None, {"T": 0.7, "h": 2.0}),
 ])
 def test_round_chained_draft_then_verify(svip, name, rows, over):
