@@ -206,6 +206,25 @@ def test_host_errors_enqueue_nothing(svip):
     assert (r.tokens.cpu().numpy() == -7).all()              # nothing ran
 
 
+def test_largest_k(svip):
+    """k_max = SVIP_MAX_K = 1024 positions per round (16 passes of the acceptance wave), close models so that
+    long runs are accepted."""
+    B, k, V = 2, svip.MAX_K, 132
+    draft, target, us, ua, ur = _make(B, k, V, torch.float32, seed=31, scale=1.0, noise=0.02)
+    r = Round(svip, draft, target, us, ua, ur, 1.0, 9.0)
+    r.draft_all(chain=False)
+    tokens = r.tokens.cpu().numpy().astype(np.int64)
+    st_d = check_draft_rows(draft, 1.0, 9.0, k, us, r, steps=[0, 1, 63, 64, 511, 1022, 1023])
+    for dl in ([1024, 700], [1, 1023]):
+        dl = np.array(dl, np.int64)
+        r.accept_prob.fill_(float("nan"))
+        for mode in ("given", None):
+            r.verify(tokens=r.tokens, draft_len=torch.from_numpy(dl).int().cuda(), lse=mode)
+            st = check_verify(draft, target, 1.0, tokens, dl, ua, ur, r)
+        _say(f"k={k} dl={dl.tolist()} n_acc={r.n_accepted.cpu().tolist()} {st} draft {st_d}")
+    assert svip.workspace_flags(r.ws) == 0
+
+
 def test_large_batch_of_short_rows(svip):
     """B = 6000 sequences (more statistics rows than a 16-bit grid dimension), tiny vocabulary."""
     B, k, V = 6000, 5, 96
