@@ -22,7 +22,8 @@
  * the cross entropy H_{q,p} (Eq. pinsker / beta-bound), the oracle, Bretagnolle-Huber and
  * approximation bounds (oracle_diagnostics), and the whole decoding loop over logit traces with
  * the SVIP, Constant and Heuristic draft-length rules (oracle_generate: Algorithm 1, Algorithm 6,
- * Section 3).
+ * Section 3).  oracle_warp_row states a truncation the paper does not have (top-k, then top-p, as
+ * thresholds on the logit value); it is pinned by a worked example and a sort-based cross-check.
  *
  * Conventions (stated where the paper is silent):
  *   - entropy in nats; logits are divided by the temperature T before the softmax
