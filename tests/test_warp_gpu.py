@@ -198,6 +198,45 @@ def test_seeded_shapes_and_settings(svip, seed):
     _check(svip, x, T, top_k, top_p, inplace=bool(seed & 1))
 
 
+def test_filter_replays_from_a_hip_graph(svip):
+    """The call allocates nothing and launches one kernel: captured with a draft step behind it and replayed
+    over changing inputs, every replay equals the eager result."""
+    B, k, V = 4, 1, 20011
+    g = torch.Generator().manual_seed(3)
+    src = torch.empty(B, k, 20016, device="cuda", dtype=torch.bfloat16)[..., :V]
+    out = torch.empty(B, k, 20016, device="cuda", dtype=torch.bfloat16)[..., :V]
+    ws = svip.new_workspace(B, 1, V)
+    u = torch.rand(B, generator=g).cuda()
+    o = {n: torch.zeros(B, dtype=t, device="cuda") for n, t in
+         (("tok", torch.int32), ("ent", torch.float32), ("lse", torch.float64), ("stop", torch.uint8))}
+
+    def step():
+        svip.warp_logits(src, temperature=0.8, top_k=64, top_p=0.92, out=out)
+        svip.draft_step(out[:, 0], temperature=0.8, h=0.5, step_j=0, k_max=1, u_sample=u, token_out=o["tok"],
+                        entropy_out=o["ent"], lse_out=o["lse"], stop_out=o["stop"], workspace=ws)
+
+    src.copy_((2.5 * torch.randn(B, k, V, generator=g)).bfloat16())
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        src.copy_((2.5 * torch.randn(B, k, V, generator=g)).bfloat16())
+        step()
+        torch.cuda.synchronize()
+        eager = (out.clone(), {n: t.clone() for n, t in o.items()})
+        out.fill_(float("nan"))
+        for t in o.values():
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager[0].view(torch.int16)), rep
+        for n, t in o.items():
+            assert torch.equal(t, eager[1][n]), (rep, n)
+        assert int((~torch.isinf(out)).sum(-1).max()) <= 64 + 8
+
+
 def test_filtered_rows_feed_the_draft_step(svip):
     """A draft step on rows filtered on the GPU equals the oracle's draft step on rows the oracle filtered."""
     w = si.workload("cfg1")
