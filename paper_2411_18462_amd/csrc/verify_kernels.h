@@ -77,22 +77,24 @@ __device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns)
     return (double)r + log2(S);
 }
 
-// grid (sequences), one wave: lane = position, 64 positions per pass.  Lanes j <= draft_len merge
-// the statistics of target row j; lanes j < draft_len run the acceptance test; a ballot finds
-// the first rejection.
+// The acceptance test of sequence b by one wave: lane = position, 64 positions per pass.  Lanes
+// j <= draft_len merge the statistics of target row j; lanes j < draft_len run the acceptance
+// test; a ballot finds the first rejection.  Returns (uniform over the wave) what the residual
+// kernels need; with `publish` lane 0 also writes n_accepted and the record, every tested lane its
+// accept probability, and bad device data sets the flags.
 template <typename DT>
-__global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
+__device__ __forceinline__ SeqRec accept_sequence(const VerifyArgs &a, int b, int lane, bool publish)
 {
-    const int b = blockIdx.x, lane = threadIdx.x;
     const int graw = a.draft_len[b];
     const int g = clamp_len(graw, a.k);
-    if (graw != g && lane == 0) atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
+    if (publish && graw != g && lane == 0) atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
     const DT *tgt = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, 0);
     const DT *drf = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, 0);
     constexpr double LOG2E = 1.4426950408889634;
+    float *accept_prob = publish ? a.accept_prob : nullptr;
     int r = -1;                 // first rejection, once known
     double Lp_r = 0.0, Lq_r = 0.0;
-    for (int j0 = 0; j0 <= g && (r < 0 || a.accept_prob); j0 += 64) {
+    for (int j0 = 0; j0 <= g && (r < 0 || accept_prob); j0 += 64) {
         const int j = j0 + lane;
         bool reject = false;
         double Lp = 0.0, Lq = 0.0;
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
             if (j < g) {
                 Lq = a.draft_lse ? lse_q * LOG2E : row_L(a.ws.part, stat_row(a, b, j), a.geo.ns);
                 if (x < 0 || x >= a.geo.V) {
-                    atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_TOKEN);
+                    if (publish) atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_TOKEN);
                     x = x < 0 ? 0 : a.geo.V - 1;
                 }
                 const double zp = (double)load_one<DT>(tgt + (long long)j * a.row_stride, x);
@@ -117,9 +119,9 @@ __global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
                 const double p = exp2(zp * a.sc.c - Lp);
                 const double q = exp2(zq * a.sc.c - Lq);
                 reject = !(u * q < p);
-                if (a.accept_prob) {
+                if (accept_prob) {
                     const double ratio = q > 0.0 ? p / q : (p > 0.0 ? 1.0 : 0.0);
-                    a.accept_prob[(size_t)b * a.k + j] = (float)(ratio < 1.0 ? ratio : 1.0);
+                    accept_prob[(size_t)b * a.k + j] = (float)(ratio < 1.0 ? ratio : 1.0);
                 }
             }
         }
@@ -136,27 +138,48 @@ __global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
             }
         }
     }
-    if (lane == 0) {
+    SeqRec rec;
+    rec.r = r;
+    rec.resid = r < g ? 1 : 0;
+    rec.Lp = Lp_r;
+    rec.Lq = Lq_r;
+    if (publish && lane == 0) {
         a.n_accepted[b] = r;
-        SeqRec rec;
-        rec.r = r;
-        rec.resid = r < g ? 1 : 0;
-        rec.Lp = Lp_r;
-        rec.Lq = Lq_r;
         a.ws.rec[b] = rec;
     }
+    return rec;
+}
+
+// grid (sequences), one wave.
+template <typename DT>
+__global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
+{
+    accept_sequence<DT>(a, blockIdx.x, threadIdx.x, true);
 }
 
 // ---- verify: residual / bonus sampling ------------------------------------------------------
 
 // grid (sequences * slices): slice masses of the weights to sample from -- [0] residual
 // max(0, p - q) at the rejected position, [1] target p of the row to sample.
-template <typename DT>
+// WITH_ACCEPT: no k_accept ran before; the first wave of every workgroup repeats the sequence's
+// acceptance test (slice 0 publishes its outputs), which trades one kernel boundary for repeated work.
+template <typename DT, bool WITH_ACCEPT>
 __global__ __launch_bounds__(WG) void k_resid_mass(VerifyArgs a)
 {
     __shared__ double lds[2 * NWAVE];
+    __shared__ SeqRec shrec;
     const int b = blockIdx.x / a.geo_s.ns, s = blockIdx.x - b * a.geo_s.ns, tid = threadIdx.x;
-    const SeqRec rec = a.ws.rec[b];
+    SeqRec rec;
+    if constexpr (WITH_ACCEPT) {
+        if (tid < 64) {
+            const SeqRec mine = accept_sequence<DT>(a, b, tid, s == 0);
+            if (tid == 0) shrec = mine;
+        }
+        __syncthreads();
+        rec = shrec;
+    } else {
+        rec = a.ws.rec[b];
+    }
     const DT *prow = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, rec.r);
     const DT *qrow = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, rec.r);
     const ExpRef ep = make_exp_ref(a.sc, rec.Lp), eq = make_exp_ref(a.sc, rec.Lq);
