@@ -73,12 +73,12 @@ class RoundBuffers:
         self.graph_greedy = None
 
     def draft_round(self, h, greedy=False):
-        """Algorithm 1's drafting loop, flags threaded on the device (no host sync)."""
-        self.stop.zero_()
+        """Algorithm 1's drafting loop, flags threaded on the device (no host sync).  The first step of a
+        round takes no flags (every sequence drafts) and writes them all, so nothing has to be cleared."""
         for j in range(self.k):
             self.svip.draft_step(
                 self.draft[:, j], temperature=self.w.T, h=h, step_j=j, k_max=self.k, greedy=greedy,
-                u_sample=self.us[:, j], stop_in=self.stop, token_out=self.tokens[:, j],
+                u_sample=self.us[:, j], stop_in=self.stop if j else None, token_out=self.tokens[:, j],
                 entropy_out=self.entropy[:, j], q_tok_out=self.q_tok[:, j], lse_out=self.lse[:, j],
                 stop_out=self.stop, draft_len_out=self.draft_len, workspace=self.ws)
 
