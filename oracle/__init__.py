@@ -41,7 +41,14 @@ _U8 = ctypes.POINTER(ctypes.c_ubyte)
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        _lib = _bind(ctypes.CDLL(build()))
+    return _lib
+
+
+def _bind(lib):
+    """Declare the C signatures of svip_oracle.c on a loaded library (also used by the test that
+    compiles copies of the oracle with planted mistakes)."""
+    if True:
         lib.oracle_softmax_row.restype = ctypes.c_double
         lib.oracle_softmax_row.argtypes = [_D, ctypes.c_long, ctypes.c_double, _D]
         lib.oracle_entropy_row.restype = ctypes.c_double
@@ -55,7 +62,7 @@ def _load():
         lib.oracle_verify.restype = None
         lib.oracle_verify.argtypes = [
             _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
-            _L, _L, _D, _D, _L, _L, _D, _D, _D]
+            _L, _L, _D, _D, _L, _L, _D, _D, _D, _D, _D, _D]
         lib.oracle_argmax_row.restype = ctypes.c_long
         lib.oracle_argmax_row.argtypes = [_D, ctypes.c_long]
         lib.oracle_draft_step_greedy.restype = None
@@ -79,8 +86,7 @@ def _load():
         lib.oracle_sd_position_trials.restype = None
         lib.oracle_sd_position_trials.argtypes = [
             _D, _D, ctypes.c_long, ctypes.c_long, ctypes.c_ulonglong, ctypes.c_int, _L, _L]
-        _lib = lib
-    return _lib
+    return lib
 
 
 def _f64(a) -> np.ndarray:
@@ -160,6 +166,9 @@ class VerifyResult:
     accept_prob: np.ndarray  # float64 [B, k_max]; NaN where j >= gamma[b]
     margin: np.ndarray       # float64 [B], smallest decision margin of the sequence
     resid_mass: np.ndarray   # float64 [B], sum max(0, p - q) at the rejection (0 if none)
+    margin_a: np.ndarray     # float64 [B, k_max], |ua - p/q| per tested position; NaN where j >= gamma[b]
+    margin_accept: np.ndarray  # float64 [B], smallest margin_a up to and including the first rejection
+    margin_sample: np.ndarray  # float64 [B], sampler margin of the correction / bonus draw
 
 
 def verify(zp, zq, T, tok, gamma, ua, ur) -> VerifyResult:
@@ -180,11 +189,12 @@ def verify(zp, zq, T, tok, gamma, ua, ur) -> VerifyResult:
         assert ((tok[b, :g] >= 0) & (tok[b, :g] < V)).all()
     out = VerifyResult(
         np.empty(B, np.int64), np.empty(B, np.int64), np.full((B, k), np.nan),
-        np.empty(B), np.empty(B))
+        np.empty(B), np.empty(B), np.full((B, k), np.nan), np.empty(B), np.empty(B))
     _load().oracle_verify(
         _p(zp, _D), _p(zq, _D), B, k, V, float(T), _p(tok, _L), _p(gamma, _L),
         _p(ua, _D), _p(ur, _D), _p(out.n_accepted, _L), _p(out.next_token, _L),
-        _p(out.accept_prob, _D), _p(out.margin, _D), _p(out.resid_mass, _D))
+        _p(out.accept_prob, _D), _p(out.margin, _D), _p(out.resid_mass, _D),
+        _p(out.margin_a, _D), _p(out.margin_accept, _D), _p(out.margin_sample, _D))
     return out
 
 

@@ -146,16 +146,20 @@ void oracle_draft_step(const double *z, long B, long V, long row_stride,
  * tok: [B][k_max] draft tokens, gamma[b] in 0..k_max, ua: [B][k_max], ur: [B].
  * Outputs per sequence: n_accepted, next_token (correction or bonus),
  * accept_prob[b][j] = min(1, p/q) for j < gamma[b] (others untouched),
- * margin[b] = smallest margin among the decisions that shaped the outputs:
- *   |ua - p/q| for every position up to and including the first rejection,
- *   and the sampler margin of the correction / bonus draw.
+ * margin_a[b][j] = |ua - p/q| of the acceptance test at position j < gamma[b] (others untouched),
+ * margin_accept[b] = smallest margin_a among the tests that shaped n_accepted: every position
+ *   up to and including the first rejection (INFINITY when gamma[b] = 0),
+ * margin_sample[b] = sampler margin of the correction / bonus draw (0 when the residual has no
+ *   mass and the draw falls back to p),
+ * margin[b] = the smaller of the two,
  * resid_mass[b] = sum max(0, p - q) at the rejected position (0 for a bonus draw).
  */
 void oracle_verify(const double *zp, const double *zq, long B, long k_max, long V,
                    double T, const long *tok, const long *gamma,
                    const double *ua, const double *ur,
                    long *n_accepted, long *next_token, double *accept_prob,
-                   double *margin, double *resid_mass)
+                   double *margin, double *resid_mass,
+                   double *margin_a, double *margin_accept, double *margin_sample)
 {
     double *p = (double *)malloc(sizeof(double) * (size_t)V);
     double *q = (double *)malloc(sizeof(double) * (size_t)V);
@@ -175,8 +179,9 @@ void oracle_verify(const double *zp, const double *zq, long B, long k_max, long 
             double ratio = qx > 0.0 ? px / qx : (px > 0.0 ? INFINITY : 0.0);
             accept_prob[b * k_max + j] = ratio < 1.0 ? ratio : 1.0;
             int acc = ua[b * k_max + j] * qx < px;
+            double d = fabs(ua[b * k_max + j] - ratio);
+            if (margin_a) margin_a[b * k_max + j] = d;
             if (r == g) {        /* no rejection so far: this decision shapes the output */
-                double d = fabs(ua[b * k_max + j] - ratio);
                 if (d < mar) mar = d;
                 if (!acc) r = j;
             }
@@ -207,6 +212,8 @@ void oracle_verify(const double *zp, const double *zq, long B, long k_max, long 
             next_token[b] = oracle_inverse_cdf(p, V, ur[b], &ms);
         }
         margin[b] = ms < mar ? ms : mar;
+        if (margin_accept) margin_accept[b] = mar;
+        if (margin_sample) margin_sample[b] = ms;
     }
     free(p); free(q); free(w);
 }
@@ -397,7 +404,7 @@ long oracle_generate(const double *zp, const double *zq, long L, long V, double 
         } else {
             double mv, rm;
             oracle_verify(zp + n * V, zq + n * V, 1, cap, V, T, tok, &drafted, ua + rounds * kw, ur + rounds,
-                          &nacc, &next, ap, &mv, &rm);
+                          &nacc, &next, ap, &mv, &rm, NULL, NULL, NULL);
             if (mv < mm) mm = mv;
         }
         for (long j = 0; j < nacc; ++j) out_tok[produced++] = tok[j];

@@ -234,7 +234,8 @@ def test_large_batch_of_short_rows(svip):
     from helpers import check_chain, oracle_chain
     rows = list(range(0, B, 97))
     tokens, dl, lse, mh, ms = oracle_chain(draft[rows], 1.0, 1.9, us[rows])
-    st = check_chain(r.tokens.cpu().numpy(), r.draft_len.cpu().numpy(), tokens, dl, mh, ms, rows=rows)
+    st = check_chain(r.tokens.cpu().numpy(), r.draft_len.cpu().numpy(), tokens, dl, mh, ms, rows=rows,
+                     draft_cpu=draft[rows], T=1.0, u_sample=us[rows])
     for mode in ("given", None):
         r.verify(lse=mode)
         sv = check_verify(draft, target, 1.0, r.tokens.cpu().numpy().astype(np.int64),

@@ -120,7 +120,7 @@ def test_seeded_shapes_round(svip, seed):
     r2.draft_all(chain=True)
     tokens, dl, lse, mh, ms = oracle_chain(draft, T, h, us)
     g_tok, g_dl = r2.tokens.cpu().numpy(), r2.draft_len.cpu().numpy()
-    check_chain(g_tok, g_dl, tokens, dl, mh, ms)
+    check_chain(g_tok, g_dl, tokens, dl, mh, ms, draft_cpu=draft, T=T, u_sample=us)
     for mode in ("given", None):
         r2.verify(lse=mode)
         check_verify(draft, target, T, np.where(g_tok < 0, 0, g_tok).astype(np.int64), g_dl.astype(np.int64), ua, ur, r2)
@@ -162,4 +162,5 @@ def test_c_abi_example_program_matches_the_binding(svip, tmp_path):
     assert got["next_token"] == r.next_token.cpu().tolist()
     assert got["tokens"] == r.tokens.cpu().flatten().tolist()
     tokens, dl, lse, mh, ms = oracle_chain(draft, T, h, us)
-    check_chain(np.array(got["tokens"]).reshape(B, k), np.array(got["draft_len"]), tokens, dl, mh, ms)
+    check_chain(np.array(got["tokens"]).reshape(B, k), np.array(got["draft_len"]), tokens, dl, mh, ms,
+                draft_cpu=draft, T=T, u_sample=us)

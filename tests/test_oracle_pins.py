@@ -288,6 +288,87 @@ def test_first_rejection_all_patterns():
                 assert r.margin[0] <= min(dec) + 1e-12
 
 
+# ---------------------------------------------------------------- decision margins (hand-worked)
+#
+# The parity tests compare a decision exactly only where the oracle reports a margin of at least
+# 1e-6, so a margin that came out too small would silently move decisions out of the comparison
+# and one that came out too large would demand more than the bar.  Each margin is pinned to
+# values worked by hand on distributions with unequal distances to the two sides.
+
+def test_sampler_margin_hand_worked():
+    """Cells of w = (1/4, 1/2, 1/4): [0, 1/4), [1/4, 3/4), [3/4, 1).  The margin is the distance of
+    u to the NEARER edge of the chosen cell, as a fraction of the total weight."""
+    w = np.array([0.25, 0.5, 0.25])
+    for u, tok, m in [(0.3, 1, 0.05), (0.7, 1, 0.05), (0.5, 1, 0.25), (0.74, 1, 0.01), (0.26, 1, 0.01),
+                      (0.1, 0, 0.1), (0.2, 0, 0.05), (0.9, 2, 0.1), (0.76, 2, 0.01), (0.0, 0, 0.0)]:
+        for scale in (1.0, 8.0, 1e-3):                       # unnormalised weights: same fraction
+            i, mar = oracle.inverse_cdf(scale * w, u)
+            assert i == tok and abs(mar - m) < 1e-12, (u, scale, i, mar)
+    # cells without weight do not shorten the distance: (0, 1/4, 0, 1/2, 1/4, 0), u = 0.3 lies 0.05 into token 3
+    i, mar = oracle.inverse_cdf([0.0, 0.25, 0.0, 0.5, 0.25, 0.0], 0.3)
+    assert i == 3 and abs(mar - 0.05) < 1e-12
+    # the draft step reports the same margin for the same distribution (logits ln 1, ln 2, ln 1)
+    z = np.log(np.array([[1.0, 2.0, 1.0]]))
+    r = oracle.draft_step(z, 1.0, 9.0, 0, 40, [0.3])
+    assert r.token[0] == 1 and abs(r.margin_s[0] - 0.05) < 1e-12
+    r = oracle.draft_step(np.repeat(z, 3, 0), 1.0, 9.0, 0, 40, [0.74, 0.1, 0.9])      # per row, not shared
+    assert np.allclose(r.margin_s, [0.01, 0.1, 0.1], atol=1e-12)
+
+
+def test_stop_margin_hand_worked():
+    """Uniform logits over 4 tokens: sqrt(H) = sqrt(ln 4) = 1.17741002251547...; margin_h = |sqrt(H) - h|."""
+    z = np.zeros((1, 4))
+    root = 1.1774100225154747
+    for h, stop in [(1.0, 1), (1.5, 0), (1.17, 1), (1.18, 0), (0.3, 1)]:
+        r = oracle.draft_step(z, 1.0, h, 0, 40, [0.2])
+        assert r.stop[0] == stop and abs(r.margin_h[0] - abs(root - h)) < 1e-12, (h, r.margin_h[0])
+    # two-point distribution (1/2, 1/2) at T = 0.5 of logits (0, 0): still uniform, H = ln 2
+    r = oracle.draft_step(np.zeros((1, 2)), 0.5, 1.0, 0, 40, [0.2])
+    assert abs(r.margin_h[0] - (1.0 - math.sqrt(math.log(2.0)))) < 1e-12
+    # at the cap the stop does not depend on the entropy: no margin
+    assert math.isinf(oracle.draft_step(z, 1.0, 1.0, 39, 40, [0.2]).margin_h[0])
+
+
+def test_verify_margins_hand_worked():
+    """q = (.4, .2, .2, .2), p uniform: p/q = .625 at token 0, residual max(0, p - q) = (0, .05, .05, .05)."""
+    k, V = 4, 4
+    zq = np.zeros((1, k, V))
+    zq[:, :, 0] = math.log(2.0)
+    zp = np.zeros((1, k + 1, V))
+    tok = np.zeros((1, k), np.int64)
+
+    def run(ua, ur, g=k):
+        return oracle.verify(zp, zq, 1.0, tok, [g], [ua], [ur])
+
+    # accepted, accepted (close), rejected, then a test that would be the closest of all but comes after the rejection
+    r = run([0.3, 0.6, 0.9, 0.62], 0.5)
+    assert r.n_accepted[0] == 2
+    assert np.allclose(r.margin_a[0], [0.325, 0.025, 0.275, 0.005], atol=1e-12)
+    assert abs(r.margin_accept[0] - 0.025) < 1e-12            # minimum over positions 0..2 only
+    # the correction: u * W = .075 lies in token 2's cell [.05, .10): .025 to either edge, W = .15
+    assert r.next_token[0] == 2 and abs(r.margin_sample[0] - 1.0 / 6.0) < 1e-12
+    assert abs(r.margin[0] - 0.025) < 1e-12                   # the smaller of the two
+    # the rejecting test itself counts
+    r = run([0.3, 0.3, 0.63, 0.1], 0.5)
+    assert r.n_accepted[0] == 2 and abs(r.margin_accept[0] - 0.005) < 1e-12 and abs(r.margin[0] - 0.005) < 1e-12
+    # a draw close to a cell edge: u * W = .0495 -> token 1, .0005 / .15 from the edge at .05
+    r = run([0.9, 0.1, 0.1, 0.1], 0.33)
+    assert r.n_accepted[0] == 0 and r.next_token[0] == 1
+    assert abs(r.margin_accept[0] - 0.275) < 1e-12 and abs(r.margin_sample[0] - 0.0005 / 0.15) < 1e-9
+    assert abs(r.margin[0] - 0.0005 / 0.15) < 1e-9
+    # everything accepted: the bonus draw from uniform p, u = .3 is .05 into token 1's cell [.25, .5)
+    r = run([0.3, 0.1, 0.6, 0.2], 0.3)
+    assert r.n_accepted[0] == 4 and r.next_token[0] == 1
+    assert abs(r.margin_accept[0] - 0.025) < 1e-12 and abs(r.margin_sample[0] - 0.05) < 1e-12
+    # shorter draft: positions at or beyond draft_len are not tested and carry no margin
+    r = run([0.3, 0.1, 0.6249, 0.6251], 0.3, g=2)
+    assert r.n_accepted[0] == 2 and abs(r.margin_accept[0] - 0.325) < 1e-12 and np.isnan(r.margin_a[0, 2:]).all()
+    # nothing drafted: only the bonus draw decides
+    r = run([0.3, 0.1, 0.6, 0.2], 0.9, g=0)
+    assert r.n_accepted[0] == 0 and r.next_token[0] == 3 and math.isinf(r.margin_accept[0])
+    assert abs(r.margin_sample[0] - 0.1) < 1e-12 and abs(r.margin[0] - 0.1) < 1e-12
+
+
 # ---------------------------------------------------------------- residual direction and the output law
 
 @pytest.mark.parametrize("seed", [11, 12, 13])

@@ -35,7 +35,10 @@ def test_draft_step_every_position(svip, name, rows, over):
         r.draft_all(chain=False)
         st = check_draft_rows(d["draft"], w.T, h, w.k, d["u_sample"], r)
         _say(f"  h={h}: {st}")
-        assert st["tok_excluded"] <= 0.5 * st["rows"]
+        # draws inside the margin, by the oracle alone: none at cfg1, 6 % at cfg2, 22-23 % at V >= 128256
+        # (a high-entropy row's cells are about 8e-6 wide there)
+        assert st["tok_excluded"] <= (0.30 if w.V > 100_000 else 0.08) * st["rows"]
+        assert st["stop_excluded"] == 0
 
 
 @pytest.mark.parametrize("name,rows,over", [
@@ -55,15 +58,17 @@ def test_round_chained_draft_then_verify(svip, name, rows, over):
     tokens, dl, lse, mh, ms = oracle_chain(d["draft"], w.T, w.h, d["u_sample"])
     g_tok = r.tokens.cpu().numpy()
     g_dl = r.draft_len.cpu().numpy()
-    st = check_chain(g_tok, g_dl, tokens, dl, mh, ms)
+    st = check_chain(g_tok, g_dl, tokens, dl, mh, ms, draft_cpu=d["draft"], T=w.T, u_sample=d["u_sample"])
     assert (r.stop.cpu().numpy() == 1).all()          # the cap stops everyone by step k-1
     _say(f"  draft_len {g_dl.tolist()} {st}")
-    assert st["len_checked"] >= 0.5 * st["rows"] and st["tok_checked"] >= 1
+    assert st["len_checked"] == st["rows"] and st["tok_checked"] >= 1
+    assert st["tok_excluded"] <= 0.30 * (st["tok_checked"] + st["tok_excluded"]) + 1
     # verify, fed by the GPU's own tokens / lengths / lse
     r.verify(lse="given")
     st = check_verify(d["draft"], d["target"], w.T, g_tok.astype(np.int64), g_dl.astype(np.int64),
                       d["u_accept"], d["u_resample"], r)
     _say(f"  verify {st}")
+    assert st["acc_excluded"] == 0 and st["tok_excluded"] <= 0.2 * st["seqs"] + 1
 
 
 @pytest.mark.parametrize("name,rows,over,glen", [
@@ -100,7 +105,8 @@ def test_verify_all_positions(svip, name, rows, over, glen, lse_mode):
              lse=torch.from_numpy(lse).cuda() if lse_mode == "given" else None)
     st = check_verify(d["draft"], d["target"], w.T, tokens, dl, d["u_accept"], d["u_resample"], r)
     _say(f"  {st} n_accepted={r.n_accepted.cpu().tolist()}")
-    assert st["excluded"] <= 0.5 * st["seqs"] + 1
+    # by the oracle alone: no acceptance test of these workloads is inside the margin, and at most one draw
+    assert st["acc_excluded"] == 0 and st["tok_excluded"] <= 0.2 * st["seqs"] + 1
 
 
 def test_bitwise_determinism(svip):
@@ -149,7 +155,7 @@ def test_full_size_round_as_benchmarked(svip, h):
     rows = list(range(B))            # the oracle does the whole batch in a few seconds
     sub = {key: d[key][rows] for key in ("draft", "target", "u_sample", "u_accept", "u_resample")}
     tokens, odl, olse, mh, ms = oracle_chain(sub["draft"], w.T, h, sub["u_sample"])
-    cst = check_chain(tok, dl, tokens, odl, mh, ms, rows=rows)
+    cst = check_chain(tok, dl, tokens, odl, mh, ms, rows=rows, draft_cpu=sub["draft"], T=w.T, u_sample=sub["u_sample"])
     st = dict(seqs=0, excluded=0, excluded_diff=0, max_rel_a=0.0)
     for n, b in enumerate(rows):
         g = min(int(dl[b]), int(odl[n]))
@@ -161,5 +167,9 @@ def test_full_size_round_as_benchmarked(svip, h):
                      dl[b:b + 1].astype(np.int64), sub["u_accept"][n:n + 1], sub["u_resample"][n:n + 1], _One, stats=st)
     _say(f"full size h={h}: chain {cst}, verify {st}, "
          f"mean draft_len {dl.mean():.2f}, mean n_accepted {nacc.mean():.2f}")
-    assert cst["len_checked"] >= B // 2 and cst["tok_checked"] >= B // 2 and st["seqs"] == len(rows)
-    assert cst["tok_excluded_diff"] <= 0.01 * (cst["tok_checked"] + cst["tok_excluded"]) and st["excluded_diff"] <= 2
+    assert cst["len_checked"] == B and st["seqs"] == len(rows)
+    # inside the margin by the oracle alone: 237 of 1024 draft tokens (h = 4), 44 of 212 (h = 3); no
+    # acceptance test, at most 4 of the 64 correction / bonus draws
+    assert cst["tok_excluded"] <= 0.30 * (cst["tok_checked"] + cst["tok_excluded"])
+    assert st["acc_excluded"] == 0 and st["tok_excluded"] <= 0.1 * B
+    assert cst["tok_excluded_diff"] <= 0.01 * (cst["tok_checked"] + cst["tok_excluded"]) and st["tok_excluded_diff"] <= 2
