@@ -24,8 +24,7 @@
  * General rules
  *   - Every pointer marked "device" is GPU memory of the current HIP device; "host" is CPU
  *     memory.  The caller owns every buffer; the library allocates nothing, frees nothing
- *     and keeps no pointer after a call returns (the benchmark timing hook at the end of
- *     this header, which creates HIP events, is the one exception).
+ *     and keeps no pointer after a call returns.
  *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without synchronising.  Outputs are valid once the stream
  *     has reached that point.
@@ -43,7 +42,11 @@
  *     device data (token id outside [0, V), draft length outside [0, k_max]) are clamped and
  *     recorded in a sticky flag word inside the workspace (svip_workspace_flags).
  *   - `workspace` is device scratch of at least svip_workspace_bytes(B, k_max, V) bytes,
- *     256-byte aligned.  Calls that run concurrently must use different workspaces.
+ *     256-byte aligned, that svip_workspace_reset has cleared once after allocation.  Besides
+ *     partial results it holds, at its end, the counters with which the workgroups of a kernel
+ *     hand a row's remaining work to whichever of them finishes last; every call leaves them
+ *     at zero again.  Pass the same `workspace_bytes` with a workspace on every call.  Calls that
+ *     run concurrently must use different workspaces.
  *   - Same inputs give bit-identical outputs (no floating-point atomics, fixed combine order).
  */
 #ifndef SVIP_H
@@ -95,8 +98,9 @@ typedef enum {
 } svip_call;
 size_t svip_workspace_needed(int call, svip_dtype dtype, int B, int k_max, int V);
 
-/* Zero the sticky flag word (enqueued on the stream).  Call once after allocating a
- * workspace; the two calls below only ever set bits. */
+/* Zero the sticky flag word and the hand-over counters at the end of the workspace (enqueued on
+ * the stream as a fill kernel).  Call once after allocating a workspace, with the size that the
+ * other calls will be given; the calls below only ever set flag bits and leave the counters zero. */
 svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Copy the flag word to *flags_host (host).  Synchronises the stream. */
@@ -329,18 +333,6 @@ svip_status svip_loop_run(const svip_loop_config *config /* host */, int first_r
 svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype dtype, int B, int n_rows,
                              int V, long long seq_stride, long long row_stride, float temperature,
                              int top_k, double top_p, int *kept_out, void *hip_stream);
-
-/*
- * Timing hook for benchmarks: between svip_profile_begin and svip_profile_end every
- * svip_verify call launches its statistics kernel (the pass that streams the target rows,
- * the dominant kernel of the path) with a start and a stop HIP event attached to the launch
- * (hipExtLaunchKernel), which take the kernel's own begin and end on the call's stream, for at
- * most max_samples calls.  svip_profile_end waits for those events, returns the summed kernel
- * time in milliseconds and the number of samples through host pointers, and releases the
- * events.  Process-wide state: not for concurrent use from several threads.
- */
-svip_status svip_profile_begin(int max_samples);
-svip_status svip_profile_end(double *total_ms_host, int *samples_host);
 
 #ifdef __cplusplus
 }

@@ -10,9 +10,16 @@ raises.
     svip.draft_step(logits[:, j], ..., workspace=ws)      # Algorithm 1, drafting loop
     svip.verify(target, draft, ..., workspace=ws)         # Algorithm 1, verification loop
 """
-from .binding import (SvipError, draft_step, load, new_workspace, verify, verify_greedy, pair_stats, warp_logits, PAIR_NSTAT, PAIR_FIELDS, Loop, LoopConfig, LOOP_NSTATE, LOOP_STATE_FIELDS, workspace_bytes, workspace_needed,
-                      workspace_flags, profile_begin, profile_end, MAX_K, FLAG_BAD_TOKEN,
-                      FLAG_BAD_DRAFT_LEN)
+from .binding import (SvipError, draft_step, load, new_workspace, verify, verify_greedy, pair_stats, warp_logits,
+                      PAIR_NSTAT, PAIR_FIELDS, Loop, LoopConfig, LOOP_NSTATE, LOOP_STATE_FIELDS, workspace_bytes,
+                      workspace_needed, workspace_flags, MAX_K, FLAG_BAD_TOKEN, FLAG_BAD_DRAFT_LEN,
+                      bench_time_kernels, bench_events_used, bench_set_tuning, bench_empty_kernel, bench_stream_read,
+                      BENCH_K_DRAFT_STEP,
+                      BENCH_K_VERIFY_STATS, BENCH_K_RESID, BENCH_K_ACCEPT)
 
-__all__ = ["SvipError", "draft_step", "load", "new_workspace", "verify", "verify_greedy", "pair_stats", "warp_logits", "PAIR_NSTAT", "PAIR_FIELDS", "Loop", "LoopConfig", "LOOP_NSTATE", "LOOP_STATE_FIELDS", "workspace_bytes", "workspace_needed",
-           "workspace_flags", "profile_begin", "profile_end", "MAX_K", "FLAG_BAD_TOKEN", "FLAG_BAD_DRAFT_LEN"]
+__all__ = ["SvipError", "draft_step", "load", "new_workspace", "verify", "verify_greedy", "pair_stats", "warp_logits",
+           "PAIR_NSTAT", "PAIR_FIELDS", "Loop", "LoopConfig", "LOOP_NSTATE", "LOOP_STATE_FIELDS", "workspace_bytes",
+           "workspace_needed", "workspace_flags", "MAX_K", "FLAG_BAD_TOKEN", "FLAG_BAD_DRAFT_LEN",
+           "bench_time_kernels", "bench_events_used", "bench_set_tuning", "bench_empty_kernel", "bench_stream_read",
+           "BENCH_K_DRAFT_STEP",
+           "BENCH_K_VERIFY_STATS", "BENCH_K_RESID", "BENCH_K_ACCEPT"]

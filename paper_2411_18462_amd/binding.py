@@ -18,8 +18,11 @@ _DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 # every symbol include/svip.h declares
 EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_needed", "svip_workspace_reset",
            "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_draft_step_greedy",
-           "svip_verify_greedy", "svip_pair_stats", "svip_warp_logits", "svip_loop_workspace_bytes", "svip_loop_init", "svip_loop_run",
-           "svip_profile_begin", "svip_profile_end")
+           "svip_verify_greedy", "svip_pair_stats", "svip_warp_logits", "svip_loop_workspace_bytes", "svip_loop_init", "svip_loop_run")
+# every symbol include/svip_bench.h declares (benchmark and experiment hooks, not the product ABI)
+BENCH_EXPORTS = ("svip_bench_time_kernels", "svip_bench_events_used", "svip_bench_set_tuning", "svip_bench_empty_kernel",
+                 "svip_bench_stream_sink_words", "svip_bench_stream_read")
+BENCH_K_DRAFT_STEP, BENCH_K_VERIFY_STATS, BENCH_K_RESID, BENCH_K_ACCEPT = 0, 1, 2, 3
 
 
 class SvipError(RuntimeError):
@@ -42,6 +45,13 @@ class LoopConfig(ctypes.Structure):
         ("round_log", ctypes.c_void_p), ("check_every", ctypes.c_int),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("hip_stream", ctypes.c_void_p),
     ]
+
+
+class BenchTuning(ctypes.Structure):
+    """svip_bench_tuning of include/svip_bench.h, field for field."""
+    _fields_ = [("draft_slices", ctypes.c_int), ("stats_slices", ctypes.c_int), ("resid_slices", ctypes.c_int),
+                ("pair_slices", ctypes.c_int), ("min_workgroups", ctypes.c_int),
+                ("even_tiles_per_slice", ctypes.c_int), ("warp_no_shortcut", ctypes.c_int), ("draft_no_tile_masses", ctypes.c_int), ("stats_workgroups", ctypes.c_int)]
 
 
 def load():
@@ -83,10 +93,18 @@ def load():
     lib.svip_loop_init.argtypes = [ctypes.POINTER(LoopConfig)]
     lib.svip_loop_run.restype = i
     lib.svip_loop_run.argtypes = [ctypes.POINTER(LoopConfig), i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
-    lib.svip_profile_begin.restype = i
-    lib.svip_profile_begin.argtypes = [i]
-    lib.svip_profile_end.restype = i
-    lib.svip_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i)]
+    lib.svip_bench_time_kernels.restype = i
+    lib.svip_bench_time_kernels.argtypes = [i, ctypes.POINTER(vp), ctypes.POINTER(vp), i]
+    lib.svip_bench_events_used.restype = i
+    lib.svip_bench_events_used.argtypes = [i]
+    lib.svip_bench_empty_kernel.restype = i
+    lib.svip_bench_empty_kernel.argtypes = [vp]
+    lib.svip_bench_stream_sink_words.restype = sz
+    lib.svip_bench_stream_sink_words.argtypes = [sz, i]
+    lib.svip_bench_stream_read.restype = i
+    lib.svip_bench_stream_read.argtypes = [vp, sz, i, vp, vp]
+    lib.svip_bench_set_tuning.restype = i
+    lib.svip_bench_set_tuning.argtypes = [ctypes.POINTER(BenchTuning)]
     _lib = lib
     return lib
 
@@ -369,13 +387,38 @@ class Loop:
         return workspace_flags(self.workspace)
 
 
-def profile_begin(max_samples: int):
-    """Start timing the statistics kernel of the next `max_samples` verify calls."""
-    _check(load().svip_profile_begin(int(max_samples)))
+def bench_time_kernels(kernel_class: int, start_events, stop_events):
+    """svip_bench_time_kernels: the next len(start_events) launches of that kernel class carry the given
+    hipEvent_t handles (integers; created, kept alive and read by the caller).  Empty lists remove them.
+    Returns the ctypes arrays, which the caller must keep alive while they are registered."""
+    n = len(start_events)
+    assert n == len(stop_events)
+    a0 = (ctypes.c_void_p * max(n, 1))(*start_events)
+    a1 = (ctypes.c_void_p * max(n, 1))(*stop_events)
+    _check(load().svip_bench_time_kernels(int(kernel_class), a0, a1, n))
+    return a0, a1
 
 
-def profile_end():
-    """(total milliseconds, samples) of the statistics kernel since profile_begin."""
-    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
-    _check(load().svip_profile_end(ctypes.byref(ms), ctypes.byref(n)))
-    return ms.value, n.value
+def bench_events_used(kernel_class: int) -> int:
+    return int(load().svip_bench_events_used(int(kernel_class)))
+
+
+def bench_set_tuning(**fields):
+    """svip_bench_set_tuning: launch-shape overrides for experiments; no arguments = the library's own choices."""
+    t = BenchTuning(**{k: int(v) for k, v in fields.items()})
+    _check(load().svip_bench_set_tuning(ctypes.byref(t) if fields else None))
+
+
+def bench_empty_kernel(stream=None):
+    _check(load().svip_bench_empty_kernel(_stream(stream)))
+
+
+def bench_stream_read(buf: torch.Tensor, sink: torch.Tensor = None, vectors_per_thread: int = 8, stream=None):
+    """svip_bench_stream_read over the bytes of a contiguous device tensor; returns the sink tensor."""
+    nbytes = buf.numel() * buf.element_size()
+    words = int(load().svip_bench_stream_sink_words(nbytes, int(vectors_per_thread)))
+    if sink is None:
+        sink = torch.empty(max(words, 1), dtype=torch.int32, device=buf.device)
+    assert sink.numel() >= words and sink.dtype == torch.int32 and buf.is_contiguous()
+    _check(load().svip_bench_stream_read(buf.data_ptr(), nbytes, int(vectors_per_thread), sink.data_ptr(), _stream(stream)))
+    return sink

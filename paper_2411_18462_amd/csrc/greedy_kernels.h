@@ -1,5 +1,6 @@
 // Kernels of svip_verify_greedy (Algorithms 3 and 5).
 #pragma once
+#include "exchange.h"
 #include "kernel_args.h"
 
 namespace svip {
@@ -10,6 +11,7 @@ struct GreedyArgs {
     const void *target;
     long long seq_t, row_stride;
     const int *pos;   // optional [B]: row j of sequence b is trace row pos[b] + j
+    const unsigned char *skip;   // optional [B]: sequences to leave alone
     int B, k;
     Geo geo;
     const int *tokens;
@@ -20,27 +22,11 @@ struct GreedyArgs {
     unsigned *flags;
 };
 
-// grid (sequences * (k+1) * slices): first maximum of slice s of target row (b, j), j <= draft_len[b].
-template <typename DT>
-__global__ __launch_bounds__(WG) void k_argmax(GreedyArgs a)
+// One wave: lane = position.  argmax of target row j from its slice keys; position j < draft_len is accepted iff
+// that argmax is the draft token; a ballot finds the first failure r, and the correction (or, if none
+// failed, the bonus token) is the argmax of row r.
+__device__ __forceinline__ void accept_greedy_sequence(const GreedyArgs &a, int b, int lane)
 {
-    __shared__ unsigned long long lds[NWAVE];
-    const int y = blockIdx.x / a.geo.ns, s = blockIdx.x - y * a.geo.ns;
-    const int b = y / (a.k + 1), j = y - b * (a.k + 1);
-    const int g = clamp_len(a.draft_len[b], a.k);
-    if (j > g) return;
-    const DT *row = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, j);
-    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    const unsigned long long key = slice_argmax<DT>(row, a.geo.V, tb, te, lds);
-    if (threadIdx.x == 0) a.keys[(size_t)y * a.geo.ns + s] = key;
-}
-
-// grid (sequences), one wave: lane = position.  argmax of target row j from its slice keys;
-// position j < draft_len is accepted iff that argmax is the draft token; a ballot finds the first
-// failure r, and the correction (or, if none failed, the bonus token) is the argmax of row r.
-__global__ __launch_bounds__(64) void k_accept_greedy(GreedyArgs a)
-{
-    const int b = blockIdx.x, lane = threadIdx.x;
     const int graw = a.draft_len[b];
     const int g = clamp_len(graw, a.k);
     if (graw != g && lane == 0) atomicOr(a.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
@@ -52,7 +38,13 @@ __global__ __launch_bounds__(64) void k_accept_greedy(GreedyArgs a)
         if (j <= g) {
             const unsigned long long *kr = a.keys + ((size_t)b * (a.k + 1) + j) * a.geo.ns;
             unsigned long long best = 0ull;
-            for (int s = 0; s < a.geo.ns; ++s) best = kr[s] > best ? kr[s] : best;
+            for (int s0 = 0; s0 < a.geo.ns; s0 += 8) {          // eight loads in flight at a time
+                unsigned long long kk[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) kk[u] = s0 + u < a.geo.ns ? kr[s0 + u] : 0ull;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) best = kk[u] > best ? kk[u] : best;
+            }
             am = argmax_index(best);
             if (j < g) {
                 const int x = a.tokens[(size_t)b * a.k + j];
@@ -74,6 +66,29 @@ __global__ __launch_bounds__(64) void k_accept_greedy(GreedyArgs a)
         a.n_accepted[b] = r;
         a.next_token[b] = next;
     }
+}
+
+// grid (sequences * (k+1) * slices): first maximum of slice s of target row (b, j), j <= draft_len[b].
+template <typename DT>
+__global__ __launch_bounds__(WG) void k_argmax(GreedyArgs a)
+{
+    __shared__ unsigned long long lds[NWAVE];
+    const int y = blockIdx.x / a.geo.ns, s = blockIdx.x - y * a.geo.ns;
+    const int b = y / (a.k + 1), j = y - b * (a.k + 1);
+    if (a.skip && a.skip[b]) return;
+    const int g = clamp_len(a.draft_len[b], a.k);
+    if (j > g) return;
+    const DT *row = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, j);
+    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const unsigned long long key = slice_argmax<DT>(row, a.geo.V, tb, te, lds);
+    if (threadIdx.x == 0) a.keys[(size_t)y * a.geo.ns + s] = key;
+}
+
+// grid (sequences), one wave.
+__global__ __launch_bounds__(64) void k_accept_greedy(GreedyArgs a)
+{
+    if (a.skip && a.skip[blockIdx.x]) return;
+    accept_greedy_sequence(a, blockIdx.x, threadIdx.x);
 }
 
 }  // namespace svip

@@ -7,7 +7,7 @@ namespace svip {
 
 // ---- workspace layout ----------------------------------------------------------------
 
-struct SeqRec {          // what k_accept hands to the residual kernels, one per sequence
+struct SeqRec {          // what the acceptance test hands to the residual kernel, one per sequence
     double Lp;           // logsumexp(target row r) * log2(e)
     double Lq;           // logsumexp(draft row r) * log2(e) (residual mode only)
     int r;               // target row to sample from (first rejection, or draft_len for a bonus)
@@ -16,30 +16,45 @@ struct SeqRec {          // what k_accept hands to the residual kernels, one per
 
 struct Workspace {
     unsigned *flags;     // sticky device-data flags
+    unsigned *tickets;   // END of the ticket counters (see ticket()): they grow downwards from here
     SeqRec *rec;         // [B]
-    double *mass;        // [B][MAX_SLICES][2] residual mass, target mass per slice
+    double *mass;        // [B][slices of the residual pass] tile masses (ResidSlot), verification only
     Partial *part;       // [stat rows][ns] slice statistics
 };
 
 constexpr int MAX_BATCH = 1 << 20;               // sequences per call (grids are one-dimensional)
 constexpr size_t HEADER_BYTES = 256;
+constexpr int TICKETS_PER_ROW = 3;               // draft step / statistics pass of verify / residual pass
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static size_t ws_rec_bytes(int B) { return align256((size_t)B * sizeof(SeqRec)); }
-static size_t ws_mass_bytes(int B) { return align256((size_t)B * MAX_SLICES * 2 * sizeof(double)); }
+static size_t ws_mass_bytes(int B, int slices) { return align256((size_t)B * slices * 2 * TILE_MASSES * sizeof(double)); }
+static size_t ws_ticket_bytes(int B) { return align256((size_t)B * TICKETS_PER_ROW * sizeof(unsigned)); }
 
-static Workspace carve(void *ws, int B)
+// Layout: flag word | records | slice masses | slice statistics ...            ... ticket counters.
+// The counters sit at the END of the workspace (the given size rounded down to 256 bytes) and counter
+// t of row b lies 3 b + t + 1 words below that end, whatever the batch size of the call: regions at the
+// front never reach them (every call checks front + counters <= size), so they keep the zeros that
+// svip_workspace_reset wrote and that every kernel restores, also when calls of different batch sizes
+// share a workspace.
+static Workspace carve(void *ws, size_t bytes, int B, int mass_slices)
 {
     char *p = static_cast<char *>(ws);
     Workspace w;
     w.flags = reinterpret_cast<unsigned *>(p);
+    w.tickets = reinterpret_cast<unsigned *>(p + (bytes & ~(size_t)255));
     p += HEADER_BYTES;
     w.rec = reinterpret_cast<SeqRec *>(p);
     p += ws_rec_bytes(B);
     w.mass = reinterpret_cast<double *>(p);
-    p += ws_mass_bytes(B);
+    p += ws_mass_bytes(B, mass_slices);
     w.part = reinterpret_cast<Partial *>(p);
     return w;
+}
+enum { TICKET_DRAFT = 0, TICKET_STATS = 1, TICKET_RESID = 2 };
+__device__ __forceinline__ unsigned *ticket(unsigned *tickets_end, int b, int t)
+{
+    return tickets_end - ((size_t)b * TICKETS_PER_ROW + t + 1);
 }
 
 // ---- kernel arguments ------------------------------------------------------------------
@@ -64,7 +79,8 @@ struct DraftArgs {
     unsigned char *stop;
     int *draft_len;
     long long io_stride;
-    Partial *part;
+    void *part;             // [B][ns] slice records (DraftSlot)
+    unsigned *tickets;      // end of the workspace's ticket counters
 };
 
 struct VerifyArgs {
@@ -72,10 +88,12 @@ struct VerifyArgs {
     const void *draft;
     long long seq_t, seq_d, row_stride;
     const int *pos;   // optional [B]: row j of sequence b is trace row pos[b] + j
+    const unsigned char *skip;   // optional [B]: sequences to leave alone (no read, no write, no ticket)
     int B, k;
     int kd;        // draft rows per sequence in the statistics pass: k if the draft logsumexps are recomputed, else 0
     int bonus;     // 1: the statistics pass also covers target row draft_len (verification), 0: rows j < draft_len only
     Geo geo;       // slicing of the statistics pass
+    long long stat_items;   // statistics rows * slices: the work items of the statistics pass
     Geo geo_s;     // slicing of the sampling pass (slices of at most LOCATE_UNROLL tiles when possible)
     Scale sc;
     const int *tokens;

@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "stage_clock.h"
 #include "wave_ops.h"
 
 namespace svip {
@@ -23,7 +24,8 @@ namespace svip {
 constexpr int WG = 256;              // threads per workgroup
 constexpr int NWAVE = WG / 64;
 constexpr int MAX_SLICES = 64;       // a wave merges one slice per lane
-constexpr int LOCATE_UNROLL = 4;     // tiles per batch of the inverse-CDF search
+constexpr int LOCATE_UNROLL = 4;     // tiles per batch of the inverse-CDF search over a whole slice
+constexpr int TILE_MASSES = 4;       // slices of at most this many tiles also report the mass of every tile
 constexpr float X_FLOOR = -200.0f;   // exp2 of anything below is 0 in fp32; also squashes NaN from -inf logits
 
 struct bf16 { uint16_t bits; };   // storage types: the bits only, widened to fp32 on load
@@ -241,8 +243,8 @@ struct Partial {
 };
 
 // Smallest token index among the batch's elements equal to v (-1 if none); z[u] is vector
-// (t0 + u) * WG + tid of the row.
-template <int N, int NU>
+// (t0 + u) * TW + (thread index within the tile) of the row, TW the tile width in vectors.
+template <int N, int NU, int TW = WG>
 __device__ __forceinline__ int first_equal(const float (&z)[NU][N], float v, int t0)
 {
     int found = -1;
@@ -250,7 +252,7 @@ __device__ __forceinline__ int first_equal(const float (&z)[NU][N], float v, int
     for (int u = NU - 1; u >= 0; --u) {
 #pragma unroll
         for (int e = N - 1; e >= 0; --e)
-            if (z[u][e] == v) found = ((t0 + u) * WG + (int)threadIdx.x) * N + e;
+            if (z[u][e] == v) found = ((t0 + u) * TW + (int)(threadIdx.x & (TW - 1))) * N + e;
     }
     return found;
 }
@@ -263,16 +265,19 @@ __device__ __forceinline__ int first_equal(const float (&z)[NU][N], float v, int
 // loop sums fract(w) (fract(1) = 0, fract(w) = w below 1) beside w itself; the difference of the two
 // batch sums is the batch's count of ones up to rounding far below 1/2.  With ARG, idx follows the
 // smallest index that holds m: it moves only when the maximum strictly increases, so earlier equal
-// values keep it; t0 is the batch's first tile.
-template <int N, int NU, bool ARG>
+// values keep it; t0 is the batch's first tile and TW the tile width in vectors.
+// With TILES, g[] additionally receives the sum of the weights of every tile (g[u0 + u] for the
+// batch's tile u, relative to the thread's running maximum like S), which lets the sampler go
+// straight to the tile that holds its target instead of searching a slice.
+template <int N, int NU, bool ARG, bool TILES, int TW>
 __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, float &ones, float &S, float &t,
-                                           const Scale &sc, int &idx, int t0)
+                                           const Scale &sc, int &idx, int t0, float (&g)[TILE_MASSES], int u0)
 {
     float mb = tree_max<N>(z[0]);
 #pragma unroll
     for (int u = 1; u < NU; ++u) mb = vmax(mb, tree_max<N>(z[u]));
     if (mb > m) {
-        if (ARG) idx = first_equal<N, NU>(z, mb, t0);
+        if (ARG) idx = first_equal<N, NU, TW>(z, mb, t0);
         if (m != neg_inf()) {
             const float xd = scaled_diff(m, mb, sc);
             const float f = exp2_raw(xd);
@@ -281,6 +286,10 @@ __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, fl
                 t = f * fmaf(xd, all, t);
                 S = f * all;
                 ones = 0.f;
+                if (TILES) {
+#pragma unroll
+                    for (int v = 0; v < TILE_MASSES; ++v) g[v] *= f;
+                }
             }                                   // else: still weight 1 at fp32 resolution, nothing moves
         }
         m = mb;
@@ -299,27 +308,34 @@ __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, fl
         }
         // group sums are formed first, then added to the batch sum: the running sums only
         // ever take one addition per batch
-        Wb += tree_sum<N>(w);
+        const float wt = tree_sum<N>(w);
+        Wb += wt;
         Sb += tree_sum<N>(fr);
         tb += tree_sum<N>(wx);
+        if (TILES) {
+#pragma unroll
+            for (int v = 0; v < TILE_MASSES; ++v) g[v] = (v == u0 + u) ? wt : g[v];
+        }
     }
     ones += rintf(Wb - Sb);
     S += Sb;
     t += tb;
 }
 
-template <typename DT, int NU, bool ARG>
+template <typename DT, int NU, bool ARG, bool TILES>
 __device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, float &ones, float &S, float &t,
-                                            int &idx, const Scale &sc)
+                                            int &idx, const Scale &sc, float (&g)[TILE_MASSES], int u0)
 {
     constexpr int N = VecOf<DT>::N;
     typename RawOf<DT>::type raw[NU];
 #pragma unroll
     for (int u = 0; u < NU; ++u) raw[u] = load_raw<DT>(row, (t0 + u) * WG + (int)threadIdx.x);
+    STAGE_LOADED(10);
     float z[NU][N];
 #pragma unroll
     for (int u = 0; u < NU; ++u) unpack<DT>(raw[u], z[u]);
-    accumulate<N, NU, ARG>(z, m, ones, S, t, sc, idx, t0);
+    accumulate<N, NU, ARG, TILES, WG>(z, m, ones, S, t, sc, idx, t0, g, u0);
+    STAGE(11);
 }
 
 // LDS of one workgroup combination (each field is written once, so two barriers suffice).
@@ -327,31 +343,40 @@ struct CombineLds {
     float m[NWAVE];
     int idx[NWAVE];
     double S[NWAVE], t[NWAVE];
+    double G[NWAVE][TILE_MASSES];
 };
 
 // Workgroup combination of the per-thread (m, ones, S, t): maximum first, then every thread
-// rescales ones + S and t to it and the sums are added in fp64.  Result valid in thread 0.  One call per
-// kernel and LDS block.
-template <bool ARG = false>
+// rescales ones + S and t to it and the sums are added in fp64 (with TILES the tile sums g likewise,
+// into G).  Result valid in thread 0.  One call per kernel and LDS block.
+template <bool ARG, bool TILES>
 __device__ __forceinline__ Partial wg_combine(float m, float ones, float S, float t, const Scale &sc,
-                                              CombineLds &lds, int idx = -1)
+                                              CombineLds &lds, int idx, const float (&g)[TILE_MASSES],
+                                              double (&G)[TILE_MASSES])
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const float mw = wave_max(m);
     if (lane == 0) lds.m[wave] = mw;
     __syncthreads();
+    STAGE(12);
     float mg = lds.m[0];
 #pragma unroll
     for (int w = 1; w < NWAVE; ++w) mg = fmaxf(mg, lds.m[w]);
-    double Sd = 0.0, td = 0.0;
+    double Sd = 0.0, td = 0.0, f = 0.0;
     if (m != neg_inf()) {
         const float xd = scaled_diff(m, mg, sc);
-        const double f = (double)exp2_raw(xd), all = (double)ones + (double)S;      // exact in fp64
+        const double all = (double)ones + (double)S;      // exact in fp64
+        f = (double)exp2_raw(xd);
         Sd = f * all;
         td = f * ((double)t + (double)xd * all);
     }
     Sd = wave_sum(Sd);
     td = wave_sum(td);
+    double Gd[TILE_MASSES];
+    if (TILES) {
+#pragma unroll
+        for (int v = 0; v < TILE_MASSES; ++v) Gd[v] = wave_sum(f * (double)g[v]);
+    }
     int wmin = 0x7FFFFFFF;
     if (ARG) {      // smallest index among the threads that hold the workgroup maximum
         const int cand = (m == mg && idx >= 0) ? idx : 0x7FFFFFFF;
@@ -361,13 +386,21 @@ __device__ __forceinline__ Partial wg_combine(float m, float ones, float S, floa
         lds.S[wave] = Sd;
         lds.t[wave] = td;
         if (ARG) lds.idx[wave] = wmin;
+        if (TILES) {
+#pragma unroll
+            for (int v = 0; v < TILE_MASSES; ++v) lds.G[wave][v] = Gd[v];
+        }
     }
+    STAGE(13);
     __syncthreads();
+    STAGE(14);
     Partial p;
     p.m = mg;
     p.idx = -1;
     p.S = 0.0;
     p.t = 0.0;
+#pragma unroll
+    for (int v = 0; v < TILE_MASSES; ++v) G[v] = 0.0;
     if (tid == 0) {
 #pragma unroll
         for (int w = 0; w < NWAVE; ++w) {
@@ -380,6 +413,13 @@ __device__ __forceinline__ Partial wg_combine(float m, float ones, float S, floa
             for (int w = 1; w < NWAVE; ++w) best = min(best, lds.idx[w]);
             p.idx = best == 0x7FFFFFFF ? -1 : best;
         }
+        if (TILES) {
+#pragma unroll
+            for (int v = 0; v < TILE_MASSES; ++v) {
+#pragma unroll
+                for (int w = 0; w < NWAVE; ++w) G[v] += lds.G[w][v];
+            }
+        }
     }
     return p;
 }
@@ -388,27 +428,31 @@ __device__ __forceinline__ Partial wg_combine(float m, float ones, float S, floa
 // maximum of its own elements (rescaling its sums on the rare increase), so the loop has no
 // barrier; the workgroup combines at the end.  Tiles that lie wholly inside the row are read in
 // unchecked batches of 32 logits per thread (then 4/2/1 vectors); only the row's last tile can be
-// partial and is read with bounds checks.  Result valid in thread 0.
-template <typename DT, bool ARG = false>
+// partial and is read with bounds checks.  With TILES (slices of at most TILE_MASSES tiles) G[v] receives
+// the mass of the slice's tile v relative to the slice maximum.  Result valid in thread 0.
+template <typename DT, bool ARG, bool TILES>
 __device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int te, const Scale &sc,
-                                               CombineLds &lds)
+                                               CombineLds &lds, double (&G)[TILE_MASSES])
 {
     constexpr int N = VecOf<DT>::N, NB = 32 / N;
     const int tid = threadIdx.x;
     float m = neg_inf(), ones = 0.f, S = 0.f, t = 0.f;
+    float g[TILE_MASSES];
+#pragma unroll
+    for (int v = 0; v < TILE_MASSES; ++v) g[v] = 0.f;
     int idx = -1;
     const int fe = min(te, V / (WG * N));      // end of the tiles that are wholly inside the row
     int t0 = tb;
-    for (; t0 + NB <= fe; t0 += NB) stats_batch<DT, NB, ARG>(row, t0, m, ones, S, t, idx, sc);
-    if (NB == 8 && t0 + 4 <= fe) { stats_batch<DT, 4, ARG>(row, t0, m, ones, S, t, idx, sc); t0 += 4; }
-    if (t0 + 2 <= fe) { stats_batch<DT, 2, ARG>(row, t0, m, ones, S, t, idx, sc); t0 += 2; }
-    if (t0 + 1 <= fe) { stats_batch<DT, 1, ARG>(row, t0, m, ones, S, t, idx, sc); t0 += 1; }
+    for (; t0 + NB <= fe; t0 += NB) stats_batch<DT, NB, ARG, TILES>(row, t0, m, ones, S, t, idx, sc, g, t0 - tb);
+    if (NB == 8 && t0 + 4 <= fe) { stats_batch<DT, 4, ARG, TILES>(row, t0, m, ones, S, t, idx, sc, g, t0 - tb); t0 += 4; }
+    if (t0 + 2 <= fe) { stats_batch<DT, 2, ARG, TILES>(row, t0, m, ones, S, t, idx, sc, g, t0 - tb); t0 += 2; }
+    if (t0 + 1 <= fe) { stats_batch<DT, 1, ARG, TILES>(row, t0, m, ones, S, t, idx, sc, g, t0 - tb); t0 += 1; }
     if (t0 < te) {
         float z[1][N];
         unpack<DT>(load_raw_checked(row, t0 * WG + tid, V), z[0]);
-        accumulate<N, 1, ARG>(z, m, ones, S, t, sc, idx, t0);
+        accumulate<N, 1, ARG, TILES, WG>(z, m, ones, S, t, sc, idx, t0, g, t0 - tb);
     }
-    return wg_combine<ARG>(m, ones, S, t, sc, lds, idx);
+    return wg_combine<ARG, TILES>(m, ones, S, t, sc, lds, idx, g, G);
 }
 
 // ---- logsumexp only (statistics pass of verification) -----------------------------------------
@@ -572,29 +616,6 @@ __device__ __forceinline__ unsigned long long slice_argmax(const DT *row, int V,
     return best;
 }
 
-// Merge of up to MAX_SLICES slice partials by one wave (lane s holds slice s; lanes >= ns
-// pass m = -inf).  Returns wave-uniform reference m, and per lane the slice mass M and its
-// t-term, both relative to m; all in fp64.
-struct Merged {
-    float m;     // row maximum of the raw logits
-    double M;    // this lane's slice mass, sum exp2((z - m) c) over the slice
-    double tt;   // this lane's sum exp2((z - m) c) * (z - m) c
-};
-__device__ __forceinline__ Merged merge_lane(float ms, double Ss, double ts, const Scale &sc)
-{
-    Merged r;
-    r.m = wave_max(ms);
-    r.M = 0.0;
-    r.tt = 0.0;
-    if (ms != neg_inf() && Ss > 0.0) {
-        const double xd = ((double)ms - (double)r.m) * sc.c;
-        const double f = exp2(xd);
-        r.M = f * Ss;
-        r.tt = f * (ts + xd * Ss);
-    }
-    return r;
-}
-
 // ---- in-slice inverse CDF ---------------------------------------------------------
 //
 // Finds the smallest token index i inside tiles [tb, te) whose inclusive prefix of weights,
@@ -606,7 +627,7 @@ __device__ __forceinline__ Merged merge_lane(float ms, double Ss, double ts, con
 // (or -1 if the slice has no mass).  All threads of the workgroup must call; the result
 // (token, its weight) is uniform.
 struct LocateLds {
-    double wtot[NWAVE][LOCATE_UNROLL];
+    double wtot[NWAVE][LOCATE_UNROLL];      // sized for the widest batch
     int wkey[NWAVE];
     int wlast[NWAVE];
     int tok;
@@ -617,11 +638,11 @@ constexpr int NOKEY = 0x7FFFFFFF;
 // One batch: w[u] holds the weights of vector (t0 + u) * WG + tid, all zero for absent tiles.
 // Returns true (uniform) if the crossing lies in this batch (L.tok / L.w are then set);
 // otherwise adds the batch mass to `run`.
-template <int N>
-__device__ __forceinline__ bool locate_batch(const float (&w)[LOCATE_UNROLL][N], int t0, int ntile,
+template <int N, int LU>
+__device__ __forceinline__ bool locate_batch(const float (&w)[LU][N], int t0, int ntile,
                                              double target, double &run, int &last, LocateLds &L)
 {
-    constexpr int LU = LOCATE_UNROLL;
+    static_assert(LU <= LOCATE_UNROLL, "batch wider than the LDS block");
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     float g[LU];
     double incl[LU];
@@ -728,7 +749,7 @@ __device__ __forceinline__ void locate_fallback(WF &wf, int last, LocateLds &L)
     __syncthreads();
 }
 
-// Search over tiles [tb, te) with the weights fetched by the functor wf:
+// Search over tiles [tb, te), LU tiles per batch, with the weights fetched by the functor wf:
 // wf.load(vi) / wf.load_checked(vi) fetch the raw vector(s) and wf.weights(pack, w) turns them
 // into the N weights of vector vi (fp32, >= 0).
 struct NoHook {
@@ -737,11 +758,10 @@ struct NoHook {
 
 // `between` runs once, after the loads of the first batch have been issued and before their data is
 // used: work that does not depend on the search hides behind the memory round trip there.
-template <int N, typename WF, typename Hook = NoHook>
+template <int N, int LU, typename WF, typename Hook = NoHook>
 __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double target, LocateLds &L,
                                                float *weight_out, Hook between = Hook())
 {
-    constexpr int LU = LOCATE_UNROLL;
     const int tid = threadIdx.x;
     const int fe = min(te, wf.V / (WG * N));   // end of the tiles wholly inside the row
     double run = 0.0;
@@ -765,7 +785,7 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
                 for (int e = 0; e < N; ++e) w[u][e] = 0.f;
             }
         }
-        found = locate_batch<N>(w, t0, min(LU, te - t0), target, run, last, L);
+        found = locate_batch<N, LU>(w, t0, min(LU, te - t0), target, run, last, L);
     }
     if (!found) locate_fallback<N>(wf, last, L);
     *weight_out = L.w;

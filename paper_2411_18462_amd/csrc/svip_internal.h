@@ -40,6 +40,7 @@ struct VerifyCall {
     int B, k_max, V;
     long long seq_stride_t, seq_stride_d, row_stride;
     const int *pos;              // device [B] or nullptr: row j of sequence b is trace row pos[b] + j
+    const unsigned char *skip;   // device [B] or nullptr: sequences with skip[b] != 0 are neither read nor written
     float temperature;
     const int *draft_tokens;
     const int *draft_len;

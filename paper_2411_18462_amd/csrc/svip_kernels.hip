@@ -1,15 +1,14 @@
 // SVIP hot path for MI355X (gfx950): launch code and the C ABI declared in include/svip.h; the kernels
-// live in draft_kernels.h, verify_kernels.h, greedy_kernels.h and pair_kernels.h.
+// live in draft_kernels.h, verify_kernels.h, greedy_kernels.h, pair_kernels.h and warp_kernels.h.
 //
-// svip_draft_step  =  k_draft_stats    grid (slices, rows)       per-slice (m, S, t) of every active row
-//                     k_draft_finish   grid (rows)               merge, entropy, stop test, inverse CDF
-//   (greedy)          k_draft_stats<ARG> + k_draft_finish_greedy     token = first maximum, no search
-// svip_verify      =  k_verify_stats   grid (slices, stat rows)  per-slice (reference, sum) of every needed row
-//                     k_accept         grid (sequences), 1 wave  p/q test, ballot scan for the first rejection
-//                                      (up to 16 sequences: done by the first wave of every k_resid_mass workgroup)
-//                     k_resid_mass     grid (slices, sequences)  slice masses of the residual / bonus row
-//                     k_resid_finish   grid (sequences)          inverse CDF of the residual / bonus row
-// svip_verify_greedy = k_argmax        grid (slices, target rows) first maximum per slice, no exponentials
+// svip_draft_step  =  k_draft_step     grid (rows * slices)      per-slice (m, S, t) of every active row; the
+//                                      workgroup that finishes a row last merges its slices: entropy, stop
+//                                      test, inverse CDF (greedy: the first maximum, no search)
+// svip_verify      =  k_verify_stats   grid (stat rows * slices) per-slice (reference, sum) of every needed row
+//                     k_accept         grid (sequences), 1 wave  p/q tests, ballot scan for the first rejection
+//                     k_resid          grid (sequences * slices) slice masses of the residual / bonus row; the
+//                                      workgroup that finishes a sequence last draws the token
+// svip_verify_greedy = k_argmax        grid (target rows * slices) first maximum per slice, no exponentials
 //                     k_accept_greedy  grid (sequences), 1 wave  argmax p == x test, ballot, correction = argmax p
 //
 // svip_pair_stats  =  k_verify_stats   (rows j < draft_len of both models), k_pair_L (logsumexps),
@@ -19,9 +18,10 @@
 // svip_warp_logits =  k_warp           grid (rows), 1024 threads  top-k / top-p thresholds by radix select, masked copy
 //
 // The passes are bound by HBM reads of the logits; there is no dense contraction, hence no MFMA.
-// Kernels of one call are ordered by the stream only (no spinning, no device-side waits), and
-// each small kernel issues all of its independent loads before the first dependent one, because
-// at small batches a step is bound by round trips to memory rather than by bandwidth.
+// Nothing spins or waits on the device: kernels of one call are ordered by the stream, and inside a
+// kernel the "last workgroup" hand-over of exchange.h lets a row's remaining work follow its slices
+// without a second launch.  Each finishing step issues all of its independent loads before the first
+// dependent one, because at small batches a step is bound by round trips to memory, not by bandwidth.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <math.h>
@@ -29,6 +29,7 @@
 #include <stdlib.h>
 
 #include "../../include/svip.h"
+#include "../../include/svip_bench.h"
 #include "row_math.h"
 #include "svip_internal.h"
 
@@ -42,15 +43,54 @@
 
 namespace svip {
 
-__global__ void k_zero(unsigned *p) { *p = 0u; }
+// svip_workspace_reset: the flag word and the ticket counters at the end of the workspace.
+struct ZeroArgs {
+    unsigned *flags;
+    uint4 *tail;
+    size_t n16;
+};
+__global__ void k_zero(ZeroArgs z)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) *z.flags = 0u;
+    const uint4 zero = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < z.n16; i += (size_t)gridDim.x * blockDim.x)
+        z.tail[i] = zero;
+}
+
+// Reference kernels of the benchmark hooks: an empty launch, and a read-only stream with the access
+// pattern of the statistics passes (256-thread workgroups, NV 16-byte non-temporal loads per thread, a
+// wave reads 1 KiB contiguous per load) that only folds what it read into one word per wave.
+__global__ __launch_bounds__(64) void k_empty(int) {}
+
+struct StreamArgs {
+    const u32x4 *buf;
+    size_t nvec;
+    unsigned *sink;
+};
+template <int NV>
+__global__ __launch_bounds__(WG) void k_stream_read(StreamArgs a)
+{
+    const size_t base = (size_t)blockIdx.x * (WG * NV) + threadIdx.x;
+    u32x4 v[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const size_t i = base + (size_t)u * WG;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        v[u] = i < a.nvec ? __builtin_nontemporal_load(a.buf + i) : zero;
+    }
+    unsigned x = 0u;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) x ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    x = (unsigned)wave_reduce((int)x, OpMax{});
+    if ((threadIdx.x & 63) == 0) a.sink[(size_t)blockIdx.x * NWAVE + (threadIdx.x >> 6)] = x;
+}
 
 // ---- host side -------------------------------------------------------------------------------
 
-static int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return v && *v ? atoi(v) : dflt;
-}
+// Launch-shape overrides for experiments (svip_bench_set_tuning; all zero = the library's own choice).
+// Workspace sizes are always computed for the library's own choice; a forced shape that needs more than
+// the workspace holds is rejected by the call.
+static svip_bench_tuning g_tune = {0, 0, 0, 0, 0, 0, 0, 0, 0};
 
 // Slices per row: enough workgroups to fill 256 CUs several times over, at most MAX_SLICES,
 // and (want_one_batch) slices of at most LOCATE_UNROLL tiles so the sampler scans one batch.
@@ -66,7 +106,7 @@ static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int for
         // 900 workgroups (few rows, or short rows) shorter slices win, down to a single tile (one row
         // of 128K bf16 logits: 6.5 us a step against 7.5 us; 64 rows of 32000: 8.5 against 10.2)
         const long long want = (2048 + rows - 1) / rows;
-        const long long floor_wg = env_int("SVIP_MIN_WORKGROUPS", 900);
+        const long long floor_wg = g_tune.min_workgroups > 0 ? g_tune.min_workgroups : 900;
         for (;;) {
             long long cap = g.ntiles / min_tiles;
             if (cap < 1) cap = 1;
@@ -90,7 +130,7 @@ static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int for
     g.tps = (g.ntiles + (int)ns - 1) / (int)ns;
     // an odd number of tiles per slice staggers the slices' start addresses over the memory
     // channels; slices that start a power of two apart measured up to 15 % slower
-    if (!want_one_batch && g.tps > 1 && (g.tps & 1) == 0 && env_int("SVIP_EVEN_TPS", 0) == 0) g.tps += 1;
+    if (!want_one_batch && g.tps > 1 && (g.tps & 1) == 0 && !g_tune.even_tiles_per_slice) g.tps += 1;
     g.ns = (g.ntiles + g.tps - 1) / g.tps;
     return g;
 }
@@ -122,50 +162,76 @@ static void by_dtype(svip_dtype d, F f)
     else f(float{});
 }
 
-static svip_status check_launch()
-{
-    return hipGetLastError() == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
-}
-
-// benchmark timing hook (see svip_profile_begin)
-struct Profile {
-    hipEvent_t *ev = nullptr;   // pairs: start, stop
-    int cap = 0, used = 0;
+// Benchmark timing hook (svip_bench_time_kernels): caller-owned HIP events, attached pair by pair to
+// the launches of one kernel class.
+struct KernelTimer {
+    void *const *start = nullptr, *const *stop = nullptr;
+    int n = 0, used = 0;
 };
-static Profile g_prof;
+static KernelTimer g_timer[SVIP_BENCH_KERNEL_CLASSES];
+
+// One kernel launch on the stream; the launch's own status is returned (an error some earlier,
+// unrelated HIP call left behind is neither consumed nor reported).  `cls` names the kernel class for
+// the timing hook.
+template <typename A>
+static bool launch(void (*kernel)(A), unsigned grid, unsigned block, hipStream_t st, const A &args, int cls = -1)
+{
+    A copy = args;
+    void *argv[] = {&copy};
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (cls >= 0 && g_timer[cls].used < g_timer[cls].n) {
+        e0 = static_cast<hipEvent_t>(g_timer[cls].start[g_timer[cls].used]);
+        e1 = static_cast<hipEvent_t>(g_timer[cls].stop[g_timer[cls].used]);
+        ++g_timer[cls].used;
+    }
+    if (!e0)        // the plain launch is the one stream capture records
+        return hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(grid), dim3(block), argv, 0, st) == hipSuccess;
+    return hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(grid), dim3(block), argv, 0, st, e0, e1, 0) ==
+           hipSuccess;
+}
 
 // ---- workspace each call needs (its own geometry; svip_workspace_bytes bounds them all) -------
 
-static size_t need_draft(int B, int V, int vec)
+// flag word + records + ticket counters + slice masses of the residual pass (mass_slices per sequence)
+static size_t ws_fixed_bytes(int B, int mass_slices)
 {
-    const Geo g = make_geo(V, vec, B, true, env_int("SVIP_DRAFT_SLICES", 0));
-    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + (size_t)B * g.ns * sizeof(Partial);
-}
-static size_t need_verify_greedy(int B, int k, int V, int vec)
-{
-    const long long rows = (long long)B * (k + 1);
-    const Geo g = make_geo(V, vec, rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + (size_t)rows * g.ns * sizeof(unsigned long long);
-}
-static size_t need_verify(int B, int k, int V, int vec, bool recompute_lse)
-{
-    const long long stat_rows = (long long)B * ((recompute_lse ? k : 0) + k + 1);
-    const Geo g = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + (size_t)stat_rows * g.ns * sizeof(Partial);
-}
-static size_t need_pair(int B, int k, int V, int vec, bool recompute_lse, size_t *part_bytes, size_t *L_bytes)
-{
-    const long long stat_rows = (long long)B * ((recompute_lse ? k : 0) + k + 1), pos = (long long)B * k;
-    const Geo g = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    const Geo g2 = make_geo(V, vec, pos, false, env_int("SVIP_PAIR_SLICES", 0));
-    const size_t pb = align256((size_t)stat_rows * g.ns * sizeof(Partial));
-    const size_t lb = align256((size_t)pos * 2 * sizeof(double));
-    if (part_bytes) *part_bytes = pb;
-    if (L_bytes) *L_bytes = lb;
-    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + pb + lb + (size_t)pos * g2.ns * 3 * sizeof(double);
+    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B, mass_slices) + ws_ticket_bytes(B);
 }
 
+static size_t need_draft(int B, const Geo &g) { return ws_fixed_bytes(B, 0) + align256((size_t)B * g.ns * sizeof(DraftSlot)); }
+static size_t need_verify_greedy(int B, int k, const Geo &g)
+{
+    return ws_fixed_bytes(B, 0) + align256((size_t)B * (k + 1) * g.ns * sizeof(unsigned long long));
+}
+static size_t need_verify(int B, int k, bool recompute_lse, const Geo &g, const Geo &gs)
+{
+    const size_t stat_rows = (size_t)B * ((recompute_lse ? k : 0) + k + 1);
+    return ws_fixed_bytes(B, gs.ns) + align256(stat_rows * g.ns * sizeof(Partial));
+}
+static size_t need_pair(int B, int k, bool recompute_lse, const Geo &g, const Geo &g2, size_t *part_bytes,
+                        size_t *L_bytes)
+{
+    const size_t stat_rows = (size_t)B * ((recompute_lse ? k : 0) + k + 1), pos = (size_t)B * k;
+    const size_t pb = align256(stat_rows * g.ns * sizeof(Partial));
+    const size_t lb = align256(pos * 2 * sizeof(double));
+    if (part_bytes) *part_bytes = pb;
+    if (L_bytes) *L_bytes = lb;
+    return ws_fixed_bytes(B, 0) + pb + lb + align256(pos * g2.ns * 3 * sizeof(double));
+}
+
+// The slicing each pass uses (forced = an experiment's override, 0 = the library's choice).
+static Geo geo_draft(int B, int V, int vec, int forced) { return make_geo(V, vec, B, true, forced); }
+static Geo geo_stats(long long stat_rows, int V, int vec, int forced) { return make_geo(V, vec, stat_rows, false, forced); }
+// the residual pass: slices of four tiles like the draft step (at 64 sequences of 128K logits, 16 slices of
+// 4 tiles take 13 us, 32 slices of 2 tiles 16 us, 8 slices 20 us, one tile per slice 26 us)
+static Geo geo_resid(int B, int V, int vec, int forced) { return make_geo(V, vec, B, true, forced, 4); }
+
 // ---- the calls behind the entry points ---------------------------------------------------------
+
+static bool workspace_ok(const void *ws, size_t have, size_t need)
+{
+    return ws && (reinterpret_cast<uintptr_t>(ws) & 255u) == 0 && (have & ~(size_t)255) >= need;
+}
 
 svip_status draft_step_call(const DraftCall &c)
 {
@@ -179,11 +245,9 @@ svip_status draft_step_call(const DraftCall &c)
     if (!(c.temperature > 0.f) || !isfinite(c.temperature) || !(c.h >= 0.f)) return SVIP_ERR_PARAM;
 
     DraftArgs a;
-    a.geo = make_geo(c.V, vec, c.B, true, env_int("SVIP_DRAFT_SLICES", 0));
-    const size_t need = need_draft(c.B, c.V, vec);
-    if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
-        return SVIP_ERR_WORKSPACE;
-    const Workspace w = carve(c.workspace, c.B);
+    a.geo = geo_draft(c.B, c.V, vec, g_tune.draft_slices);
+    if (!workspace_ok(c.workspace, c.workspace_bytes, need_draft(c.B, a.geo))) return SVIP_ERR_WORKSPACE;
+    const Workspace w = carve(c.workspace, c.workspace_bytes, c.B, 0);
     a.logits = c.logits;
     a.row_stride = c.row_stride;
     a.pos = c.pos;
@@ -204,19 +268,18 @@ svip_status draft_step_call(const DraftCall &c)
     a.draft_len = c.draft_len_out;
     a.io_stride = c.io_stride;
     a.part = w.part;
+    a.tickets = w.tickets;
     hipStream_t st = static_cast<hipStream_t>(c.stream);
-    const dim3 grid((unsigned)a.geo.ns * (unsigned)c.B);
+    const unsigned grid = (unsigned)a.geo.ns * (unsigned)c.B;
+    bool ok = false;
+    const bool tiles = a.geo.tps <= TILE_MASSES && !g_tune.draft_no_tile_masses;      // short slices: the search goes straight to one tile
     by_dtype(c.dtype, [&](auto tag) {
         using DT = decltype(tag);
-        if (c.greedy) {
-            hipLaunchKernelGGL((k_draft_stats<DT, true>), grid, dim3(WG), 0, st, a);
-            hipLaunchKernelGGL(k_draft_finish_greedy, dim3(c.B), dim3(64), 0, st, a);
-        } else {
-            hipLaunchKernelGGL((k_draft_stats<DT, false>), grid, dim3(WG), 0, st, a);
-            hipLaunchKernelGGL(k_draft_finish<DT>, dim3(c.B), dim3(WG), 0, st, a);
-        }
+        if (c.greedy) ok = launch(k_draft_step<DT, true, false>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STEP);
+        else if (tiles) ok = launch(k_draft_step<DT, false, true>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STEP);
+        else ok = launch(k_draft_step<DT, false, false>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STEP);
     });
-    return check_launch();
+    return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
 
 static svip_status verify_greedy_call(const VerifyCall &c)
@@ -231,11 +294,9 @@ static svip_status verify_greedy_call(const VerifyCall &c)
     const int vec = vec_of(c.dtype);
     if (!aligned16(c.target) || c.row_stride % vec != 0 || c.seq_stride_t % vec != 0) return SVIP_ERR_ALIGN;
     GreedyArgs a;
-    a.geo = make_geo(c.V, vec, rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    const size_t need = need_verify_greedy(c.B, c.k_max, c.V, vec);
-    if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
-        return SVIP_ERR_WORKSPACE;
-    const Workspace w = carve(c.workspace, c.B);
+    a.geo = geo_stats(rows, c.V, vec, g_tune.stats_slices);
+    if (!workspace_ok(c.workspace, c.workspace_bytes, need_verify_greedy(c.B, c.k_max, a.geo))) return SVIP_ERR_WORKSPACE;
+    const Workspace w = carve(c.workspace, c.workspace_bytes, c.B, 0);
     a.target = c.target;
     a.seq_t = c.seq_stride_t;
     a.row_stride = c.row_stride;
@@ -246,13 +307,16 @@ static svip_status verify_greedy_call(const VerifyCall &c)
     a.draft_len = c.draft_len;
     a.n_accepted = c.n_accepted_out;
     a.next_token = c.next_token_out;
+    a.skip = c.skip;
     a.keys = reinterpret_cast<unsigned long long *>(w.part);
     a.flags = w.flags;
     hipStream_t st = static_cast<hipStream_t>(c.stream);
-    const dim3 grid((unsigned)(rows * a.geo.ns));
-    by_dtype(c.dtype, [&](auto tag) { hipLaunchKernelGGL(k_argmax<decltype(tag)>, grid, dim3(WG), 0, st, a); });
-    hipLaunchKernelGGL(k_accept_greedy, dim3(c.B), dim3(64), 0, st, a);
-    return check_launch();
+    bool ok = false;
+    by_dtype(c.dtype, [&](auto tag) {
+        ok = launch(k_argmax<decltype(tag)>, (unsigned)(rows * a.geo.ns), WG, st, a, SVIP_BENCH_K_VERIFY_STATS);
+    });
+    ok = ok && launch(k_accept_greedy, (unsigned)c.B, 64, st, a, SVIP_BENCH_K_ACCEPT);
+    return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
 
 svip_status verify_call(const VerifyCall &c)
@@ -276,11 +340,9 @@ svip_status verify_call(const VerifyCall &c)
     if (!(c.temperature > 0.f) || !isfinite(c.temperature)) return SVIP_ERR_PARAM;
 
     VerifyArgs a;
-    a.geo = make_geo(c.V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
-    // the residual pass reads two rows per slice: half as many tiles per slice as the draft step
-    a.geo_s = make_geo(c.V, vec, c.B, true, env_int("SVIP_SAMPLE_SLICES", 0), 2);
-    const size_t need = need_verify(c.B, c.k_max, c.V, vec, kd != 0);
-    if (!c.workspace || (reinterpret_cast<uintptr_t>(c.workspace) & 255u) || c.workspace_bytes < need)
+    a.geo = geo_stats(stat_rows, c.V, vec, g_tune.stats_slices);
+    a.geo_s = geo_resid(c.B, c.V, vec, g_tune.resid_slices);
+    if (!workspace_ok(c.workspace, c.workspace_bytes, need_verify(c.B, c.k_max, kd != 0, a.geo, a.geo_s)))
         return SVIP_ERR_WORKSPACE;
     a.target = c.target;
     a.draft = c.draft;
@@ -288,6 +350,7 @@ svip_status verify_call(const VerifyCall &c)
     a.seq_d = c.seq_stride_d;
     a.row_stride = c.row_stride;
     a.pos = c.pos;
+    a.skip = c.skip;
     a.B = c.B;
     a.k = c.k_max;
     a.kd = kd;
@@ -301,33 +364,21 @@ svip_status verify_call(const VerifyCall &c)
     a.n_accepted = c.n_accepted_out;
     a.next_token = c.next_token_out;
     a.accept_prob = c.accept_prob_out;
-    a.ws = carve(c.workspace, c.B);
+    a.ws = carve(c.workspace, c.workspace_bytes, c.B, a.geo_s.ns);
     hipStream_t st = static_cast<hipStream_t>(c.stream);
-    const dim3 g_stats((unsigned)(stat_rows * a.geo.ns)), g_mass((unsigned)a.geo_s.ns * (unsigned)c.B);
-    const bool timed = g_prof.ev && g_prof.used < g_prof.cap;
-    if (timed) {        // the launch itself carries the two events: they take the kernel's own start and end
-        hipEvent_t e0 = g_prof.ev[2 * g_prof.used], e1 = g_prof.ev[2 * g_prof.used + 1];
-        by_dtype(c.dtype, [&](auto tag) {
-            hipExtLaunchKernelGGL(k_verify_stats<decltype(tag)>, g_stats, dim3(WG), 0, st, e0, e1, 0, a);
-        });
-        ++g_prof.used;
-    } else {
-        by_dtype(c.dtype, [&](auto tag) { hipLaunchKernelGGL(k_verify_stats<decltype(tag)>, g_stats, dim3(WG), 0, st, a); });
-    }
+    a.stat_items = stat_rows * a.geo.ns;
+    unsigned g_stats = (unsigned)a.stat_items;
+    if (g_tune.stats_workgroups > 0 && (unsigned)g_tune.stats_workgroups < g_stats) g_stats = (unsigned)g_tune.stats_workgroups;
+    const unsigned g_resid = (unsigned)a.geo_s.ns * (unsigned)c.B;
+    bool ok = false;
     by_dtype(c.dtype, [&](auto tag) {
         using DT = decltype(tag);
-        // few sequences: every workgroup of the mass pass repeats the acceptance test instead of waiting for a
-        // kernel of its own (about 1 us less per call up to 16 sequences, 2 us more at 64)
-        const int in_mass = env_int("SVIP_ACCEPT_IN_MASS", -1);
-        if (in_mass < 0 ? c.B <= 16 : in_mass != 0) {
-            hipLaunchKernelGGL((k_resid_mass<DT, true>), g_mass, dim3(WG), 0, st, a);
-        } else {
-            hipLaunchKernelGGL(k_accept<DT>, dim3(c.B), dim3(64), 0, st, a);
-            hipLaunchKernelGGL((k_resid_mass<DT, false>), g_mass, dim3(WG), 0, st, a);
-        }
-        hipLaunchKernelGGL(k_resid_finish<DT>, dim3(c.B), dim3(WG), 0, st, a);
+        ok = launch(k_verify_stats<DT>, g_stats, WG, st, a, SVIP_BENCH_K_VERIFY_STATS) &&
+             launch(k_accept<DT>, (unsigned)c.B, 64, st, a, SVIP_BENCH_K_ACCEPT) &&
+             (a.geo_s.tps <= TILE_MASSES ? launch(k_resid<DT, true>, g_resid, WG, st, a, SVIP_BENCH_K_RESID)
+                                         : launch(k_resid<DT, false>, g_resid, WG, st, a, SVIP_BENCH_K_RESID));
     });
-    return check_launch();
+    return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
 
 }  // namespace svip
@@ -358,36 +409,53 @@ size_t svip_workspace_bytes(int B, int k_max, int V)
     // streaming passes (statistics of verify, argmax, diagnostics) have up to B (2 k + 1) rows, of
     // which make_geo cuts at most ceil(8192 / rows) slices each: rows + 8192 slices at most
     const size_t vrows = (size_t)B * (2 * (size_t)k_max + 1);
-    size_t parts = (size_t)B * MAX_SLICES;
-    if (vrows + 8192 > parts) parts = vrows + 8192;
+    // a row has at most `tiles` slices (fp32 rows have the most vectors)
+    const size_t tiles = ((size_t)V + 4 * WG - 1) / (4 * WG);
+    const size_t ns_max = tiles < MAX_SLICES ? tiles : MAX_SLICES;
+    size_t part_bytes = (size_t)B * ns_max * sizeof(DraftSlot);
+    if ((vrows + 8192) * sizeof(Partial) > part_bytes) part_bytes = (vrows + 8192) * sizeof(Partial);
     // diagnostics: two logsumexps per position and three sums per slice of its second pass
     const size_t pos = (size_t)B * (size_t)k_max;
-    return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B) + align256(parts * sizeof(Partial)) +
-           align256(pos * 2 * sizeof(double)) + align256((pos + 8192) * 3 * sizeof(double));
+    return ws_fixed_bytes(B, (int)ns_max) + align256(part_bytes) + align256(pos * 2 * sizeof(double)) +
+           align256((pos + 8192) * 3 * sizeof(double));
 }
 
 size_t svip_workspace_needed(int call, svip_dtype dtype, int B, int k_max, int V)
 {
     if (!dtype_ok(dtype) || B <= 0 || B > MAX_BATCH || k_max < 1 || k_max > SVIP_MAX_K || V <= 0) return 0;
     const int vec = vec_of(dtype);
+    const long long rows_t = (long long)B * (k_max + 1), rows_all = (long long)B * (2 * k_max + 1);
     switch (call) {
-        case SVIP_CALL_DRAFT_STEP: return need_draft(B, V, vec);
-        case SVIP_CALL_VERIFY: return need_verify(B, k_max, V, vec, false);
-        case SVIP_CALL_VERIFY_RECOMPUTE: return need_verify(B, k_max, V, vec, true);
-        case SVIP_CALL_VERIFY_GREEDY: return need_verify_greedy(B, k_max, V, vec);
-        case SVIP_CALL_PAIR_STATS: return need_pair(B, k_max, V, vec, false, nullptr, nullptr);
-        case SVIP_CALL_PAIR_STATS_RECOMPUTE: return need_pair(B, k_max, V, vec, true, nullptr, nullptr);
+        case SVIP_CALL_DRAFT_STEP: return need_draft(B, geo_draft(B, V, vec, 0));
+        case SVIP_CALL_VERIFY: return need_verify(B, k_max, false, geo_stats(rows_t, V, vec, 0), geo_resid(B, V, vec, 0));
+        case SVIP_CALL_VERIFY_RECOMPUTE:
+            return need_verify(B, k_max, true, geo_stats(rows_all, V, vec, 0), geo_resid(B, V, vec, 0));
+        case SVIP_CALL_VERIFY_GREEDY: return need_verify_greedy(B, k_max, geo_stats(rows_t, V, vec, 0));
+        case SVIP_CALL_PAIR_STATS:
+            return need_pair(B, k_max, false, geo_stats(rows_t, V, vec, 0), geo_stats((long long)B * k_max, V, vec, 0),
+                             nullptr, nullptr);
+        case SVIP_CALL_PAIR_STATS_RECOMPUTE:
+            return need_pair(B, k_max, true, geo_stats(rows_all, V, vec, 0), geo_stats((long long)B * k_max, V, vec, 0),
+                             nullptr, nullptr);
         default: return 0;
     }
 }
 
 svip_status svip_workspace_reset(void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!workspace || workspace_bytes < HEADER_BYTES || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    if (!workspace || workspace_bytes < 2 * HEADER_BYTES || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return SVIP_ERR_WORKSPACE;
-    hipLaunchKernelGGL(k_zero, dim3(1), dim3(1), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<unsigned *>(workspace));
-    return check_launch();
+    // the flag word, and the ticket counters at the end of the workspace (for any batch size up to MAX_BATCH
+    // that this workspace may later be used with): a fill kernel, so that the call can be captured in a graph
+    const size_t end = workspace_bytes & ~(size_t)255;
+    size_t tail = ws_ticket_bytes(MAX_BATCH);
+    if (tail > end - HEADER_BYTES) tail = end - HEADER_BYTES;
+    ZeroArgs z;
+    z.flags = static_cast<unsigned *>(workspace);
+    z.tail = reinterpret_cast<uint4 *>(static_cast<char *>(workspace) + end - tail);
+    z.n16 = tail / 16;
+    const unsigned grid = (unsigned)((z.n16 + 255) / 256 < 1024 ? (z.n16 + 255) / 256 : 1024);
+    return launch(k_zero, grid ? grid : 1u, 256, static_cast<hipStream_t>(hip_stream), z) ? SVIP_OK : SVIP_ERR_HIP;
 }
 
 svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsigned *flags_host)
@@ -431,7 +499,7 @@ svip_status svip_verify_greedy(const void *target_logits, svip_dtype dtype, int 
                                const int *draft_len, int *n_accepted_out, int *next_token_out,
                                void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    const VerifyCall c{true, target_logits, nullptr, dtype, B, k_max, V, seq_stride_t, 0, row_stride, nullptr, 1.f,
+    const VerifyCall c{true, target_logits, nullptr, dtype, B, k_max, V, seq_stride_t, 0, row_stride, nullptr, nullptr, 1.f,
                        draft_tokens, draft_len, nullptr, nullptr, nullptr, n_accepted_out, next_token_out,
                        nullptr, workspace, workspace_bytes, hip_stream};
     return verify_call(c);
@@ -446,7 +514,7 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
                         void *hip_stream)
 {
     const VerifyCall c{false, target_logits, draft_logits, dtype, B, k_max, V, seq_stride_t, seq_stride_d,
-                       row_stride, nullptr, temperature, draft_tokens, draft_len, draft_lse, u_accept,
+                       row_stride, nullptr, nullptr, temperature, draft_tokens, draft_len, draft_lse, u_accept,
                        u_resample, n_accepted_out, next_token_out, accept_prob_out, workspace,
                        workspace_bytes, hip_stream};
     return verify_call(c);
@@ -482,11 +550,13 @@ svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype
     const int shift = 62 - lg < 44 ? 62 - lg : 44;
     a.fix_scale = ldexpf(1.f, shift);
     a.kept = kept_out;
-    a.no_shortcut = env_int("SVIP_WARP_NO_SHORTCUT", 0);
+    a.no_shortcut = g_tune.warp_no_shortcut;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid((unsigned)((long long)B * k_max));
-    by_dtype(dtype, [&](auto tag) { hipLaunchKernelGGL(k_warp<decltype(tag)>, grid, dim3(WARP_WG), 0, st, a); });
-    return check_launch();
+    bool ok = false;
+    by_dtype(dtype, [&](auto tag) {
+        ok = launch(k_warp<decltype(tag)>, (unsigned)((long long)B * k_max), WARP_WG, st, a);
+    });
+    return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
 
 svip_status svip_pair_stats(const void *target_logits, const void *draft_logits, svip_dtype dtype, int B,
@@ -510,19 +580,19 @@ svip_status svip_pair_stats(const void *target_logits, const void *draft_logits,
     if (!(temperature > 0.f) || !isfinite(temperature) || !(c >= 0.f) || !isfinite(c)) return SVIP_ERR_PARAM;
 
     PairArgs a;
-    a.v.geo = make_geo(V, vec, stat_rows, false, env_int("SVIP_VERIFY_SLICES", 0));
+    a.v.geo = geo_stats(stat_rows, V, vec, g_tune.stats_slices);
     a.v.geo_s = a.v.geo;
-    a.geo2 = make_geo(V, vec, pos, false, env_int("SVIP_PAIR_SLICES", 0));
+    a.geo2 = geo_stats(pos, V, vec, g_tune.pair_slices);
     size_t part_bytes, L_bytes;
-    const size_t need = need_pair(B, k_max, V, vec, kd != 0, &part_bytes, &L_bytes);
-    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
-        return SVIP_ERR_WORKSPACE;
+    const size_t need = need_pair(B, k_max, kd != 0, a.v.geo, a.geo2, &part_bytes, &L_bytes);
+    if (!workspace_ok(workspace, workspace_bytes, need)) return SVIP_ERR_WORKSPACE;
     a.v.target = target_logits;
     a.v.draft = draft_logits;
     a.v.seq_t = seq_stride_t;
     a.v.seq_d = seq_stride_d;
     a.v.row_stride = row_stride;
     a.v.pos = nullptr;
+    a.v.skip = nullptr;
     a.v.B = B;
     a.v.k = k_max;
     a.v.kd = kd;
@@ -536,59 +606,97 @@ svip_status svip_pair_stats(const void *target_logits, const void *draft_logits,
     a.v.n_accepted = nullptr;
     a.v.next_token = nullptr;
     a.v.accept_prob = nullptr;
-    a.v.ws = carve(workspace, B);
+    a.v.ws = carve(workspace, workspace_bytes, B, 0);
     char *after = reinterpret_cast<char *>(a.v.ws.part) + part_bytes;
     a.L = reinterpret_cast<double *>(after);
     a.sums = reinterpret_cast<double *>(after + L_bytes);
     a.c = c;
     a.out = stats_out;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const dim3 g_stats((unsigned)(stat_rows * a.v.geo.ns)), g_pos((unsigned)((pos + 63) / 64)),
-        g_sums((unsigned)(pos * a.geo2.ns));
-    by_dtype(dtype, [&](auto tag) { hipLaunchKernelGGL(k_verify_stats<decltype(tag)>, g_stats, dim3(WG), 0, st, a.v); });
-    hipLaunchKernelGGL(k_pair_L, g_pos, dim3(64), 0, st, a);
-    by_dtype(dtype, [&](auto tag) { hipLaunchKernelGGL(k_pair_sums<decltype(tag)>, g_sums, dim3(WG), 0, st, a); });
-    hipLaunchKernelGGL(k_pair_finish, g_pos, dim3(64), 0, st, a);
-    return check_launch();
+    a.v.stat_items = stat_rows * a.v.geo.ns;
+    const unsigned g_stats = (unsigned)a.v.stat_items, g_pos = (unsigned)((pos + 63) / 64),
+                   g_sums = (unsigned)(pos * a.geo2.ns);
+    bool ok = false;
+    by_dtype(dtype, [&](auto tag) { ok = launch(k_verify_stats<decltype(tag)>, g_stats, WG, st, a.v); });
+    ok = ok && launch(k_pair_L, g_pos, 64, st, a);
+    if (ok) by_dtype(dtype, [&](auto tag) { ok = launch(k_pair_sums<decltype(tag)>, g_sums, WG, st, a); });
+    ok = ok && launch(k_pair_finish, g_pos, 64, st, a);
+    return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
 
-svip_status svip_profile_begin(int max_samples)
+// ---- benchmark and experiment hooks (include/svip_bench.h) -------------------------------------------
+
+svip_status svip_bench_time_kernels(int kernel_class, void *const *start_events, void *const *stop_events, int n_pairs)
 {
-    if (max_samples < 1 || g_prof.ev) return SVIP_ERR_PARAM;
-    g_prof.ev = static_cast<hipEvent_t *>(malloc(sizeof(hipEvent_t) * 2 * (size_t)max_samples));
-    if (!g_prof.ev) return SVIP_ERR_HIP;
-    for (int i = 0; i < 2 * max_samples; ++i) {
-        if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
-            for (int j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
-            free(g_prof.ev);
-            g_prof = Profile();
-            return SVIP_ERR_HIP;
-        }
-    }
-    g_prof.cap = max_samples;
-    g_prof.used = 0;
+    if (kernel_class < 0 || kernel_class >= SVIP_BENCH_KERNEL_CLASSES || n_pairs < 0) return SVIP_ERR_PARAM;
+    if (n_pairs > 0 && (!start_events || !stop_events)) return SVIP_ERR_NULL;
+    KernelTimer &t = g_timer[kernel_class];
+    t.start = n_pairs ? start_events : nullptr;
+    t.stop = n_pairs ? stop_events : nullptr;
+    t.n = n_pairs;
+    t.used = 0;
     return SVIP_OK;
 }
 
-svip_status svip_profile_end(double *total_ms_host, int *samples_host)
+int svip_bench_events_used(int kernel_class)
 {
-    if (!total_ms_host || !samples_host) return SVIP_ERR_NULL;
-    if (!g_prof.ev) return SVIP_ERR_PARAM;
-    double total = 0.0;
-    svip_status rc = SVIP_OK;
-    for (int i = 0; i < g_prof.used; ++i) {
-        float ms = 0.f;
-        if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess ||
-            hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess)
-            rc = SVIP_ERR_HIP;
-        total += ms;
-    }
-    *total_ms_host = total;
-    *samples_host = g_prof.used;
-    for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
-    free(g_prof.ev);
-    g_prof = Profile();
-    return rc;
+    return kernel_class >= 0 && kernel_class < SVIP_BENCH_KERNEL_CLASSES ? g_timer[kernel_class].used : -1;
+}
+
+svip_status svip_bench_empty_kernel(void *hip_stream)
+{
+    return launch(k_empty, 1u, 64u, static_cast<hipStream_t>(hip_stream), 0) ? SVIP_OK : SVIP_ERR_HIP;
+}
+
+size_t svip_bench_stream_sink_words(size_t bytes, int vectors_per_thread)
+{
+    if (vectors_per_thread != 4 && vectors_per_thread != 8 && vectors_per_thread != 16) return 0;
+    const size_t nvec = bytes / 16, per_wg = (size_t)WG * vectors_per_thread;
+    return ((nvec + per_wg - 1) / per_wg) * NWAVE;
+}
+
+svip_status svip_bench_stream_read(const void *buf, size_t bytes, int vectors_per_thread, unsigned *sink,
+                                   void *hip_stream)
+{
+    if (!buf || !sink) return SVIP_ERR_NULL;
+    if (!aligned16(buf)) return SVIP_ERR_ALIGN;
+    const size_t words = svip_bench_stream_sink_words(bytes, vectors_per_thread);
+    if (words == 0 || words / NWAVE > 0x7FFFFFFFull) return SVIP_ERR_SHAPE;
+    StreamArgs a;
+    a.buf = static_cast<const u32x4 *>(buf);
+    a.nvec = bytes / 16;
+    a.sink = sink;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const unsigned grid = (unsigned)(words / NWAVE);
+    bool ok;
+    if (vectors_per_thread == 4) ok = launch(k_stream_read<4>, grid, WG, st, a);
+    else if (vectors_per_thread == 8) ok = launch(k_stream_read<8>, grid, WG, st, a);
+    else ok = launch(k_stream_read<16>, grid, WG, st, a);
+    return ok ? SVIP_OK : SVIP_ERR_HIP;
+}
+
+#ifdef SVIP_STAGE_CLOCK
+// Only in builds with -DSVIP_STAGE_CLOCK (not declared in any header): copies the stage notes of the
+// first `groups` workgroups of the last instrumented launch to the host; synchronises the device.
+svip_status svip_bench_stage_clock(unsigned long long *out_host, int groups)
+{
+    if (!out_host || groups < 1 || groups > STAGE_GROUPS) return SVIP_ERR_PARAM;
+    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(g_stage_clock), sizeof(unsigned long long) * STAGE_SLOTS * groups) ==
+                   hipSuccess
+               ? SVIP_OK
+               : SVIP_ERR_HIP;
+}
+#endif
+
+svip_status svip_bench_set_tuning(const svip_bench_tuning *tuning)
+{
+    const svip_bench_tuning zero = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const svip_bench_tuning t = tuning ? *tuning : zero;
+    if (t.draft_slices < 0 || t.stats_slices < 0 || t.resid_slices < 0 || t.pair_slices < 0 || t.min_workgroups < 0 ||
+        t.stats_workgroups < 0)
+        return SVIP_ERR_PARAM;
+    g_tune = t;
+    return SVIP_OK;
 }
 
 }  // extern "C"

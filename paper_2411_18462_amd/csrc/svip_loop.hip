@@ -24,6 +24,7 @@ struct RoundBuffers {          // carved from the loop workspace after the kerne
     int *tokens;               // [B, gamma_max]
     double *lse;               // [B, gamma_max]
     unsigned char *stop;       // [B]
+    unsigned char *done;       // [B] 1: the sequence has finished, verification skips it
     int *draft_len;            // [B]
     int *n_accepted;           // [B]
     int *next_token;           // [B]
@@ -46,7 +47,7 @@ static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 static size_t round_buffer_bytes(int B, int k)
 {
     const size_t n = (size_t)B, nk = n * (size_t)k;
-    return up256(nk * 4) + up256(nk * 8) + up256(n) + 6 * up256(n * 4) + 256;
+    return up256(nk * 4) + up256(nk * 8) + 2 * up256(n) + 6 * up256(n * 4) + 256;
 }
 
 static RoundBuffers carve_round(char *p, int B, int k)
@@ -56,6 +57,7 @@ static RoundBuffers carve_round(char *p, int B, int k)
     r.tokens = reinterpret_cast<int *>(p); p += up256(nk * 4);
     r.lse = reinterpret_cast<double *>(p); p += up256(nk * 8);
     r.stop = reinterpret_cast<unsigned char *>(p); p += up256(n);
+    r.done = reinterpret_cast<unsigned char *>(p); p += up256(n);
     r.draft_len = reinterpret_cast<int *>(p); p += up256(n * 4);
     r.n_accepted = reinterpret_cast<int *>(p); p += up256(n * 4);
     r.next_token = reinterpret_cast<int *>(p); p += up256(n * 4);
@@ -117,6 +119,7 @@ __global__ __launch_bounds__(LOOP_WG) void k_round_begin(LoopArgs a)
         a.rb.pos[b] = done ? 0 : st[0];
         a.rb.cap[b] = done ? 1 : st[1];
         a.rb.stop[b] = done ? 1 : 0;
+        a.rb.done[b] = done ? 1 : 0;
         a.rb.draft_len[b] = 0;
     }
 }
@@ -183,7 +186,7 @@ static svip_status check_config(const svip_loop_config *c)
     if (!c->target_trace || !c->draft_trace || !c->state || !c->out_tokens) return SVIP_ERR_NULL;
     if (!c->greedy && (!c->u_sample || !c->u_accept || !c->u_resample)) return SVIP_ERR_NULL;
     if (c->B <= 0 || c->V <= 0 || c->gamma_max < 1 || c->gamma_max > SVIP_MAX_K || c->gamma0 < 1 ||
-        c->gamma0 > c->gamma_max || c->L < 2 || c->n0 < 0 || c->n0 >= c->L || c->max_new < 0 ||
+        c->gamma0 > c->gamma_max || c->L < c->gamma_max + 1 || c->n0 < 0 || c->n0 >= c->L || c->max_new < 0 ||
         c->row_stride < c->V || c->seq_stride < (long long)c->L * c->row_stride - (c->row_stride - c->V) ||
         c->out_stride < (long long)c->max_new + c->gamma_max || c->rounds < 1)
         return SVIP_ERR_SHAPE;
@@ -214,11 +217,11 @@ svip_status svip_loop_init(const svip_loop_config *c)
     hipStream_t st = static_cast<hipStream_t>(c->hip_stream);
     const size_t base = up256(svip_workspace_bytes(c->B, c->gamma_max, c->V));
     const RoundBuffers rb = carve_round(static_cast<char *>(c->workspace) + base, c->B, c->gamma_max);
-    const svip_status r = svip_workspace_reset(c->workspace, c->workspace_bytes, c->hip_stream);
+    const svip_status r = svip_workspace_reset(c->workspace, base, c->hip_stream);
     if (r != SVIP_OK) return r;
     hipLaunchKernelGGL(k_loop_init, dim3(1), dim3(LOOP_WG), 0, st, c->state, c->B, c->n0, c->gamma0, c->L,
                        c->max_new, rb.counter);
-    return hipGetLastError() == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
+    return hipPeekAtLastError() == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
 }
 
 svip_status svip_loop_run(const svip_loop_config *c, int first_round, int max_rounds, int *rounds_run_host,
@@ -278,7 +281,7 @@ svip_status svip_loop_run(const svip_loop_config *c, int first_round, int max_ro
             d.draft_len_out = rb.draft_len;
             d.io_stride = k;
             d.workspace = c->workspace;
-            d.workspace_bytes = c->workspace_bytes;
+            d.workspace_bytes = base;             // the kernels' own part of the loop workspace
             d.stream = c->hip_stream;
             r = draft_step_call(d);
             if (r != SVIP_OK) return r;
@@ -312,14 +315,15 @@ svip_status svip_loop_run(const svip_loop_config *c, int first_round, int max_ro
         v.n_accepted_out = rb.n_accepted;
         v.next_token_out = rb.next_token;
         v.accept_prob_out = nullptr;
+        v.skip = rb.done;
         v.workspace = c->workspace;
-        v.workspace_bytes = c->workspace_bytes;
+        v.workspace_bytes = base;
         v.stream = c->hip_stream;
         r = verify_call(v);
         if (r != SVIP_OK) return r;
 
         hipLaunchKernelGGL(k_round_end, dim3(1), dim3(LOOP_WG), 0, st, a);
-        if (hipGetLastError() != hipSuccess) return SVIP_ERR_HIP;
+        if (hipPeekAtLastError() != hipSuccess) return SVIP_ERR_HIP;
         r = read_counter(rb.counter, &running, st);
         if (r != SVIP_OK) return r;
         ++done_rounds;

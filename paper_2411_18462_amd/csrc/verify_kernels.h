@@ -1,5 +1,6 @@
 // Kernels of svip_verify (Algorithm 2 Verify, Algorithm 4 Correct, the bonus sample of Algorithm 1).
 #pragma once
+#include "exchange.h"
 #include "kernel_args.h"
 #include "sample_weights.h"
 
@@ -15,44 +16,55 @@ __device__ __forceinline__ size_t stat_row(const VerifyArgs &a, int b, int jj)
 }
 
 // grid (sequences * rows per sequence * slices).  Draft rows are needed for j < draft_len[b],
-// target rows for j <= draft_len[b]; workgroups of other rows exit at once.
+// target rows for j <= draft_len[b]; workgroups of other rows exit at once.  (Handing the acceptance
+// test to the workgroup that finishes a sequence last was measured and dropped here: the wait for the
+// acknowledged stores and the ticket adds about 1 us to every workgroup of a kernel whose workgroups
+// live about 5 us, and the pass went from 47 us to 63 us; the separate one-wave kernel costs 5 us.)
 template <typename DT>
-__global__ __launch_bounds__(WG) void k_verify_stats(VerifyArgs a)
+__global__ __launch_bounds__(WG, 8) void k_verify_stats(VerifyArgs a)
 {
     __shared__ CombineLds lds;
-    const int y = blockIdx.x / a.geo.ns, s = blockIdx.x - y * a.geo.ns;
     const int rps = a.kd + a.k + 1;
-    const int b = y / rps, jj = y - b * rps;
-    const int g = clamp_len(a.draft_len[b], a.k);
-    const DT *row;
-    if (jj < a.kd) {
-        if (jj >= g) return;
-        row = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, jj);
-    } else {
-        const int j = jj - a.kd;
-        if (j >= g + a.bonus) return;
-        row = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, j);
+    // one item = one slice of one statistics row; a workgroup takes items blockIdx, blockIdx + grid, ...
+    // (the grid covers all items unless the launch asks for fewer, longer-lived workgroups)
+    for (long long item = blockIdx.x; item < a.stat_items; item += gridDim.x) {
+        const int y = (int)(item / a.geo.ns), s = (int)(item - (long long)y * a.geo.ns);
+        const int b = y / rps, jj = y - b * rps;
+        if (a.skip && a.skip[b]) continue;
+        const int g = clamp_len(a.draft_len[b], a.k);
+        const DT *row;
+        if (jj < a.kd) {
+            if (jj >= g) continue;
+            row = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, jj);
+        } else {
+            const int j = jj - a.kd;
+            if (j >= g + a.bonus) continue;
+            row = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, j);
+        }
+        const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+        // the LDS block can be reused at once: every wave has read the maxima before the second barrier of
+        // slice_lse, and thread 0 has read the sums before its wave reaches the next item's first barrier
+        const Partial p = slice_lse<DT>(row, a.geo.V, tb, te, a.sc, lds);
+        if (threadIdx.x == 0) a.ws.part[stat_row(a, b, jj) * a.geo.ns + s] = p;
     }
-    const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    const Partial p = slice_lse<DT>(row, a.geo.V, tb, te, a.sc, lds);
-    if (threadIdx.x == 0) a.ws.part[stat_row(a, b, jj) * a.geo.ns + s] = p;
 }
 
 // ---- verify: acceptance test and first rejection -------------------------------------------
 
 // logsumexp * log2(e) of statistics row y from its slices' (ref, S) pairs (slice_lse): the sums are
 // brought to the largest reference with single-precision exp2 of the (small, exactly formed)
-// reference differences and added in fp64.  Slices are fetched eight at a time so that the loads
+// reference differences and added in fp64.  Slices are fetched four at a time so that the loads
 // of a chunk are in flight together.
 __device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns)
 {
+    constexpr int CH = 4;       // slices fetched together (more would cost the streaming kernel registers)
     float r = neg_inf();
     double S = 0.0;
-    for (int s0 = 0; s0 < ns; s0 += 8) {
-        float pm[8];
-        double pS[8];
+    for (int s0 = 0; s0 < ns; s0 += CH) {
+        float pm[CH];
+        double pS[CH];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < CH; ++u) {
             const bool in = s0 + u < ns;
             const Partial *p = part + y * ns + (in ? s0 + u : 0);
             pm[u] = p->m;
@@ -64,14 +76,14 @@ __device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns)
         }
         float rc = pm[0];
 #pragma unroll
-        for (int u = 1; u < 8; ++u) rc = vmax(rc, pm[u]);
+        for (int u = 1; u < CH; ++u) rc = vmax(rc, pm[u]);
         if (rc == neg_inf()) continue;
         if (rc > r) {
             if (r != neg_inf()) S *= (double)exp2_raw((float)((double)r - (double)rc));
             r = rc;
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < CH; ++u)
             if (pm[u] != neg_inf()) S += pS[u] * (double)exp2_raw((float)((double)pm[u] - (double)r));
     }
     return (double)r + log2(S);
@@ -154,100 +166,143 @@ __device__ __forceinline__ SeqRec accept_sequence(const VerifyArgs &a, int b, in
 template <typename DT>
 __global__ __launch_bounds__(64) void k_accept(VerifyArgs a)
 {
+    if (a.skip && a.skip[blockIdx.x]) return;
     accept_sequence<DT>(a, blockIdx.x, threadIdx.x, true);
 }
 
 // ---- verify: residual / bonus sampling ------------------------------------------------------
 
-// grid (sequences * slices): slice masses of the weights to sample from -- [0] residual
-// max(0, p - q) at the rejected position, [1] target p of the row to sample.
-// WITH_ACCEPT: no k_accept ran before; the first wave of every workgroup repeats the sequence's
-// acceptance test (slice 0 publishes its outputs), which trades one kernel boundary for repeated work.
-template <typename DT, bool WITH_ACCEPT>
-__global__ __launch_bounds__(WG) void k_resid_mass(VerifyArgs a)
+// What a slice's workgroup hands to the sequence's last workgroup: residual and target mass of each
+// of its tiles (slices longer than TILE_MASSES tiles fold the rest into the last entry and are
+// searched as a whole).
+struct ResidSlot {
+    double W[TILE_MASSES], P[TILE_MASSES];
+};
+
+struct ResidLds {
+    double sums[NWAVE][2 * TILE_MASSES];
+    FinishLds fin;
+    int last;
+};
+
+// grid (sequences * slices), the whole residual / bonus draw in one launch.  Every workgroup sums
+// the weights of its slice tile by tile -- residual max(0, p - q) at the rejected position, and target p
+// of the row to sample -- and publishes them; the workgroup that draws the sequence's final ticket
+// chooses between residual and target weights (no residual mass: draw from p), picks the slice and
+// the tile that hold u * total and finds the token there by the inverse CDF.  TILES: slices have at
+// most TILE_MASSES tiles, so the search reads one tile; otherwise it walks the chosen slice.
+template <typename DT, bool TILES>
+__global__ __launch_bounds__(WG, 4) void k_resid(VerifyArgs a)
 {
-    __shared__ double lds[2 * NWAVE];
-    __shared__ SeqRec shrec;
-    const int b = blockIdx.x / a.geo_s.ns, s = blockIdx.x - b * a.geo_s.ns, tid = threadIdx.x;
-    SeqRec rec;
-    if constexpr (WITH_ACCEPT) {
-        if (tid < 64) {
-            const SeqRec mine = accept_sequence<DT>(a, b, tid, s == 0);
-            if (tid == 0) shrec = mine;
-        }
-        __syncthreads();
-        rec = shrec;
-    } else {
-        rec = a.ws.rec[b];
-    }
+    constexpr int N = VecOf<DT>::N;
+    __shared__ ResidLds sh;
+    const int ns = a.geo_s.ns;
+    const int b = blockIdx.x / ns, s = blockIdx.x - b * ns, tid = threadIdx.x;
+    if (a.skip && a.skip[b]) return;
+    const SeqRec rec = a.ws.rec[b];
     const DT *prow = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, rec.r);
     const DT *qrow = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, rec.r);
     const ExpRef ep = make_exp_ref(a.sc, rec.Lp), eq = make_exp_ref(a.sc, rec.Lq);
-    const int tb = s * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
-    float Wacc = 0.f, Pacc = 0.f;
-    if (rec.resid) slice_mass<DT, true>(prow, qrow, a.geo_s.V, tb, te, ep, eq, Wacc, Pacc);
-    else slice_mass<DT, false>(prow, qrow, a.geo_s.V, tb, te, ep, eq, Wacc, Pacc);
-    const double Wd = wave_sum((double)Wacc), Pd = wave_sum((double)Pacc);
-    const int wave = tid >> 6, lane = tid & 63;
-    if (lane == 0) {
-        lds[wave] = Wd;
-        lds[NWAVE + wave] = Pd;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        double W = 0.0, P = 0.0;
+    ResidSlot *slots = reinterpret_cast<ResidSlot *>(a.ws.mass) + (size_t)b * ns;
+    {
+        const int tb = s * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
+        float Wt[TILE_MASSES], Pt[TILE_MASSES];
 #pragma unroll
-        for (int w = 0; w < NWAVE; ++w) {
-            W += lds[w];
-            P += lds[NWAVE + w];
+        for (int v = 0; v < TILE_MASSES; ++v) Wt[v] = Pt[v] = 0.f;
+        if (rec.resid) slice_mass<DT, true>(prow, qrow, a.geo_s.V, tb, te, ep, eq, Wt, Pt);
+        else slice_mass<DT, false>(prow, qrow, a.geo_s.V, tb, te, ep, eq, Wt, Pt);
+        const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+        for (int v = 0; v < TILE_MASSES; ++v) {
+            const double Wd = wave_sum((double)Wt[v]), Pd = wave_sum((double)Pt[v]);
+            if (lane == 0) {
+                sh.sums[wave][v] = Wd;
+                sh.sums[wave][TILE_MASSES + v] = Pd;
+            }
         }
-        double *out = a.ws.mass + ((size_t)b * MAX_SLICES + s) * 2;
-        out[0] = W;
-        out[1] = P;
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+            for (int v = 0; v < TILE_MASSES; ++v) {
+                double W = 0.0, P = 0.0;
+#pragma unroll
+                for (int w = 0; w < NWAVE; ++w) {
+                    W += sh.sums[w][v];
+                    P += sh.sums[w][TILE_MASSES + v];
+                }
+                publish_f64(&slots[s].W[v], W);
+                publish_f64(&slots[s].P[v], P);
+            }
+            stores_done();
+            sh.last = take_ticket(ticket(a.ws.tickets, b, TICKET_RESID)) == (unsigned)ns - 1u;
+        }
+        __syncthreads();
     }
-}
+    if (!sh.last) return;
 
-// grid (sequences): choice between residual and target weights, slice selection, inverse CDF.
-template <typename DT>
-__global__ __launch_bounds__(WG) void k_resid_finish(VerifyArgs a)
-{
-    constexpr int N = VecOf<DT>::N;
-    __shared__ FinishLds sh;
-    const int b = blockIdx.x, tid = threadIdx.x;
-    // independent loads first
-    const SeqRec rec = a.ws.rec[b];
-    const float u = a.u_resample[b];
-    double W = 0.0, P = 0.0;
-    if (tid < a.geo_s.ns) {
-        const double *in = a.ws.mass + ((size_t)b * MAX_SLICES + tid) * 2;
-        W = in[0];
-        P = in[1];
-    }
+    // ---- the sequence's last workgroup ----
     if (tid < 64) {
-        const double inclW = wave_inclusive_sum(W), inclP = wave_inclusive_sum(P);
+        const float u = a.u_resample[b];
+        double W[TILE_MASSES], P[TILE_MASSES];
+#pragma unroll
+        for (int v = 0; v < TILE_MASSES; ++v) W[v] = P[v] = 0.0;
+        if (tid < ns) {
+            unsigned long long x[2 * TILE_MASSES];
+#pragma unroll
+            for (int v = 0; v < TILE_MASSES; ++v) {          // all in flight together
+                x[v] = fetch_u64(&slots[tid].W[v]);
+                x[TILE_MASSES + v] = fetch_u64(&slots[tid].P[v]);
+            }
+#pragma unroll
+            for (int v = 0; v < TILE_MASSES; ++v) {
+                W[v] = __longlong_as_double((long long)x[v]);
+                P[v] = __longlong_as_double((long long)x[TILE_MASSES + v]);
+            }
+        }
+        if (tid == 0) reset_tickets(ticket(a.ws.tickets, b, TICKET_RESID));
+        double Ws = 0.0, Ps = 0.0;
+#pragma unroll
+        for (int v = 0; v < TILE_MASSES; ++v) {
+            Ws += W[v];
+            Ps += P[v];
+        }
+        const double inclW = wave_inclusive_sum(Ws), inclP = wave_inclusive_sum(Ps);
         const double totW = read_lane(inclW, 63), totP = read_lane(inclP, 63);
         const bool resid = rec.resid && totW > 0.0;   // no residual mass: draw from the target row
-        const double M = resid ? W : P, incl = resid ? inclW : inclP, tot = resid ? totW : totP;
+        const double M = resid ? Ws : Ps, incl = resid ? inclW : inclP, tot = resid ? totW : totP;
         double local;
-        const int s = pick_slice(M, (double)u * tot, incl, &local);
+        const int sl = pick_slice(M, (double)u * tot, incl, &local);
+        int tile = 0;
+        if (TILES) {
+            double Gs[TILE_MASSES];
+#pragma unroll
+            for (int v = 0; v < TILE_MASSES; ++v) Gs[v] = read_lane(resid ? W[v] : P[v], sl);
+            double in_tile;
+            tile = pick_tile(Gs, local, &in_tile);
+            local = in_tile;
+        }
         if (tid == 0) {
-            sh.target = local;
-            sh.slice = s;
-            sh.use_resid = resid ? 1 : 0;
+            sh.fin.target = local;
+            sh.fin.slice = sl;
+            sh.fin.tile = tile;
+            sh.fin.use_resid = resid ? 1 : 0;
         }
     }
     __syncthreads();
-    const DT *prow = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, rec.r);
-    const DT *qrow = static_cast<const DT *>(a.draft) + row_offset(a, a.seq_d, b, rec.r);
-    const int tb = sh.slice * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
+    int tb = sh.fin.slice * a.geo_s.tps, te = min(tb + a.geo_s.tps, a.geo_s.ntiles);
+    if (TILES) {
+        tb += sh.fin.tile;
+        te = tb + 1;
+    }
+    constexpr int LU = TILES ? 1 : 2;
     float wtok;
     int tok;
-    if (sh.use_resid) {
-        ResidualWeights<DT> wf{prow, qrow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp), make_exp_ref(a.sc, rec.Lq)};
-        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+    if (sh.fin.use_resid) {
+        ResidualWeights<DT> wf{prow, qrow, a.geo_s.V, ep, eq};
+        tok = locate_in_slice<N, LU>(wf, tb, te, sh.fin.target, sh.fin.loc, &wtok);
     } else {
-        SoftmaxWeights<DT> wf{prow, a.geo_s.V, make_exp_ref(a.sc, rec.Lp)};
-        tok = locate_in_slice<N>(wf, tb, te, sh.target, sh.loc, &wtok);
+        SoftmaxWeights<DT> wf{prow, a.geo_s.V, ep};
+        tok = locate_in_slice<N, LU>(wf, tb, te, sh.fin.target, sh.fin.loc, &wtok);
     }
     if (tid == 0) a.next_token[b] = tok;
 }

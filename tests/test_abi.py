@@ -5,19 +5,35 @@ import os
 import re
 
 import paper_2411_18462_amd as svip
-from paper_2411_18462_amd.binding import EXPORTS
+from paper_2411_18462_amd.binding import BENCH_EXPORTS, EXPORTS
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_every_declared_symbol_is_exported():
     lib = svip.load()
-    header = open(os.path.join(ROOT, "include", "svip.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(svip_[a-z_]+)\s*\(", header))
-    assert declared == set(EXPORTS), declared ^ set(EXPORTS)
-    for name in declared:
-        assert hasattr(lib, name), name
+    for name, exports in (("svip.h", EXPORTS), ("svip_bench.h", BENCH_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared = set(re.findall(r"\b(svip_[a-z_]+)\s*\(", header))
+        assert declared == set(exports), declared ^ set(exports)
+        for sym in declared:
+            assert hasattr(lib, sym), sym
+
+
+def test_bench_hooks_reject_bad_arguments_and_never_change_workspace_sizes():
+    lib = svip.load()
+    assert lib.svip_bench_time_kernels(7, None, None, 0) == 6 and lib.svip_bench_time_kernels(0, None, None, 3) == 1
+    assert lib.svip_bench_time_kernels(0, None, None, 0) == 0 and lib.svip_bench_events_used(0) == 0
+    assert lib.svip_bench_events_used(9) == -1
+    before = [svip.workspace_needed(c, __import__("torch").bfloat16, 64, 16, 128256) for c in range(6)]
+    svip.bench_set_tuning(draft_slices=64, stats_slices=64, resid_slices=64, pair_slices=64, min_workgroups=1)
+    try:
+        assert before == [svip.workspace_needed(c, __import__("torch").bfloat16, 64, 16, 128256) for c in range(6)]
+    finally:
+        svip.bench_set_tuning()
+    t = svip.binding.BenchTuning(draft_slices=-1)
+    assert lib.svip_bench_set_tuning(ctypes.byref(t)) == 6
 
 
 def test_status_strings():
@@ -64,7 +80,7 @@ def test_host_checks_reject_before_any_gpu_call():
     assert draft(logits=p + 2) == 4 and draft(row_stride=V + 4) == 4 and draft(dtype=0, row_stride=V + 2) == 4
     assert draft(T=0.0) == 6 and draft(T=-1.0) == 6 and draft(T=float("inf")) == 6 and draft(h=-0.1) == 6
     assert draft(h=float("nan")) == 6 and draft(T=float("nan")) == 6
-    assert draft(ws=None) == 5 and draft(ws=p + 16) == 5 and draft(wsb=1024) == 5
+    assert draft(ws=None) == 5 and draft(ws=p + 16) == 5 and draft(wsb=512) == 5
 
     def verify(**kw):
         a = dict(t=p, d=p, dtype=1, B=2, k=4, V=V, st_t=5 * V, st_d=4 * V, rs=V, T=1.0, tok=p, dl=p, lse=None,
@@ -87,9 +103,7 @@ def test_host_checks_reject_before_any_gpu_call():
     out = ctypes.c_uint(0)
     assert lib.svip_workspace_flags(None, None, ctypes.byref(out)) == 5
     assert lib.svip_workspace_flags(p, None, None) == 1
-    ms, n = ctypes.c_double(0), ctypes.c_int(0)
-    assert lib.svip_profile_end(ctypes.byref(ms), ctypes.byref(n)) == 6      # not begun
-    assert lib.svip_profile_begin(0) == 6
+    assert lib.svip_workspace_reset(p, 256, None) == 5           # no room for a counter behind the flag word
 
 
 def test_host_checks_of_the_greedy_diagnostic_and_loop_calls():

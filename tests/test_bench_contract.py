@@ -24,14 +24,33 @@ def test_bench_prints_one_json_line_with_the_required_objects():
     assert len(lines) == 1
     d = json.loads(lines[0])
     for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
-                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+                "vs_baseline", "dtype", "data", "config", "roofline", "roofline_calls", "kernels", "stream_read_peak",
+                "cpu_baseline"):
         assert key in d, key
     assert d["n_gpus"] == 1 and d["steps"] == 4 and d["warmup"] == 2 and d["unit"] == "rows/s"
     assert d["vs_baseline"] is None and d["data"] == "synthetic" and "workload" in d["config"]
     r = d["roofline"]
     assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
-    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9 and 0.3 < r["frac"] < 1.0
-    assert r["bytes_per_launch"] == 64 * 17 * 128256 * 2
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9 and 0.05 < r["frac"] < 1.0
+    # the roofline object describes the kernel that holds the largest share of the step
+    ks = d["kernels"]
+    assert set(ks) == {"k_draft_step", "k_verify_stats", "k_accept", "k_resid"}
+    top = max(ks, key=lambda n: ks[n]["us_per_step"])
+    assert r["kernel"].startswith(top) and r["bytes_per_launch"] == ks[top]["bytes_per_launch"]
+    assert abs(sum(k["share_of_step_kernel_time"] for k in ks.values()) - 1.0) < 1e-9
+    assert ks["k_verify_stats"]["bytes_per_launch"] == 64 * 17 * 128256 * 2
+    assert ks["k_draft_step"]["bytes_per_launch"] == 64 * 128256 * 2 and ks["k_draft_step"]["launches_per_step"] == 16
+    # the calls, priced on algorithmic bytes: nothing beats the peak, the step is the sum of its parts
+    rc = d["roofline_calls"]
+    for name in ("draft_step", "verify", "whole_step"):
+        assert 0 < rc[name]["frac"] < 1.0 and abs(rc[name]["frac"] - rc[name]["GBps"] / 8000.0) < 1e-9
+    assert rc["whole_step"]["bytes"] == 16 * rc["draft_step"]["bytes"] + rc["verify"]["bytes"]
+    assert abs(rc["whole_step"]["us"] - 1e3 * d["ms_per_step"]) < 1e-6
+    sum_kernels = sum(k["us_per_step"] for k in ks.values())
+    assert sum_kernels < 1.05 * rc["whole_step"]["us"]             # kernel time cannot exceed the wall time of the step
+    sp = d["stream_read_peak"]
+    assert 0.5 < sp["frac_of_hbm_peak"] < 1.0
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["unit"] == "rows/s" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
+    assert c["one_thread_rows_per_s"] > 0 and c["os_cpu_count"] >= 1
     assert d["value"] > 100 * c["value"]

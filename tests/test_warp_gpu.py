@@ -136,7 +136,7 @@ def test_crowded_bin_is_refined_by_row_sweeps(svip, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
-def test_small_k_shortcut_equals_the_histogram_path(svip, dtype, monkeypatch):
+def test_small_k_shortcut_equals_the_histogram_path(svip, dtype):
     """For a small top_k the thresholds come from a sampled pivot and a candidate list; the result must be
     bit for bit that of the histogram path (same integer arithmetic), also where the sample misleads."""
     _say(f"warp shortcut {dtype}")
@@ -151,23 +151,23 @@ def test_small_k_shortcut_equals_the_histogram_path(svip, dtype, monkeypatch):
     buf, src = _padded_buf(x)
     for top_k, top_p in ((1, 1.0), (50, 1.0), (50, 0.9), (300, 0.5), (2000, 0.99), (2048, 1.0), (5, 0.999),
                          (0, 0.9), (0, 0.3), (0, 0.999), (0, 0.05)):
-        monkeypatch.delenv("SVIP_WARP_NO_SHORTCUT", raising=False)
+        svip.bench_set_tuning()
         k1 = torch.zeros(8, dtype=torch.int32, device="cuda")
         a = svip.warp_logits(src, temperature=0.9, top_k=top_k, top_p=top_p, out=_padded_buf(torch.zeros_like(x))[1], kept_out=k1)
-        monkeypatch.setenv("SVIP_WARP_NO_SHORTCUT", "1")
+        svip.bench_set_tuning(warp_no_shortcut=1)
         k2 = torch.zeros(8, dtype=torch.int32, device="cuda")
         b = svip.warp_logits(src, temperature=0.9, top_k=top_k, top_p=top_p, out=_padded_buf(torch.zeros_like(x))[1], kept_out=k2)
         torch.cuda.synchronize()
         bits = torch.int32 if dtype == torch.float32 else torch.int16
         assert torch.equal(a.contiguous().view(bits), b.contiguous().view(bits)), (top_k, top_p)
         assert torch.equal(k1, k2)
-        monkeypatch.delenv("SVIP_WARP_NO_SHORTCUT", raising=False)       # in place: the shortcut without the early write
+        svip.bench_set_tuning()       # in place: the shortcut without the early write
         k3 = torch.zeros(8, dtype=torch.int32, device="cuda")
         c = svip.warp_logits(_padded_buf(x)[1], temperature=0.9, top_k=top_k, top_p=top_p, kept_out=k3)
         torch.cuda.synchronize()
         assert torch.equal(a.contiguous().view(bits), c.contiguous().view(bits)), (top_k, top_p, "in place")
         assert torch.equal(k1, k3)
-    monkeypatch.delenv("SVIP_WARP_NO_SHORTCUT", raising=False)
+    svip.bench_set_tuning()
     _check(svip, x, 0.9, 50, 0.9)
     _check(svip, x, 0.9, 300, 1.0)
     _check(svip, x, 0.9, 0, 0.9)
