@@ -100,7 +100,7 @@ class HipEvents:
 class KernelClock:
     """Attaches events to the next launches of the library's kernel classes and reads them back."""
 
-    CLASSES = {"k_draft_step": 0, "k_verify_stats": 1, "k_resid": 2, "k_accept": 3}
+    CLASSES = {"k_draft_step": 0, "k_verify_stats": 1, "k_resid": 2, "k_accept": 3, "k_draft_finish": 4}
 
     def __init__(self, svip, counts):
         self.svip = svip

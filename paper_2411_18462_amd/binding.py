@@ -50,8 +50,8 @@ class LoopConfig(ctypes.Structure):
 class BenchTuning(ctypes.Structure):
     """svip_bench_tuning of include/svip_bench.h, field for field."""
     _fields_ = [("draft_slices", ctypes.c_int), ("stats_slices", ctypes.c_int), ("resid_slices", ctypes.c_int),
-                ("pair_slices", ctypes.c_int), ("min_workgroups", ctypes.c_int),
-                ("even_tiles_per_slice", ctypes.c_int), ("warp_no_shortcut", ctypes.c_int), ("draft_no_tile_masses", ctypes.c_int), ("stats_workgroups", ctypes.c_int)]
+                ("pair_slices", ctypes.c_int),
+                ("even_tiles_per_slice", ctypes.c_int), ("warp_no_shortcut", ctypes.c_int), ("draft_no_tile_masses", ctypes.c_int), ("draft_launches", ctypes.c_int), ("stats_workgroups", ctypes.c_int)]
 
 
 def load():

@@ -90,17 +90,26 @@ __device__ __forceinline__ void write_row_outputs(const DraftArgs &a, int b, lon
 // slice that holds u * S, re-read from cache; or, with ARG (greedy drafting), as the first maximum
 // the statistics already carry.  A stopped row's workgroups leave at once; its slice 0 writes the
 // token -1 and keeps the flag.
-template <typename DT, bool ARG, bool TILES>
+// PHASE 0 is that single launch.  PHASES 1 and 2 are the same work as two launches ordered by the stream:
+// 1 = the slices' statistics only, grid (rows * slices), stored plainly; 2 = the rows' last step only,
+// grid (rows).  A kernel boundary costs about 2 us; the hand-over inside one launch costs every slice's
+// workgroup about 1 us of waiting for acknowledged stores and its ticket, which a grid of more than one
+// round of workgroups pays again and again, so large batches take the two launches.
+template <typename DT, bool ARG, bool TILES, int PHASE>
 __global__ __launch_bounds__(WG, 5) void k_draft_step(DraftArgs a)
 {
     constexpr int N = VecOf<DT>::N;
     __shared__ DraftLds sh;
     const int ns = a.geo.ns;
-    const int b = blockIdx.x / ns, s = blockIdx.x - b * ns, tid = threadIdx.x;
+    const int b = PHASE == 2 ? blockIdx.x : blockIdx.x / ns, s = PHASE == 2 ? 0 : blockIdx.x - b * ns, tid = threadIdx.x;
     const long long o = (long long)b * a.io_stride;
     STAGE(0);
     STAGE_WHERE();
-    if (a.stop_in && a.stop_in[b]) {
+    // A stopped row leaves at once -- except in the single launch, which is bound by round trips to memory,
+    // not by bandwidth: there the flag is only looked at once the slice has been read, so that its load and
+    // the logits' loads travel together (the logits of a stopped row are read and ignored).
+    const bool stopped = a.stop_in && a.stop_in[b];
+    if (PHASE != 0 && stopped) {
         if (s == 0 && tid == 0) {
             a.token[o] = -1;
             a.stop[b] = 1;
@@ -109,12 +118,29 @@ __global__ __launch_bounds__(WG, 5) void k_draft_step(DraftArgs a)
     }
     const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
     DraftSlot *slots = static_cast<DraftSlot *>(a.part) + (size_t)b * ns;
-    {
+    if (PHASE != 2) {
         const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
         STAGE(1);
         double G[TILE_MASSES];
         const Partial p = slice_stats<DT, ARG, TILES && !ARG>(row, a.geo.V, tb, te, a.sc, sh.comb, G);
         STAGE(2);
+        if (PHASE == 0 && stopped) {
+            if (s == 0 && tid == 0) {
+                a.token[o] = -1;
+                a.stop[b] = 1;
+            }
+            return;
+        }
+        if (PHASE == 1) {
+            if (tid == 0) {
+                slots[s].p = p;
+                if (TILES && !ARG) {
+#pragma unroll
+                    for (int v = 0; v < TILE_MASSES; ++v) slots[s].G[v] = G[v];
+                }
+            }
+            return;
+        }
         if (tid == 0) {
             if (ns == 1) {
                 sh.own.p = p;
@@ -128,10 +154,10 @@ __global__ __launch_bounds__(WG, 5) void k_draft_step(DraftArgs a)
                 sh.last = take_ticket(ticket(a.tickets, b, TICKET_DRAFT)) == (unsigned)ns - 1u;
             }
         }
+        __syncthreads();
+        STAGE(4);
+        if (!sh.last) return;
     }
-    __syncthreads();
-    STAGE(4);
-    if (!sh.last) return;
 
     // ---- the row's last workgroup ----
     if (tid < 64) {
@@ -143,7 +169,15 @@ __global__ __launch_bounds__(WG, 5) void k_draft_step(DraftArgs a)
         double G[TILE_MASSES];
 #pragma unroll
         for (int v = 0; v < TILE_MASSES; ++v) G[v] = 0.0;
-        if (ns == 1) {
+        if (PHASE == 2) {
+            if (tid < ns) {         // written by the launch before: plain loads
+                p = slots[tid].p;
+                if (TILES && !ARG) {
+#pragma unroll
+                    for (int v = 0; v < TILE_MASSES; ++v) G[v] = slots[tid].G[v];
+                }
+            }
+        } else if (ns == 1) {
             if (tid == 0) {
                 p = sh.own.p;
 #pragma unroll
@@ -154,7 +188,7 @@ __global__ __launch_bounds__(WG, 5) void k_draft_step(DraftArgs a)
         }
         float u = 0.f;
         if (!ARG) u = a.u[o];
-        if (tid == 0 && ns > 1) reset_tickets(ticket(a.tickets, b, TICKET_DRAFT));
+        if (PHASE == 0 && tid == 0 && ns > 1) reset_tickets(ticket(a.tickets, b, TICKET_DRAFT));
         // everything relative to the row maximum: this lane's slice by the factor f
         const float mrow = wave_max(p.m);
         double f = 0.0, xd = 0.0;

@@ -102,18 +102,11 @@ static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int for
     g.ntiles = (nvec + WG - 1) / WG;
     long long ns;
     if (want_one_batch) {
-        // aim at 2048 workgroups of at least min_tiles tiles each; where that leaves fewer than about
-        // 900 workgroups (few rows, or short rows) shorter slices win, down to a single tile (one row
-        // of 128K bf16 logits: 6.5 us a step against 7.5 us; 64 rows of 32000: 8.5 against 10.2)
-        const long long want = (2048 + rows - 1) / rows;
-        const long long floor_wg = g_tune.min_workgroups > 0 ? g_tune.min_workgroups : 900;
-        for (;;) {
-            long long cap = g.ntiles / min_tiles;
-            if (cap < 1) cap = 1;
-            ns = want < cap ? want : cap;
-            if (ns * rows >= floor_wg || min_tiles == 1) break;
-            min_tiles /= 2;
-        }
+        // slices of min_tiles tiles (4: one batch of the statistics loop, and few enough tiles for tile masses);
+        // measured at 128K logits from 1 to 256 rows, 16 slices of 4 tiles beat both finer and coarser cuts
+        long long cap = g.ntiles / min_tiles;
+        if (cap < 1) cap = 1;
+        ns = cap;
         const long long need = (g.ntiles + LOCATE_UNROLL - 1) / LOCATE_UNROLL;
         if (ns < need) ns = need;
         // large batches are bound by bandwidth, not by latency: longer slices of an odd number of
@@ -272,12 +265,31 @@ svip_status draft_step_call(const DraftCall &c)
     hipStream_t st = static_cast<hipStream_t>(c.stream);
     const unsigned grid = (unsigned)a.geo.ns * (unsigned)c.B;
     bool ok = false;
-    const bool tiles = a.geo.tps <= TILE_MASSES && !g_tune.draft_no_tile_masses;      // short slices: the search goes straight to one tile
+    // one launch while all workgroups fit on the GPU at once (the hand-over inside the launch then costs less
+    // than a kernel boundary), two launches beyond that
+    const int mode = g_tune.draft_launches ? g_tune.draft_launches : (grid <= 1536u ? 1 : 2);
+    // tile masses shorten the last step and lengthen the statistics: they pay in the single launch only
+    // (two launches at 256 rows: 28 us without, 29.5 us with)
+    const bool tiles = a.geo.tps <= TILE_MASSES && (g_tune.draft_no_tile_masses ? false : mode == 1 || g_tune.draft_launches == 2);
     by_dtype(c.dtype, [&](auto tag) {
         using DT = decltype(tag);
-        if (c.greedy) ok = launch(k_draft_step<DT, true, false>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STEP);
-        else if (tiles) ok = launch(k_draft_step<DT, false, true>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STEP);
-        else ok = launch(k_draft_step<DT, false, false>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STEP);
+        const int cls = SVIP_BENCH_K_DRAFT_STEP;
+        if (mode == 1) {
+            if (c.greedy) ok = launch(k_draft_step<DT, true, false, 0>, grid, WG, st, a, cls);
+            else if (tiles) ok = launch(k_draft_step<DT, false, true, 0>, grid, WG, st, a, cls);
+            else ok = launch(k_draft_step<DT, false, false, 0>, grid, WG, st, a, cls);
+        } else {
+            const unsigned rows = (unsigned)c.B;
+            if (c.greedy)
+                ok = launch(k_draft_step<DT, true, false, 1>, grid, WG, st, a, cls) &&
+                     launch(k_draft_step<DT, true, false, 2>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
+            else if (tiles)
+                ok = launch(k_draft_step<DT, false, true, 1>, grid, WG, st, a, cls) &&
+                     launch(k_draft_step<DT, false, true, 2>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
+            else
+                ok = launch(k_draft_step<DT, false, false, 1>, grid, WG, st, a, cls) &&
+                     launch(k_draft_step<DT, false, false, 2>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
+        }
     });
     return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
@@ -692,8 +704,8 @@ svip_status svip_bench_set_tuning(const svip_bench_tuning *tuning)
 {
     const svip_bench_tuning zero = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     const svip_bench_tuning t = tuning ? *tuning : zero;
-    if (t.draft_slices < 0 || t.stats_slices < 0 || t.resid_slices < 0 || t.pair_slices < 0 || t.min_workgroups < 0 ||
-        t.stats_workgroups < 0)
+    if (t.draft_slices < 0 || t.stats_slices < 0 || t.resid_slices < 0 || t.pair_slices < 0 ||
+        t.stats_workgroups < 0 || t.draft_launches < 0 || t.draft_launches > 2)
         return SVIP_ERR_PARAM;
     g_tune = t;
     return SVIP_OK;
