@@ -144,6 +144,27 @@ svip_status svip_draft_step(
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * svip_draft_step for callers that cannot allocate device memory or hand a workspace through: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as svip_draft_step (bit for bit), without the workspace: the slice records and ticket
+ * counters live in a fixed array of SVIP_STATIC_SCRATCH_BYTES inside the library's device code, one
+ * copy per GPU, held until the process ends.  The call allocates nothing and frees nothing.
+ *   - Sizes whose records do not fit that array (svip_workspace_needed(SVIP_CALL_DRAFT_STEP, ...) >
+ *     SVIP_STATIC_SCRATCH_BYTES; a few thousand rows of a 128K vocabulary) return SVIP_ERR_WORKSPACE.
+ *   - All calls on one GPU share the array: calls that overlap on one GPU (different streams, or
+ *     threads) race and must be serialised by the caller.  Device-data flags are not reported.
+ *   - The first call on a GPU looks the array up and enqueues a fill kernel that clears it; make that
+ *     call before capturing a graph if the capture should hold the draft step alone.
+ */
+#define SVIP_STATIC_SCRATCH_BYTES (1 << 20)
+svip_status svip_draft_step_static(
+    const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+    float temperature, float h, int step_j, int k_max, const float *u_sample,
+    const unsigned char *stop_in, int *token_out, float *entropy_out, float *q_tok_out,
+    double *lse_out, unsigned char *stop_out, int *draft_len_out, long long io_stride,
+    void *hip_stream);
+
+/*
  * Verification of one round for every sequence.
  *
  * For each sequence b with g = draft_len[b] drafted tokens x_0..x_{g-1} (0 <= g <= k_max):

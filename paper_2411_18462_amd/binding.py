@@ -17,7 +17,7 @@ _DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 
 # every symbol include/svip.h declares
 EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_needed", "svip_workspace_reset",
-           "svip_workspace_flags", "svip_draft_step", "svip_verify", "svip_draft_step_greedy",
+           "svip_workspace_flags", "svip_draft_step", "svip_draft_step_static", "svip_verify", "svip_draft_step_greedy",
            "svip_verify_greedy", "svip_pair_stats", "svip_warp_logits", "svip_loop_workspace_bytes", "svip_loop_init", "svip_loop_run")
 # every symbol include/svip_bench.h declares (benchmark and experiment hooks, not the product ABI)
 BENCH_EXPORTS = ("svip_bench_time_kernels", "svip_bench_events_used", "svip_bench_set_tuning", "svip_bench_empty_kernel",
@@ -75,6 +75,8 @@ def load():
     lib.svip_workspace_flags.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint)]
     lib.svip_draft_step.restype = i
     lib.svip_draft_step.argtypes = [vp, i, i, i, ll, f, f, i, i, vp, vp, vp, vp, vp, vp, vp, vp, ll, vp, sz, vp]
+    lib.svip_draft_step_static.restype = i
+    lib.svip_draft_step_static.argtypes = [vp, i, i, i, ll, f, f, i, i, vp, vp, vp, vp, vp, vp, vp, vp, ll, vp]
     lib.svip_verify.restype = i
     lib.svip_verify.argtypes = [vp, vp, i, i, i, i, ll, ll, ll, f, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.svip_draft_step_greedy.restype = i
@@ -167,10 +169,11 @@ def workspace_flags(workspace: torch.Tensor, stream=None) -> int:
     return out.value
 
 
-def draft_step(draft_logits, *, temperature, h, step_j, k_max, token_out, lse_out, stop_out, workspace,
+def draft_step(draft_logits, *, temperature, h, step_j, k_max, token_out, lse_out, stop_out, workspace=None,
                u_sample=None, greedy=False, stop_in=None, entropy_out=None, q_tok_out=None,
                draft_len_out=None, stream=None):
-    """svip_draft_step, or svip_draft_step_greedy when greedy=True (then u_sample is not used).
+    """svip_draft_step, or svip_draft_step_greedy when greedy=True (then u_sample is not used), or, with
+    workspace=None, svip_draft_step_static (the library's own fixed scratch; sampling only).
     draft_logits: [B, V] view (unit stride along V); u_sample, token_out, entropy_out, q_tok_out,
     lse_out: [B] tensors or column views sharing one stride; stop_in / stop_out / draft_len_out:
     contiguous [B]."""
@@ -192,6 +195,13 @@ def draft_step(draft_logits, *, temperature, h, step_j, k_max, token_out, lse_ou
             raise ValueError(f"{n} must be contiguous [{B}]")
     head = (_ptr(draft_logits, None, "draft_logits"), _DTYPES[draft_logits.dtype], B, V, row_stride,
             float(temperature), float(h), int(step_j), int(k_max))
+    if workspace is None:
+        if greedy:
+            raise ValueError("the greedy draft step needs a workspace")
+        _check(load().svip_draft_step_static(
+            *head, pu, _ptr(stop_in, torch.uint8, "stop_in"), pt, pe, pq, pl, _ptr(stop_out, torch.uint8, "stop_out"),
+            _ptr(draft_len_out, torch.int32, "draft_len_out"), ios or 1, _stream(stream)))
+        return
     tail = (_ptr(stop_in, torch.uint8, "stop_in"), pt, pe, pq, pl,
             _ptr(stop_out, torch.uint8, "stop_out"), _ptr(draft_len_out, torch.int32, "draft_len_out"),
             ios or 1, _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream))

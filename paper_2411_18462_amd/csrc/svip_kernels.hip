@@ -85,6 +85,11 @@ __global__ __launch_bounds__(WG) void k_stream_read(StreamArgs a)
     if ((threadIdx.x & 63) == 0) a.sink[(size_t)blockIdx.x * NWAVE + (threadIdx.x >> 6)] = x;
 }
 
+// Scratch of svip_draft_step_static: the workspace of a draft step for callers that cannot allocate one.
+// One copy per GPU the library runs on, held until the process ends.  Host code never uses this name as an
+// address: static_scratch() asks the runtime for the array's device address, once per device.
+static __device__ __align__(256) unsigned char scratch[SVIP_STATIC_SCRATCH_BYTES];
+
 // ---- host side -------------------------------------------------------------------------------
 
 // Launch-shape overrides for experiments (svip_bench_set_tuning; all zero = the library's own choice).
@@ -294,6 +299,28 @@ svip_status draft_step_call(const DraftCall &c)
     return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
 
+// Device address of `scratch` on the current device, or nullptr.  The first call on a device looks the
+// symbol up (hipGetSymbolAddress with that device current) and clears the array with a fill kernel on the
+// given stream (the ticket counters must start at zero; every call leaves them at zero again).
+static void *static_scratch(hipStream_t st)
+{
+    constexpr int MAX_DEVICES = 64;
+    static void *ptr[MAX_DEVICES] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        ZeroArgs z;
+        z.flags = static_cast<unsigned *>(p);
+        z.tail = static_cast<uint4 *>(p);
+        z.n16 = SVIP_STATIC_SCRATCH_BYTES / 16;
+        if (!launch(k_zero, 256u, 256u, st, z)) return nullptr;
+        ptr[dev] = p;
+    }
+    return ptr[dev];
+}
+
 static svip_status verify_greedy_call(const VerifyCall &c)
 {
     if (!c.target || !c.draft_tokens || !c.draft_len || !c.n_accepted_out || !c.next_token_out) return SVIP_ERR_NULL;
@@ -490,6 +517,25 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
     const DraftCall c{false, draft_logits, dtype, B, V, row_stride, nullptr, 0, nullptr, temperature, h, step_j,
                       k_max, u_sample, stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out,
                       draft_len_out, io_stride, workspace, workspace_bytes, hip_stream};
+    return draft_step_call(c);
+}
+
+svip_status svip_draft_step_static(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+                                   float temperature, float h, int step_j, int k_max, const float *u_sample,
+                                   const unsigned char *stop_in, int *token_out, float *entropy_out,
+                                   float *q_tok_out, double *lse_out, unsigned char *stop_out,
+                                   int *draft_len_out, long long io_stride, void *hip_stream)
+{
+    // sizes first: a batch whose slice records do not fit the fixed scratch is refused before anything else
+    if (!dtype_ok(dtype)) return SVIP_ERR_DTYPE;
+    if (B <= 0 || B > MAX_BATCH || V <= 0) return SVIP_ERR_SHAPE;
+    if (need_draft(B, geo_draft(B, V, vec_of(dtype), g_tune.draft_slices)) > (size_t)SVIP_STATIC_SCRATCH_BYTES)
+        return SVIP_ERR_WORKSPACE;
+    void *ws = static_scratch(static_cast<hipStream_t>(hip_stream));
+    if (!ws) return SVIP_ERR_HIP;
+    const DraftCall c{false, draft_logits, dtype, B, V, row_stride, nullptr, 0, nullptr, temperature, h, step_j,
+                      k_max, u_sample, stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out,
+                      draft_len_out, io_stride, ws, (size_t)SVIP_STATIC_SCRATCH_BYTES, hip_stream};
     return draft_step_call(c);
 }
 
