@@ -69,7 +69,9 @@ typedef enum {
     SVIP_ERR_HIP = 7         /* a HIP runtime call failed */
 } svip_status;
 
-/* Storage type of the logits; every value is widened exactly to fp32 on load. */
+/* Storage type of the logits; every value is widened exactly to fp32 on load.  The calls take it as a
+ * plain int (`dtype`), so that a value outside this list is an error the library reports
+ * (SVIP_ERR_DTYPE), not an invalid enumeration value. */
 typedef enum { SVIP_F32 = 0, SVIP_BF16 = 1, SVIP_F16 = 2 } svip_dtype;
 
 /* Bits of the sticky device-data flag word. */
@@ -96,7 +98,7 @@ typedef enum {
     SVIP_CALL_PAIR_STATS = 4,            /* svip_pair_stats with draft_lse given */
     SVIP_CALL_PAIR_STATS_RECOMPUTE = 5   /* svip_pair_stats with draft_lse == NULL */
 } svip_call;
-size_t svip_workspace_needed(int call, svip_dtype dtype, int B, int k_max, int V);
+size_t svip_workspace_needed(int call, int dtype, int B, int k_max, int V);
 
 /* Zero the sticky flag word and the hand-over counters at the end of the workspace (enqueued on
  * the stream as a fill kernel).  Call once after allocating a workspace, with the size that the
@@ -129,7 +131,7 @@ svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsign
  */
 svip_status svip_draft_step(
     const void *draft_logits,        /* device, row b at element offset b * row_stride */
-    svip_dtype dtype, int B, int V, long long row_stride,
+    int dtype, int B, int V, long long row_stride,
     float temperature, float h,
     int step_j, int k_max,           /* 0 <= step_j < k_max <= SVIP_MAX_K */
     const float *u_sample,           /* device, uniforms in [0,1), row b at b * io_stride */
@@ -158,7 +160,7 @@ svip_status svip_draft_step(
  */
 #define SVIP_STATIC_SCRATCH_BYTES (1 << 20)
 svip_status svip_draft_step_static(
-    const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+    const void *draft_logits, int dtype, int B, int V, long long row_stride,
     float temperature, float h, int step_j, int k_max, const float *u_sample,
     const unsigned char *stop_in, int *token_out, float *entropy_out, float *q_tok_out,
     double *lse_out, unsigned char *stop_out, int *draft_len_out, long long io_stride,
@@ -186,7 +188,7 @@ svip_status svip_draft_step_static(
 svip_status svip_verify(
     const void *target_logits,       /* device, row (b, j) at b * seq_stride_t + j * row_stride, j <= k_max */
     const void *draft_logits,        /* device, row (b, j) at b * seq_stride_d + j * row_stride, j <  k_max */
-    svip_dtype dtype, int B, int k_max, int V,
+    int dtype, int B, int k_max, int V,
     long long seq_stride_t, long long seq_stride_d, long long row_stride,
     float temperature,
     const int *draft_tokens,         /* device [B, k_max] */
@@ -209,7 +211,7 @@ svip_status svip_verify(
  * of stopped rows and the output layout are identical.  No uniforms are needed.
  */
 svip_status svip_draft_step_greedy(
-    const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+    const void *draft_logits, int dtype, int B, int V, long long row_stride,
     float temperature, float h, int step_j, int k_max,
     const unsigned char *stop_in, int *token_out, float *entropy_out, float *q_tok_out,
     double *lse_out, unsigned char *stop_out, int *draft_len_out, long long io_stride,
@@ -225,7 +227,7 @@ svip_status svip_draft_step_greedy(
  */
 svip_status svip_verify_greedy(
     const void *target_logits,       /* device, row (b, j) at b * seq_stride_t + j * row_stride, j <= k_max */
-    svip_dtype dtype, int B, int k_max, int V,
+    int dtype, int B, int k_max, int V,
     long long seq_stride_t, long long row_stride,
     const int *draft_tokens,         /* device [B, k_max] */
     const int *draft_len,            /* device [B] */
@@ -256,7 +258,7 @@ svip_status svip_verify_greedy(
 svip_status svip_pair_stats(
     const void *target_logits,       /* device, row (b, j) at b * seq_stride_t + j * row_stride, j < k_max */
     const void *draft_logits,        /* device, row (b, j) at b * seq_stride_d + j * row_stride, j < k_max */
-    svip_dtype dtype, int B, int k_max, int V,
+    int dtype, int B, int k_max, int V,
     long long seq_stride_t, long long seq_stride_d, long long row_stride,
     float temperature,
     const int *draft_len,            /* device [B] */
@@ -289,7 +291,7 @@ svip_status svip_pair_stats(
 typedef struct svip_loop_config {
     const void *target_trace;   /* device [B, L, V]: row (b, n) at b * seq_stride + n * row_stride */
     const void *draft_trace;    /* device, same layout */
-    svip_dtype dtype;
+    int dtype;
     int B, L, V;
     long long seq_stride, row_stride;   /* elements; multiples of 16 bytes */
     float temperature;
@@ -351,7 +353,7 @@ svip_status svip_loop_run(const svip_loop_config *config /* host */, int first_r
  * No workspace.  Enqueues on hip_stream and returns; errors as for the other calls
  * (SVIP_ERR_PARAM: temperature, top_k < 0, top_p <= 0 or NaN).
  */
-svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype dtype, int B, int n_rows,
+svip_status svip_warp_logits(const void *logits_in, void *logits_out, int dtype, int B, int n_rows,
                              int V, long long seq_stride, long long row_stride, float temperature,
                              int top_k, double top_p, int *kept_out, void *hip_stream);
 

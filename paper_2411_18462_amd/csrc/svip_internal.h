@@ -11,7 +11,7 @@ namespace svip {
 struct DraftCall {
     bool greedy;                 // argmax instead of a draw (u_sample unused)
     const void *logits;          // device
-    svip_dtype dtype;
+    int dtype;
     int B, V;
     long long row_stride;        // elements between the rows (or traces) of consecutive sequences
     const int *pos;              // device [B] or nullptr: sequence b reads trace row pos[b] + step_j
@@ -36,7 +36,7 @@ struct DraftCall {
 struct VerifyCall {
     bool greedy;                 // Algorithms 3 and 5: only the target, tokens and lengths are used
     const void *target, *draft;  // device
-    svip_dtype dtype;
+    int dtype;
     int B, k_max, V;
     long long seq_stride_t, seq_stride_d, row_stride;
     const int *pos;              // device [B] or nullptr: row j of sequence b is trace row pos[b] + j

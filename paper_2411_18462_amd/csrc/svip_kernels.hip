@@ -148,12 +148,12 @@ static Scale make_scale(float temperature)
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-static bool dtype_ok(svip_dtype d) { return d == SVIP_F32 || d == SVIP_BF16 || d == SVIP_F16; }
-static int vec_of(svip_dtype d) { return d == SVIP_F32 ? 4 : 8; }       // logits per 16-byte vector
+static bool dtype_ok(int d) { return d == SVIP_F32 || d == SVIP_BF16 || d == SVIP_F16; }
+static int vec_of(int d) { return d == SVIP_F32 ? 4 : 8; }       // logits per 16-byte vector
 
 // Calls f with a value of the storage type that d names (f is a generic lambda).
 template <typename F>
-static void by_dtype(svip_dtype d, F f)
+static void by_dtype(int d, F f)
 {
     if (d == SVIP_BF16) f(bf16{});
     else if (d == SVIP_F16) f(f16{});
@@ -459,7 +459,7 @@ size_t svip_workspace_bytes(int B, int k_max, int V)
            align256((pos + 8192) * 3 * sizeof(double));
 }
 
-size_t svip_workspace_needed(int call, svip_dtype dtype, int B, int k_max, int V)
+size_t svip_workspace_needed(int call, int dtype, int B, int k_max, int V)
 {
     if (!dtype_ok(dtype) || B <= 0 || B > MAX_BATCH || k_max < 1 || k_max > SVIP_MAX_K || V <= 0) return 0;
     const int vec = vec_of(dtype);
@@ -507,7 +507,7 @@ svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsign
     return hipStreamSynchronize(st) == hipSuccess ? SVIP_OK : SVIP_ERR_HIP;
 }
 
-svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+svip_status svip_draft_step(const void *draft_logits, int dtype, int B, int V, long long row_stride,
                             float temperature, float h, int step_j, int k_max, const float *u_sample,
                             const unsigned char *stop_in, int *token_out, float *entropy_out,
                             float *q_tok_out, double *lse_out, unsigned char *stop_out,
@@ -520,7 +520,7 @@ svip_status svip_draft_step(const void *draft_logits, svip_dtype dtype, int B, i
     return draft_step_call(c);
 }
 
-svip_status svip_draft_step_static(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+svip_status svip_draft_step_static(const void *draft_logits, int dtype, int B, int V, long long row_stride,
                                    float temperature, float h, int step_j, int k_max, const float *u_sample,
                                    const unsigned char *stop_in, int *token_out, float *entropy_out,
                                    float *q_tok_out, double *lse_out, unsigned char *stop_out,
@@ -539,7 +539,7 @@ svip_status svip_draft_step_static(const void *draft_logits, svip_dtype dtype, i
     return draft_step_call(c);
 }
 
-svip_status svip_draft_step_greedy(const void *draft_logits, svip_dtype dtype, int B, int V, long long row_stride,
+svip_status svip_draft_step_greedy(const void *draft_logits, int dtype, int B, int V, long long row_stride,
                                    float temperature, float h, int step_j, int k_max,
                                    const unsigned char *stop_in, int *token_out, float *entropy_out,
                                    float *q_tok_out, double *lse_out, unsigned char *stop_out,
@@ -552,7 +552,7 @@ svip_status svip_draft_step_greedy(const void *draft_logits, svip_dtype dtype, i
     return draft_step_call(c);
 }
 
-svip_status svip_verify_greedy(const void *target_logits, svip_dtype dtype, int B, int k_max, int V,
+svip_status svip_verify_greedy(const void *target_logits, int dtype, int B, int k_max, int V,
                                long long seq_stride_t, long long row_stride, const int *draft_tokens,
                                const int *draft_len, int *n_accepted_out, int *next_token_out,
                                void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -563,7 +563,7 @@ svip_status svip_verify_greedy(const void *target_logits, svip_dtype dtype, int 
     return verify_call(c);
 }
 
-svip_status svip_verify(const void *target_logits, const void *draft_logits, svip_dtype dtype, int B,
+svip_status svip_verify(const void *target_logits, const void *draft_logits, int dtype, int B,
                         int k_max, int V, long long seq_stride_t, long long seq_stride_d,
                         long long row_stride, float temperature, const int *draft_tokens,
                         const int *draft_len, const double *draft_lse, const float *u_accept,
@@ -578,7 +578,7 @@ svip_status svip_verify(const void *target_logits, const void *draft_logits, svi
     return verify_call(c);
 }
 
-svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype dtype, int B, int k_max, int V,
+svip_status svip_warp_logits(const void *logits_in, void *logits_out, int dtype, int B, int k_max, int V,
                              long long seq_stride, long long row_stride, float temperature, int top_k,
                              double top_p, int *kept_out, void *hip_stream)
 {
@@ -617,7 +617,7 @@ svip_status svip_warp_logits(const void *logits_in, void *logits_out, svip_dtype
     return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
 
-svip_status svip_pair_stats(const void *target_logits, const void *draft_logits, svip_dtype dtype, int B,
+svip_status svip_pair_stats(const void *target_logits, const void *draft_logits, int dtype, int B,
                             int k_max, int V, long long seq_stride_t, long long seq_stride_d,
                             long long row_stride, float temperature, const int *draft_len,
                             const double *draft_lse, float c, float *stats_out, void *workspace,
