@@ -338,7 +338,13 @@ def host_cores():
     return os.cpu_count() or 1, aff
 
 
-def loop_policies(svip, si, dev, max_new=96, gamma_max=40, draft_cost=0.1):
+# The paper's settings (Section 3): draft-length limit, the Constant baseline's length, the Heuristic baseline's
+# +2 / -1 rule.  tests/golden/paper_hyperparameters.txt holds the same values with their citation.
+PAPER = {"max_draft_length": 40, "constant_draft_length": 5, "heuristic_increase": 2, "heuristic_decrease": 1,
+         "sampling_temperature": 1.0, "entropy_threshold_h": 0.3}
+
+
+def loop_policies(svip, si, dev, max_new=96, gamma_max=PAPER["max_draft_length"], draft_cost=0.1):
     """The decoding loop (Algorithm 1 / Algorithm 6) over Markov low/high-entropy traces shaped like
     BASELINE config 4 (B = 8, V = 151936, bf16; the models agree on low-entropy rows and disagree on
     high-entropy ones) under the three draft-length policies the paper compares,
@@ -354,8 +360,9 @@ def loop_policies(svip, si, dev, max_new=96, gamma_max=40, draft_cost=0.1):
     res = {"workload": f"{w.name} traces: B={w.B} V={w.V} {w.dtype}, L={L}, max_new={max_new}, limit {gamma_max}, T={w.T}",
            "draft_cost": draft_cost}
     for name, (h, g0, gmax, inc, dec) in (("svip_h3", (w.h, gamma_max, gamma_max, 0, 0)),
-                                          ("constant_5", (math.inf, 5, 5, 0, 0)),
-                                          ("heuristic", (math.inf, 5, gamma_max, 2, 1))):
+                                          ("constant_5", (math.inf, PAPER["constant_draft_length"], PAPER["constant_draft_length"], 0, 0)),
+                                          ("heuristic", (math.inf, PAPER["constant_draft_length"], gamma_max,
+                                                         PAPER["heuristic_increase"], PAPER["heuristic_decrease"]))):
         best = None
         for rep in range(2):            # second run is the timed one (first touches every page)
             loop = svip.Loop(zt, zd, temperature=w.T, h=h, gamma0=g0, gamma_max=gmax, gamma_inc=inc, gamma_dec=dec,
@@ -498,11 +505,12 @@ def sweep(svip, dev, cells, counter_pass):
     return out
 
 
-def merge_counters(cells, directory, copy_factor):
-    """Adds HBM bytes per launch from two rocprofv3 --pmc runs of `--sweep --sweep-counter-pass`
+def merge_counters(cells, directory):
+    """Adds HBM bytes per launch from two rocprofv3 --pmc runs of `--sweep --sweep-counter-pass --calibrate-copy`
     (directory/fetch/**/*counter_collection.csv with FETCH_SIZE, directory/write/... with WRITE_SIZE; KiB per
-    dispatch).  Dispatches are matched to cells by order: the library's kernels appear in launch order and
-    every cell launches a known number of each."""
+    dispatch).  Each counter is scaled by what it reads for the plain 256 MiB device copy of --calibrate-copy.
+    Dispatches are matched to cells by order: a counter pass runs two rounds per cell, a round ends with its
+    k_resid launch, and the library's kernels appear in launch order."""
     import csv
     import glob
 
@@ -517,22 +525,44 @@ def merge_counters(cells, directory, copy_factor):
         rows.sort()
         return rows
 
-    fetch, write = load("fetch", "FETCH_SIZE"), load("write", "WRITE_SIZE")
-    for name, rows, factor in (("fetch", fetch, copy_factor["FETCH_SIZE"]), ("write", write, copy_factor["WRITE_SIZE"])):
-        per_kernel = {kn: [v for _, n, v in rows if f"svip::{kn}<" in n or f"svip::{kn}(" in n] for kn in SWEEP_KERNELS}
-        pos = {kn: 0 for kn in SWEEP_KERNELS}
-        for c in cells:
-            k = c["k"]
-            for kn, n in (("k_draft_step", 2 * k), ("k_verify_stats", 2), ("k_accept", 2), ("k_resid", 2)):
-                vals = per_kernel[kn][pos[kn]:pos[kn] + n]
-                pos[kn] += n
-                assert len(vals) == n, f"cell {c['cell']}: {len(vals)} of {n} dispatches of {kn} in the {name} run"
-                c[f"{kn}_{name}_MB"] = sum(vals) / n * 1024 / factor / 1e6
+    def classify(name):
+        if "svip::k_draft_step<" in name:
+            return "k_draft_finish" if name.split("(")[0].rstrip().endswith(", 2>") else "k_draft_step"
+        for kn in ("k_verify_stats", "k_accept", "k_resid"):
+            if f"svip::{kn}<" in name:
+                return kn
+        return None
+
+    factors = {}
+    for sub, counter in (("fetch", "FETCH_SIZE"), ("write", "WRITE_SIZE")):
+        rows = load(sub, counter)
+        first_kernel = min(i for i, n, _ in rows if classify(n))
+        copies = [v for i, n, v in rows if "copyBuffer" in n and i < first_kernel]
+        assert copies, "the counter pass must be run with --calibrate-copy"
+        factors[counter] = max(copies) / 262144.0            # counter units per KiB actually moved (the 256 MiB copies come first)
+        acc = {}
+        rounds_done = 0
+        for _, name, v in rows:
+            kn = classify(name)
+            if kn is None:
+                continue
+            key = (rounds_done // 2, kn)
+            tot, n = acc.get(key, (0.0, 0))
+            acc[key] = (tot + v, n + 1)
+            if kn == "k_resid":
+                rounds_done += 1
+        assert rounds_done == 2 * len(cells), f"{rounds_done} rounds in the {sub} run, {2 * len(cells)} expected"
+        for i, c in enumerate(cells):
+            for kn in ("k_draft_step", "k_draft_finish", "k_verify_stats", "k_accept", "k_resid"):
+                if (i, kn) in acc:
+                    tot, n = acc[(i, kn)]
+                    c[f"{kn}_{sub}_MB"] = tot / n / factors[counter] * 1024 / 1e6
+                    c[f"{kn}_launches_counted"] = n
     for c in cells:
         B, V, k = c["B"], c["V"], c["k"]
         c["k_draft_step_alg_MB"] = B * V * 2 / 1e6
         c["k_verify_stats_alg_MB"] = B * (k + 1) * V * 2 / 1e6
-    return cells
+    return cells, factors
 
 
 def sources_digest():
@@ -568,6 +598,11 @@ def main():
         print("bench.py: this build runs on ONE GPU (the path shards over sequences with no "
               "exchange, so N GPUs would each run this same program on their share of the batch); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    if a.sweep and a.sweep_counters:          # a merge of files, no GPU involved
+        table = json.load(open(os.path.join(a.sweep_counters, "sweep.json")))["sweep"]
+        merged, factors = merge_counters(table, a.sweep_counters)
+        print(json.dumps({"counter_units_per_KiB": factors, "sweep": merged}))
+        return
     import numpy as np
     import torch
     import paper_2411_18462_amd as svip
@@ -578,11 +613,6 @@ def main():
     dev = torch.device("cuda:0")
     if a.sweep:
         cells = [int(x) for x in a.sweep_cells.split(",")] if a.sweep_cells else list(range(len(sweep_cells())))
-        if a.sweep_counters:
-            table = json.load(open(os.path.join(a.sweep_counters, "cells.json")))
-            factor = json.load(open(os.path.join(a.sweep_counters, "copy_factor.json")))
-            print(json.dumps({"sweep": merge_counters(table, a.sweep_counters, factor)}))
-            return
         if a.calibrate_copy:
             src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
             dst = torch.empty_like(src)

@@ -15,6 +15,20 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert p.returncode != 0 and "ONE GPU" in p.stderr and p.stdout.strip() == ""
 
 
+def test_loop_policies_use_the_settings_the_paper_states():
+    """Section 3: limit 40, Constant 5, Heuristic +2 / -1, T = 1, h = 0.3 (fixture with the citation)."""
+    sys.path.insert(0, ROOT)
+    import bench
+    vals = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "paper_hyperparameters.txt")):
+        if line.strip() and not line.startswith("#"):
+            key, *rest = line.split()
+            vals[key] = [float(x) for x in rest]
+    for key, v in bench.PAPER.items():
+        assert vals[key] == [float(v)], key
+    assert vals["entropy_threshold_grid"] == [0.2, 0.3, 0.4, 0.5] and bench.PAPER["entropy_threshold_h"] in vals["entropy_threshold_grid"]
+
+
 @pytest.mark.gpu
 def test_bench_prints_one_json_line_with_the_required_objects():
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "4", "--warmup", "2",

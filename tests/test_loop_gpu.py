@@ -16,7 +16,7 @@ import torch
 
 import oracle
 import svip_inputs as si
-from helpers import MARGIN, f32
+from helpers import MARGIN, cell_is_valid, f32
 
 pytestmark = pytest.mark.gpu
 
@@ -84,6 +84,13 @@ def _check(res, tr, w, policy, max_new, greedy=False, n0=0):
                     st["in_margin_diff"] += 1
                     clean = False
                     assert ((seg >= 0) & (seg < V)).all()
+                    # whatever side a borderline decision fell on, every accepted draft token must still be a
+                    # legitimate draw of its own row for its own uniform (a cell within 2 * MARGIN of u)
+                    if not greedy:
+                        for j in range(int(na)):
+                            q, _ = oracle.softmax_row(zq[pos + j], T)
+                            assert cell_is_valid(q, int(seg[j]), float(us[r, j]), 2 * MARGIN), \
+                                f"seq {b} round {r}: accepted token {seg[j]} at step {j} is no valid draw"
             produced += na + 1
             drafted += g
             accepted += na
