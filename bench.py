@@ -100,7 +100,7 @@ class HipEvents:
 class KernelClock:
     """Attaches events to the next launches of the library's kernel classes and reads them back."""
 
-    CLASSES = {"k_draft_step": 0, "k_verify_stats": 1, "k_resid": 2, "k_accept": 3, "k_draft_finish": 4}
+    CLASSES = {"k_draft_stats": 0, "k_verify_stats": 1, "k_resid": 2, "k_accept": 3, "k_draft_finish": 4}
 
     def __init__(self, svip, counts):
         self.svip = svip
@@ -231,7 +231,8 @@ def kernel_durations(svip, sets, h, steps):
     the host's launch rate does not enter.  {kernel: [us, ...]}."""
     import torch
     k = sets[0].k
-    clock = KernelClock(svip, {"k_draft_step": steps * k, "k_verify_stats": steps, "k_accept": steps, "k_resid": steps})
+    clock = KernelClock(svip, {"k_draft_stats": steps * k, "k_draft_finish": steps * k, "k_verify_stats": steps, "k_accept": steps,
+                               "k_resid": steps})
     for i in range(steps):
         s = sets[i % len(sets)]
         s.draft_round(h)
@@ -391,7 +392,7 @@ def loop_policies(svip, si, dev, max_new=96, gamma_max=PAPER["max_draft_length"]
 SWEEP_B, SWEEP_V, SWEEP_K, SWEEP_T = (1, 8, 64, 256), (32000, 128256, 151936), (4, 16, 64), (0.7, 1.0)
 SWEEP_POOL_BYTES = 1 << 30       # inputs rotate through at least this much, or the cell is labelled cache-warm
 SWEEP_MAX_SETS = 8
-SWEEP_KERNELS = ("k_draft_step", "k_verify_stats", "k_accept", "k_resid")
+SWEEP_KERNELS = ("k_draft_stats", "k_draft_finish", "k_verify_stats", "k_accept", "k_resid")
 
 
 def sweep_cells():
@@ -466,7 +467,7 @@ def sweep(svip, dev, cells, counter_pass):
                 s.draft_round(H_FULL)
                 s.verify()
             torch.cuda.synchronize()
-            cell["launches"] = {"k_draft_step": 2 * k, "k_verify_stats": 2, "k_accept": 2, "k_resid": 2}
+            cell["launches"] = {"k_draft_stats": 2 * k, "k_draft_finish": 2 * k, "k_verify_stats": 2, "k_accept": 2, "k_resid": 2}
             out.append(cell)
             print(json.dumps({"sweep_cell": cell}), file=sys.stderr, flush=True)
             del sets
@@ -492,7 +493,8 @@ def sweep(svip, dev, cells, counter_pass):
             "draft_step_us": 1e6 * t_draft / k, "draft_step_GBps": B * row_bytes / (t_draft / k) / 1e9,
             "verify_us": 1e6 * t_verify, "verify_GBps": verify_bytes / t_verify / 1e9,
             "round_rows_per_s": B * (2 * k + 1) / (t_draft + t_verify),
-            "k_draft_step_us": med["k_draft_step"], "k_draft_step_GBps": B * row_bytes / (med["k_draft_step"] * 1e-6) / 1e9,
+            "k_draft_stats_us": med["k_draft_stats"], "k_draft_stats_GBps": B * row_bytes / (med["k_draft_stats"] * 1e-6) / 1e9,
+            "k_draft_finish_us": med["k_draft_finish"],
             "k_verify_stats_us": med["k_verify_stats"],
             "k_verify_stats_GBps": B * (k + 1) * row_bytes / (med["k_verify_stats"] * 1e-6) / 1e9,
             "k_accept_us": med["k_accept"], "k_resid_us": med["k_resid"], "rejecting": nrej,
@@ -526,9 +528,7 @@ def merge_counters(cells, directory):
         return rows
 
     def classify(name):
-        if "svip::k_draft_step<" in name:
-            return "k_draft_finish" if name.split("(")[0].rstrip().endswith(", 2>") else "k_draft_step"
-        for kn in ("k_verify_stats", "k_accept", "k_resid"):
+        for kn in ("k_draft_stats", "k_draft_finish", "k_verify_stats", "k_accept", "k_resid"):
             if f"svip::{kn}<" in name:
                 return kn
         return None
@@ -553,14 +553,14 @@ def merge_counters(cells, directory):
                 rounds_done += 1
         assert rounds_done == 2 * len(cells), f"{rounds_done} rounds in the {sub} run, {2 * len(cells)} expected"
         for i, c in enumerate(cells):
-            for kn in ("k_draft_step", "k_draft_finish", "k_verify_stats", "k_accept", "k_resid"):
+            for kn in ("k_draft_stats", "k_draft_finish", "k_verify_stats", "k_accept", "k_resid"):
                 if (i, kn) in acc:
                     tot, n = acc[(i, kn)]
                     c[f"{kn}_{sub}_MB"] = tot / n / factors[counter] * 1024 / 1e6
                     c[f"{kn}_launches_counted"] = n
     for c in cells:
         B, V, k = c["B"], c["V"], c["k"]
-        c["k_draft_step_alg_MB"] = B * V * 2 / 1e6
+        c["k_draft_stats_alg_MB"] = B * V * 2 / 1e6
         c["k_verify_stats_alg_MB"] = B * (k + 1) * V * 2 / 1e6
     return cells, factors
 
@@ -673,8 +673,9 @@ def main():
     # the kernels' own durations: the same rounds, eager, events attached to every launch
     k_steps = min(a.steps, 200)
     kd = kernel_durations(svip, sets, H_FULL, k_steps)
-    per_launch_bytes = {"k_draft_step": B * row_bytes, "k_verify_stats": stats_bytes, "k_accept": 0, "k_resid": resid_bytes}
-    launches = {"k_draft_step": k, "k_verify_stats": 1, "k_accept": 1, "k_resid": 1}
+    per_launch_bytes = {"k_draft_stats": B * row_bytes, "k_draft_finish": 0, "k_verify_stats": stats_bytes, "k_accept": 0,
+                        "k_resid": resid_bytes}
+    launches = {"k_draft_stats": k, "k_draft_finish": k, "k_verify_stats": 1, "k_accept": 1, "k_resid": 1}
     kernels = {}
     for name, v in kd.items():
         v = np.array(v)

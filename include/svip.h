@@ -120,8 +120,10 @@ svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsign
  * and writes, at index b * io_stride of each per-row output array,
  *   token_out, entropy_out = H, q_tok_out = q[token], lse_out = logsumexp(logits / temperature),
  * plus stop_out[b] and, if draft_len_out != NULL, draft_len_out[b] = step_j + 1.
- * Rows with stop_in[b] != 0 are not read; they get token_out = -1 and stop_out[b] = 1 and
- * nothing else is written for them.
+ * Rows with stop_in[b] != 0 get token_out = -1 and stop_out[b] = 1 and nothing else is written
+ * for them.  Their logits do not enter any result but may still be read (the flag and the logits
+ * are fetched together: a step is bound by memory round trips, and waiting for the flag first
+ * costs 0.13 us of a 12.9 us step at 64 rows), so draft_logits must be readable for every row.
  *
  * io_stride lets the per-row arrays be columns of [B, k_max] buffers (pass the address of
  * column step_j and io_stride = k_max), which is the layout svip_verify consumes; likewise

@@ -16,11 +16,11 @@ extern "C" {
 
 /* Kernel classes whose launches can carry timing events. */
 enum {
-    SVIP_BENCH_K_DRAFT_STEP = 0,    /* the kernel of svip_draft_step / svip_draft_step_greedy (the first one if it takes two) */
+    SVIP_BENCH_K_DRAFT_STATS = 0,   /* statistics launch of svip_draft_step / svip_draft_step_greedy */
     SVIP_BENCH_K_VERIFY_STATS = 1,  /* statistics pass of svip_verify (argmax pass of svip_verify_greedy) */
     SVIP_BENCH_K_RESID = 2,         /* residual / bonus pass of svip_verify */
     SVIP_BENCH_K_ACCEPT = 3,        /* acceptance tests and first-rejection scan of svip_verify / svip_verify_greedy */
-    SVIP_BENCH_K_DRAFT_FINISH = 4,  /* second launch of a draft step that takes two (large batches) */
+    SVIP_BENCH_K_DRAFT_FINISH = 4,  /* second launch of a draft step: the rows' merge, stop test and token */
     SVIP_BENCH_KERNEL_CLASSES = 5
 };
 
@@ -44,14 +44,12 @@ int svip_bench_events_used(int kernel_class);
  * SVIP_ERR_WORKSPACE.  Results do not depend on the shape beyond the rounding of partial sums.
  */
 typedef struct svip_bench_tuning {
-    int draft_slices;          /* slices per row of the draft step */
+    int draft_slices;          /* records (waves) per row of the draft step */
     int stats_slices;          /* slices per row of the statistics / argmax pass of verification */
     int resid_slices;          /* slices per row of the residual pass */
     int pair_slices;           /* slices per row of the second pass of svip_pair_stats */
     int even_tiles_per_slice;  /* 1: do not round the streaming passes' slices up to an odd number of tiles */
     int warp_no_shortcut;      /* 1: svip_warp_logits always takes the histogram path */
-    int draft_no_tile_masses;  /* 1: the draft step never publishes tile masses; its last workgroup searches a whole slice */
-    int draft_launches;        /* 1: the draft step as one launch, 2: as two (statistics, then the rows' last step) */
     int stats_workgroups;      /* workgroups of the statistics pass of svip_verify: fewer than its items makes each loop over several */
 } svip_bench_tuning;
 svip_status svip_bench_set_tuning(const svip_bench_tuning *tuning /* host, or NULL */);

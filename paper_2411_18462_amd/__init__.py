@@ -14,12 +14,12 @@ from .binding import (SvipError, draft_step, load, new_workspace, verify, verify
                       PAIR_NSTAT, PAIR_FIELDS, Loop, LoopConfig, LOOP_NSTATE, LOOP_STATE_FIELDS, workspace_bytes,
                       workspace_needed, workspace_flags, MAX_K, FLAG_BAD_TOKEN, FLAG_BAD_DRAFT_LEN,
                       bench_time_kernels, bench_events_used, bench_set_tuning, bench_empty_kernel, bench_stream_read,
-                      BENCH_K_DRAFT_STEP,
-                      BENCH_K_VERIFY_STATS, BENCH_K_RESID, BENCH_K_ACCEPT)
+                      BENCH_K_DRAFT_STATS,
+                      BENCH_K_VERIFY_STATS, BENCH_K_RESID, BENCH_K_ACCEPT, BENCH_K_DRAFT_FINISH)
 
 __all__ = ["SvipError", "draft_step", "load", "new_workspace", "verify", "verify_greedy", "pair_stats", "warp_logits",
            "PAIR_NSTAT", "PAIR_FIELDS", "Loop", "LoopConfig", "LOOP_NSTATE", "LOOP_STATE_FIELDS", "workspace_bytes",
            "workspace_needed", "workspace_flags", "MAX_K", "FLAG_BAD_TOKEN", "FLAG_BAD_DRAFT_LEN",
            "bench_time_kernels", "bench_events_used", "bench_set_tuning", "bench_empty_kernel", "bench_stream_read",
-           "BENCH_K_DRAFT_STEP",
-           "BENCH_K_VERIFY_STATS", "BENCH_K_RESID", "BENCH_K_ACCEPT"]
+           "BENCH_K_DRAFT_STATS",
+           "BENCH_K_VERIFY_STATS", "BENCH_K_RESID", "BENCH_K_ACCEPT", "BENCH_K_DRAFT_FINISH"]

@@ -22,7 +22,7 @@ EXPORTS = ("svip_status_string", "svip_workspace_bytes", "svip_workspace_needed"
 # every symbol include/svip_bench.h declares (benchmark and experiment hooks, not the product ABI)
 BENCH_EXPORTS = ("svip_bench_time_kernels", "svip_bench_events_used", "svip_bench_set_tuning", "svip_bench_empty_kernel",
                  "svip_bench_stream_sink_words", "svip_bench_stream_read")
-BENCH_K_DRAFT_STEP, BENCH_K_VERIFY_STATS, BENCH_K_RESID, BENCH_K_ACCEPT = 0, 1, 2, 3
+BENCH_K_DRAFT_STATS, BENCH_K_VERIFY_STATS, BENCH_K_RESID, BENCH_K_ACCEPT, BENCH_K_DRAFT_FINISH = 0, 1, 2, 3, 4
 
 
 class SvipError(RuntimeError):
@@ -51,7 +51,7 @@ class BenchTuning(ctypes.Structure):
     """svip_bench_tuning of include/svip_bench.h, field for field."""
     _fields_ = [("draft_slices", ctypes.c_int), ("stats_slices", ctypes.c_int), ("resid_slices", ctypes.c_int),
                 ("pair_slices", ctypes.c_int),
-                ("even_tiles_per_slice", ctypes.c_int), ("warp_no_shortcut", ctypes.c_int), ("draft_no_tile_masses", ctypes.c_int), ("draft_launches", ctypes.c_int), ("stats_workgroups", ctypes.c_int)]
+                ("even_tiles_per_slice", ctypes.c_int), ("warp_no_shortcut", ctypes.c_int), ("stats_workgroups", ctypes.c_int)]
 
 
 def load():

@@ -1,8 +1,6 @@
 // Kernels of svip_draft_step and svip_draft_step_greedy.
 #pragma once
-#include "exchange.h"
 #include "kernel_args.h"
-#include "stage_clock.h"
 #include "sample_weights.h"
 
 namespace svip {
@@ -19,54 +17,12 @@ __device__ __forceinline__ bool at_cap(const DraftArgs &a, int b)
     return a.step_j + 1 >= cap;
 }
 
-// What a slice's workgroup hands to the row's last workgroup: the slice statistics and, for slices of
-// at most TILE_MASSES tiles, the mass of every tile (relative to the slice maximum).  Seven 64-bit words.
-struct DraftSlot {
-    Partial p;
-    double G[TILE_MASSES];
-};
-template <bool TILES>
-__device__ __forceinline__ void publish_slot(DraftSlot *slot, const Partial &p, const double (&G)[TILE_MASSES])
-{
-    unsigned long long *w = reinterpret_cast<unsigned long long *>(slot);
-    publish_u64(w + 0, (unsigned long long)__float_as_uint(p.m) | ((unsigned long long)(unsigned)p.idx << 32));
-    publish_u64(w + 1, (unsigned long long)__double_as_longlong(p.S));
-    publish_u64(w + 2, (unsigned long long)__double_as_longlong(p.t));
-    if (TILES) {
-#pragma unroll
-        for (int v = 0; v < TILE_MASSES; ++v) publish_u64(w + 3 + v, (unsigned long long)__double_as_longlong(G[v]));
-    }
-}
-template <bool TILES>
-__device__ __forceinline__ void fetch_slot(const DraftSlot *slot, Partial &p, double (&G)[TILE_MASSES])
-{
-    const unsigned long long *w = reinterpret_cast<const unsigned long long *>(slot);
-    unsigned long long x[3 + TILE_MASSES];
-#pragma unroll
-    for (int v = 0; v < (TILES ? 3 + TILE_MASSES : 3); ++v) x[v] = fetch_u64(w + v);      // all in flight together
-    p.m = __uint_as_float((unsigned)x[0]);
-    p.idx = (int)(unsigned)(x[0] >> 32);
-    p.S = __longlong_as_double((long long)x[1]);
-    p.t = __longlong_as_double((long long)x[2]);
-    if (TILES) {
-#pragma unroll
-        for (int v = 0; v < TILE_MASSES; ++v) G[v] = __longlong_as_double((long long)x[3 + v]);
-    }
-}
-
 struct FinishLds {
     LocateLds loc;
     double target, L, S, tt;
     float m;
     int slice, tile;
     int use_resid;
-};
-
-struct DraftLds {
-    CombineLds comb;
-    FinishLds fin;
-    DraftSlot own;     // the only slice's record when a row is not cut
-    int last;          // this workgroup drew the row's final ticket
 };
 
 // Entropy of weights e_i = exp2(x_i) with sum S and tt = sum e_i x_i:  H = ln S - ln2 tt / S, then the
@@ -83,113 +39,125 @@ __device__ __forceinline__ void write_row_outputs(const DraftArgs &a, int b, lon
     if (a.draft_len) a.draft_len[b] = a.step_j + 1;
 }
 
-// The whole draft step in one launch, grid (rows * slices).  Every workgroup streams one slice of
-// one row and publishes its statistics; the workgroup that draws the row's final ticket merges the
-// slices, writes entropy, logsumexp and stop flag, and finds the token: by the inverse CDF in the one
-// tile (TILES: slices of at most TILE_MASSES tiles, whose tile masses are published too) or the one
-// slice that holds u * S, re-read from cache; or, with ARG (greedy drafting), as the first maximum
-// the statistics already carry.  A stopped row's workgroups leave at once; its slice 0 writes the
-// token -1 and keeps the flag.
-// PHASE 0 is that single launch.  PHASES 1 and 2 are the same work as two launches ordered by the stream:
-// 1 = the slices' statistics only, grid (rows * slices), stored plainly; 2 = the rows' last step only,
-// grid (rows).  A kernel boundary costs about 2 us; the hand-over inside one launch costs every slice's
-// workgroup about 1 us of waiting for acknowledged stores and its ticket, which a grid of more than one
-// round of workgroups pays again and again, so large batches take the two launches.
-template <typename DT, bool ARG, bool TILES, int PHASE>
-__global__ __launch_bounds__(WG, 5) void k_draft_step(DraftArgs a)
+// The draft step is two launches ordered by the stream.
+//
+// k_draft_stats: the statistics of a row as one record per WAVE.  Record r of a row covers tiles
+// [r * tps, (r + 1) * tps), and a wave reads a tile (256 consecutive vectors) as four loads of 64
+// consecutive vectors.  Nothing is shared between the waves of a workgroup -- no LDS, no barrier, so
+// no wave waits for data that another wave's loads are still bringing in.
+// k_draft_finish: one workgroup per row; one wave merges the row's records (a record per lane), writes
+// entropy, logsumexp and stop flag, and picks the record that holds u * S -- for rows of up to 64 tiles
+// a single tile, which is all the inverse-CDF search has to read again; with greedy drafting (ARG) the
+// token is the first maximum the records already carry and nothing is read again.
+//
+// A single launch in which the row's last workgroup does the second part (hand-over through
+// write-through stores and a ticket, as the residual pass of verification does) measured the same at 64
+// rows of 128K logits and slower beyond, and was dropped for this simpler form.
+
+// One batch of a wave: chunks [c0, c0 + NU) of 64 vectors each; CHECKED for the row's last, partial tile.
+template <typename DT, int NU, bool CHECKED>
+__device__ __forceinline__ void wave_load(const DT *row, int V, int c0, typename RawOf<DT>::type (&raw)[NU])
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+        raw[u] = CHECKED ? load_raw_checked<DT>(row, (c0 + u) * 64 + lane, V) : load_raw<DT>(row, (c0 + u) * 64 + lane);
+}
+template <typename DT, int NU, bool ARG>
+__device__ __forceinline__ void wave_accumulate(const typename RawOf<DT>::type (&raw)[NU], int c0, float &m, float &ones,
+                                                float &S, float &t, int &idx, const Scale &sc)
 {
     constexpr int N = VecOf<DT>::N;
-    __shared__ DraftLds sh;
-    const int ns = a.geo.ns;
-    const int b = PHASE == 2 ? blockIdx.x : blockIdx.x / ns, s = PHASE == 2 ? 0 : blockIdx.x - b * ns, tid = threadIdx.x;
-    const long long o = (long long)b * a.io_stride;
-    STAGE(0);
-    STAGE_WHERE();
-    // A stopped row leaves at once -- except in the single launch, which is bound by round trips to memory,
-    // not by bandwidth: there the flag is only looked at once the slice has been read, so that its load and
-    // the logits' loads travel together (the logits of a stopped row are read and ignored).
+    float z[NU][N];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) unpack<DT>(raw[u], z[u]);
+    accumulate<N, NU, ARG>(z, m, ones, S, t, sc, idx, c0);
+}
+
+// grid (ceil(rows * records / 4)), one wave per record.
+template <typename DT, bool ARG>
+__global__ __launch_bounds__(WG, 8) void k_draft_stats(DraftArgs a)
+{
+    constexpr int N = VecOf<DT>::N, CPT = WG / 64;       // chunks of 64 vectors per tile
+    const int lane = threadIdx.x & 63, nrec = a.geo.ns;
+    const unsigned gw = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+    if (gw >= (unsigned)a.B * (unsigned)nrec) return;
+    const int b = (int)(gw / (unsigned)nrec), r = (int)(gw - (unsigned)b * (unsigned)nrec);
+    const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
+    const int tb = r * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const int fe = min(te, a.geo.V / (WG * N));           // end of the tiles wholly inside the row
+    float m = neg_inf(), ones = 0.f, S = 0.f, t = 0.f;
+    int idx = -1;
+    // The record's first tile is requested before the row's stop flag is looked at, so that the two travel
+    // together (a step is bound by round trips to memory); a stopped row costs those loads and nothing else.
     const bool stopped = a.stop_in && a.stop_in[b];
-    if (PHASE != 0 && stopped) {
-        if (s == 0 && tid == 0) {
+    typename RawOf<DT>::type raw[CPT];
+    if (tb < fe) wave_load<DT, CPT, false>(row, a.geo.V, tb * CPT, raw);
+    else wave_load<DT, CPT, true>(row, a.geo.V, tb * CPT, raw);
+    if (stopped) return;
+    wave_accumulate<DT, CPT, ARG>(raw, tb * CPT, m, ones, S, t, idx, a.sc);
+    for (int t0 = tb + 1; t0 < te; ++t0) {
+        if (t0 < fe) wave_load<DT, CPT, false>(row, a.geo.V, t0 * CPT, raw);
+        else wave_load<DT, CPT, true>(row, a.geo.V, t0 * CPT, raw);
+        wave_accumulate<DT, CPT, ARG>(raw, t0 * CPT, m, ones, S, t, idx, a.sc);
+    }
+    // the wave's lanes to one record: maximum first, then sums rescaled to it in fp64
+    const float mw = wave_max(m);
+    double Sd = 0.0, td = 0.0;
+    if (m != neg_inf()) {
+        const float xd = scaled_diff(m, mw, a.sc);
+        const double all = (double)ones + (double)S, f = (double)exp2_raw(xd);
+        Sd = f * all;
+        td = f * ((double)t + (double)xd * all);
+    }
+    Sd = wave_sum(Sd);
+    td = wave_sum(td);
+    int first = -1;
+    if (ARG) {      // smallest index among the lanes that hold the wave maximum
+        const int cand = (m == mw && idx >= 0) ? idx : 0x7FFFFFFF;
+        const int wmin = -wave_reduce(-cand, OpMax{});
+        first = wmin == 0x7FFFFFFF ? -1 : wmin;
+    }
+    if (lane == 0) {
+        Partial p;
+        p.m = mw;
+        p.idx = first;
+        p.S = Sd;
+        p.t = td;
+        a.part[(size_t)b * nrec + r] = p;
+    }
+}
+
+// grid (rows): the rows' last step over the records of k_draft_stats.
+template <typename DT, bool ARG>
+__global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
+{
+    constexpr int N = VecOf<DT>::N;
+    __shared__ FinishLds fin;
+    const int b = blockIdx.x, tid = threadIdx.x, nrec = a.geo.ns;
+    const long long o = (long long)b * a.io_stride;
+    // independent loads first: the row's flag, its uniform and its records travel together
+    const bool stopped = a.stop_in && a.stop_in[b];
+    Partial p;
+    p.m = neg_inf();
+    p.idx = -1;
+    p.S = 0.0;
+    p.t = 0.0;
+    float u = 0.f;
+    if (tid < 64) {
+        if (tid < nrec) p = a.part[(size_t)b * nrec + tid];
+        if (!ARG) u = a.u[o];
+    }
+    if (stopped) {
+        if (tid == 0) {
             a.token[o] = -1;
             a.stop[b] = 1;
         }
         return;
     }
     const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
-    DraftSlot *slots = static_cast<DraftSlot *>(a.part) + (size_t)b * ns;
-    if (PHASE != 2) {
-        const int tb = s * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-        STAGE(1);
-        double G[TILE_MASSES];
-        const Partial p = slice_stats<DT, ARG, TILES && !ARG>(row, a.geo.V, tb, te, a.sc, sh.comb, G);
-        STAGE(2);
-        if (PHASE == 0 && stopped) {
-            if (s == 0 && tid == 0) {
-                a.token[o] = -1;
-                a.stop[b] = 1;
-            }
-            return;
-        }
-        if (PHASE == 1) {
-            if (tid == 0) {
-                slots[s].p = p;
-                if (TILES && !ARG) {
-#pragma unroll
-                    for (int v = 0; v < TILE_MASSES; ++v) slots[s].G[v] = G[v];
-                }
-            }
-            return;
-        }
-        if (tid == 0) {
-            if (ns == 1) {
-                sh.own.p = p;
-#pragma unroll
-                for (int v = 0; v < TILE_MASSES; ++v) sh.own.G[v] = G[v];
-                sh.last = 1;
-            } else {
-                publish_slot<TILES && !ARG>(slots + s, p, G);
-                stores_done();
-                STAGE(3);
-                sh.last = take_ticket(ticket(a.tickets, b, TICKET_DRAFT)) == (unsigned)ns - 1u;
-            }
-        }
-        __syncthreads();
-        STAGE(4);
-        if (!sh.last) return;
-    }
-
-    // ---- the row's last workgroup ----
     if (tid < 64) {
-        Partial p;
-        p.m = neg_inf();
-        p.idx = -1;
-        p.S = 0.0;
-        p.t = 0.0;
-        double G[TILE_MASSES];
-#pragma unroll
-        for (int v = 0; v < TILE_MASSES; ++v) G[v] = 0.0;
-        if (PHASE == 2) {
-            if (tid < ns) {         // written by the launch before: plain loads
-                p = slots[tid].p;
-                if (TILES && !ARG) {
-#pragma unroll
-                    for (int v = 0; v < TILE_MASSES; ++v) G[v] = slots[tid].G[v];
-                }
-            }
-        } else if (ns == 1) {
-            if (tid == 0) {
-                p = sh.own.p;
-#pragma unroll
-                for (int v = 0; v < TILE_MASSES; ++v) G[v] = sh.own.G[v];
-            }
-        } else if (tid < ns) {
-            fetch_slot<TILES && !ARG>(slots + tid, p, G);
-        }
-        float u = 0.f;
-        if (!ARG) u = a.u[o];
-        if (PHASE == 0 && tid == 0 && ns > 1) reset_tickets(ticket(a.tickets, b, TICKET_DRAFT));
-        // everything relative to the row maximum: this lane's slice by the factor f
+        // everything relative to the row maximum: this lane's record by the factor f
         const float mrow = wave_max(p.m);
         double f = 0.0, xd = 0.0;
         if (p.m != neg_inf() && p.S > 0.0) {
@@ -197,11 +165,11 @@ __global__ __launch_bounds__(WG, 5) void k_draft_step(DraftArgs a)
             f = exp2(xd);
         }
         const double M = f * p.S;
-        const double S = wave_sum(M);
+        const double incl = wave_inclusive_sum(M);
+        const double S = read_lane(incl, 63);
         const double tt = wave_sum(f * (p.t + xd * p.S));
-        STAGE(5);
         if (ARG) {
-            // slices are in index order: the first slice that reaches the row maximum holds its first index
+            // records are in index order: the first that reaches the row maximum holds its first index
             const unsigned long long at_max = __ballot(p.m == mrow && p.idx >= 0);
             const int tok = at_max ? read_lane(p.idx, __ffsll((long long)at_max) - 1) : -1;
             if (tid == 0) {
@@ -210,62 +178,33 @@ __global__ __launch_bounds__(WG, 5) void k_draft_step(DraftArgs a)
                 write_row_outputs(a, b, o, mrow, S, tt);
             }
         } else {
-            // the draw: slices by the masses the search itself will meet (the tile sums where there are any)
-            double Mp = M;
-            if (TILES) {
-                Mp = 0.0;
-#pragma unroll
-                for (int v = 0; v < TILE_MASSES; ++v) {
-                    G[v] *= f;
-                    Mp += G[v];
-                }
-            }
-            const double incl = wave_inclusive_sum(Mp);
             double local;
-            const int sl = pick_slice(Mp, (double)u * read_lane(incl, 63), incl, &local);
-            int tile = 0;
-            if (TILES) {
-                double Gs[TILE_MASSES];
-#pragma unroll
-                for (int v = 0; v < TILE_MASSES; ++v) Gs[v] = read_lane(G[v], sl);
-                double in_tile;
-                tile = pick_tile(Gs, local, &in_tile);
-                local = in_tile;
-            }
+            const int rec = pick_slice(M, (double)u * S, incl, &local);
             if (tid == 0) {
-                sh.fin.target = local;
-                sh.fin.L = (double)mrow * a.sc.c;
-                sh.fin.S = S;
-                sh.fin.tt = tt;
-                sh.fin.m = mrow;
-                sh.fin.slice = sl;
-                sh.fin.tile = tile;
+                fin.target = local;
+                fin.L = (double)mrow * a.sc.c;
+                fin.S = S;
+                fin.tt = tt;
+                fin.m = mrow;
+                fin.slice = rec;
             }
         }
     }
     if (ARG) return;
     __syncthreads();
-    STAGE(6);
-    SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, sh.fin.L)};
+    SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, fin.L)};
     // entropy, logsumexp and the stop test do not depend on the token: one thread of the last wave
     // computes and stores them while the logits are on their way
     auto row_outputs = [&]() {
-        if (tid == WG - 1) write_row_outputs(a, b, o, sh.fin.m, sh.fin.S, sh.fin.tt);
+        if (tid == WG - 1) write_row_outputs(a, b, o, fin.m, fin.S, fin.tt);
     };
     float wtok;
-    int tok;
-    if (TILES) {
-        const int tb = sh.fin.slice * a.geo.tps + sh.fin.tile;
-        tok = locate_in_slice<N, 1>(wf, tb, tb + 1, sh.fin.target, sh.fin.loc, &wtok, row_outputs);
-    } else {
-        const int tb = sh.fin.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-        tok = locate_in_slice<N, LOCATE_UNROLL>(wf, tb, te, sh.fin.target, sh.fin.loc, &wtok, row_outputs);
-    }
+    const int tb = fin.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const int tok = locate_in_slice<N, 1>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs);
     if (tid == 0) {
         a.token[o] = tok;
-        if (a.q_tok) a.q_tok[o] = (float)((double)wtok / sh.fin.S);
+        if (a.q_tok) a.q_tok[o] = (float)((double)wtok / fin.S);
     }
-    STAGE(7);
 }
 
 }  // namespace svip

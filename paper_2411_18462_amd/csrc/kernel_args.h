@@ -24,7 +24,10 @@ struct Workspace {
 
 constexpr int MAX_BATCH = 1 << 20;               // sequences per call (grids are one-dimensional)
 constexpr size_t HEADER_BYTES = 256;
-constexpr int TICKETS_PER_ROW = 3;               // draft step / statistics pass of verify / residual pass
+#ifndef SVIP_TICKET_STRIDE
+#define SVIP_TICKET_STRIDE 16
+#endif
+constexpr int TICKETS_PER_ROW = SVIP_TICKET_STRIDE;   // words between the counters of consecutive rows
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static size_t ws_rec_bytes(int B) { return align256((size_t)B * sizeof(SeqRec)); }
@@ -33,7 +36,7 @@ static size_t ws_ticket_bytes(int B) { return align256((size_t)B * TICKETS_PER_R
 
 // Layout: flag word | records | slice masses | slice statistics ...            ... ticket counters.
 // The counters sit at the END of the workspace (the given size rounded down to 256 bytes) and counter
-// t of row b lies 3 b + t + 1 words below that end, whatever the batch size of the call: regions at the
+// t of row b lies TICKETS_PER_ROW * b + t + 1 words below that end, whatever the batch size of the call: regions at the
 // front never reach them (every call checks front + counters <= size), so they keep the zeros that
 // svip_workspace_reset wrote and that every kernel restores, also when calls of different batch sizes
 // share a workspace.
@@ -51,7 +54,7 @@ static Workspace carve(void *ws, size_t bytes, int B, int mass_slices)
     w.part = reinterpret_cast<Partial *>(p);
     return w;
 }
-enum { TICKET_DRAFT = 0, TICKET_STATS = 1, TICKET_RESID = 2 };
+enum { TICKET_RESID = 0 };
 __device__ __forceinline__ unsigned *ticket(unsigned *tickets_end, int b, int t)
 {
     return tickets_end - ((size_t)b * TICKETS_PER_ROW + t + 1);
@@ -79,8 +82,7 @@ struct DraftArgs {
     unsigned char *stop;
     int *draft_len;
     long long io_stride;
-    void *part;             // [B][ns] slice records (DraftSlot)
-    unsigned *tickets;      // end of the workspace's ticket counters
+    Partial *part;          // [B][ns] records of the row's waves
 };
 
 struct VerifyArgs {

@@ -1,9 +1,10 @@
 // Per-row building blocks of the SVIP kernels: 128-bit logit loads, the scaled exponential,
 // streaming softmax statistics of a row slice, and the in-slice inverse-CDF search.
 //
-// Geometry.  A row of V logits is cut into vectors of 16 bytes (8 bf16 or fp16 / 4 fp32), tiles of
-// WG consecutive vectors (one per thread, so a wave reads 1 KiB contiguous), and `ns` slices
-// of `tps` consecutive tiles.  One workgroup handles one slice of one row.
+// Geometry.  A row of V logits is cut into vectors of 16 bytes (8 bf16 or fp16 / 4 fp32), chunks of 64
+// consecutive vectors (what one wave reads with one load: 1 KiB contiguous), tiles of WG consecutive
+// vectors (four chunks; one vector per thread of a workgroup), and `ns` slices of `tps` consecutive
+// tiles.  The streaming passes give a slice to a workgroup; the draft statistics give it to a wave.
 //
 // Arithmetic.  With c = log2(e)/T split into two fp32 parts, a logit z contributes
 // exp2((z - m) * c) relative to the running maximum m (draft statistics: the subtraction comes
@@ -16,7 +17,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "stage_clock.h"
 #include "wave_ops.h"
 
 namespace svip {
@@ -243,7 +243,8 @@ struct Partial {
 };
 
 // Smallest token index among the batch's elements equal to v (-1 if none); z[u] is vector
-// (t0 + u) * TW + (thread index within the tile) of the row, TW the tile width in vectors.
+// (t0 + u) * TW + (thread index modulo TW) of the row: TW = WG for a workgroup reading tile by tile,
+// TW = 64 for a wave reading chunk by chunk.
 template <int N, int NU, int TW = WG>
 __device__ __forceinline__ int first_equal(const float (&z)[NU][N], float v, int t0)
 {
@@ -265,19 +266,16 @@ __device__ __forceinline__ int first_equal(const float (&z)[NU][N], float v, int
 // loop sums fract(w) (fract(1) = 0, fract(w) = w below 1) beside w itself; the difference of the two
 // batch sums is the batch's count of ones up to rounding far below 1/2.  With ARG, idx follows the
 // smallest index that holds m: it moves only when the maximum strictly increases, so earlier equal
-// values keep it; t0 is the batch's first tile and TW the tile width in vectors.
-// With TILES, g[] additionally receives the sum of the weights of every tile (g[u0 + u] for the
-// batch's tile u, relative to the thread's running maximum like S), which lets the sampler go
-// straight to the tile that holds its target instead of searching a slice.
-template <int N, int NU, bool ARG, bool TILES, int TW>
+// values keep it; the batch is one wave's chunks c0 .. c0 + NU - 1 (64 vectors each).
+template <int N, int NU, bool ARG>
 __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, float &ones, float &S, float &t,
-                                           const Scale &sc, int &idx, int t0, float (&g)[TILE_MASSES], int u0)
+                                           const Scale &sc, int &idx, int c0)
 {
     float mb = tree_max<N>(z[0]);
 #pragma unroll
     for (int u = 1; u < NU; ++u) mb = vmax(mb, tree_max<N>(z[u]));
     if (mb > m) {
-        if (ARG) idx = first_equal<N, NU, TW>(z, mb, t0);
+        if (ARG) idx = first_equal<N, NU, 64>(z, mb, c0);
         if (m != neg_inf()) {
             const float xd = scaled_diff(m, mb, sc);
             const float f = exp2_raw(xd);
@@ -286,10 +284,6 @@ __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, fl
                 t = f * fmaf(xd, all, t);
                 S = f * all;
                 ones = 0.f;
-                if (TILES) {
-#pragma unroll
-                    for (int v = 0; v < TILE_MASSES; ++v) g[v] *= f;
-                }
             }                                   // else: still weight 1 at fp32 resolution, nothing moves
         }
         m = mb;
@@ -308,152 +302,20 @@ __device__ __forceinline__ void accumulate(const float (&z)[NU][N], float &m, fl
         }
         // group sums are formed first, then added to the batch sum: the running sums only
         // ever take one addition per batch
-        const float wt = tree_sum<N>(w);
-        Wb += wt;
+        Wb += tree_sum<N>(w);
         Sb += tree_sum<N>(fr);
         tb += tree_sum<N>(wx);
-        if (TILES) {
-#pragma unroll
-            for (int v = 0; v < TILE_MASSES; ++v) g[v] = (v == u0 + u) ? wt : g[v];
-        }
     }
     ones += rintf(Wb - Sb);
     S += Sb;
     t += tb;
 }
 
-template <typename DT, int NU, bool ARG, bool TILES>
-__device__ __forceinline__ void stats_batch(const DT *row, int t0, float &m, float &ones, float &S, float &t,
-                                            int &idx, const Scale &sc, float (&g)[TILE_MASSES], int u0)
-{
-    constexpr int N = VecOf<DT>::N;
-    typename RawOf<DT>::type raw[NU];
-#pragma unroll
-    for (int u = 0; u < NU; ++u) raw[u] = load_raw<DT>(row, (t0 + u) * WG + (int)threadIdx.x);
-    STAGE_LOADED(10);
-    float z[NU][N];
-#pragma unroll
-    for (int u = 0; u < NU; ++u) unpack<DT>(raw[u], z[u]);
-    accumulate<N, NU, ARG, TILES, WG>(z, m, ones, S, t, sc, idx, t0, g, u0);
-    STAGE(11);
-}
-
 // LDS of one workgroup combination (each field is written once, so two barriers suffice).
 struct CombineLds {
     float m[NWAVE];
-    int idx[NWAVE];
-    double S[NWAVE], t[NWAVE];
-    double G[NWAVE][TILE_MASSES];
+    double S[NWAVE];
 };
-
-// Workgroup combination of the per-thread (m, ones, S, t): maximum first, then every thread
-// rescales ones + S and t to it and the sums are added in fp64 (with TILES the tile sums g likewise,
-// into G).  Result valid in thread 0.  One call per kernel and LDS block.
-template <bool ARG, bool TILES>
-__device__ __forceinline__ Partial wg_combine(float m, float ones, float S, float t, const Scale &sc,
-                                              CombineLds &lds, int idx, const float (&g)[TILE_MASSES],
-                                              double (&G)[TILE_MASSES])
-{
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const float mw = wave_max(m);
-    if (lane == 0) lds.m[wave] = mw;
-    __syncthreads();
-    STAGE(12);
-    float mg = lds.m[0];
-#pragma unroll
-    for (int w = 1; w < NWAVE; ++w) mg = fmaxf(mg, lds.m[w]);
-    double Sd = 0.0, td = 0.0, f = 0.0;
-    if (m != neg_inf()) {
-        const float xd = scaled_diff(m, mg, sc);
-        const double all = (double)ones + (double)S;      // exact in fp64
-        f = (double)exp2_raw(xd);
-        Sd = f * all;
-        td = f * ((double)t + (double)xd * all);
-    }
-    Sd = wave_sum(Sd);
-    td = wave_sum(td);
-    double Gd[TILE_MASSES];
-    if (TILES) {
-#pragma unroll
-        for (int v = 0; v < TILE_MASSES; ++v) Gd[v] = wave_sum(f * (double)g[v]);
-    }
-    int wmin = 0x7FFFFFFF;
-    if (ARG) {      // smallest index among the threads that hold the workgroup maximum
-        const int cand = (m == mg && idx >= 0) ? idx : 0x7FFFFFFF;
-        wmin = -wave_reduce(-cand, OpMax{});
-    }
-    if (lane == 0) {
-        lds.S[wave] = Sd;
-        lds.t[wave] = td;
-        if (ARG) lds.idx[wave] = wmin;
-        if (TILES) {
-#pragma unroll
-            for (int v = 0; v < TILE_MASSES; ++v) lds.G[wave][v] = Gd[v];
-        }
-    }
-    STAGE(13);
-    __syncthreads();
-    STAGE(14);
-    Partial p;
-    p.m = mg;
-    p.idx = -1;
-    p.S = 0.0;
-    p.t = 0.0;
-#pragma unroll
-    for (int v = 0; v < TILE_MASSES; ++v) G[v] = 0.0;
-    if (tid == 0) {
-#pragma unroll
-        for (int w = 0; w < NWAVE; ++w) {
-            p.S += lds.S[w];
-            p.t += lds.t[w];
-        }
-        if (ARG) {
-            int best = lds.idx[0];
-#pragma unroll
-            for (int w = 1; w < NWAVE; ++w) best = min(best, lds.idx[w]);
-            p.idx = best == 0x7FFFFFFF ? -1 : best;
-        }
-        if (TILES) {
-#pragma unroll
-            for (int v = 0; v < TILE_MASSES; ++v) {
-#pragma unroll
-                for (int w = 0; w < NWAVE; ++w) G[v] += lds.G[w][v];
-            }
-        }
-    }
-    return p;
-}
-
-// Streaming statistics (m, S, t) of tiles [tb, te) of one row.  Every thread keeps a running
-// maximum of its own elements (rescaling its sums on the rare increase), so the loop has no
-// barrier; the workgroup combines at the end.  Tiles that lie wholly inside the row are read in
-// unchecked batches of 32 logits per thread (then 4/2/1 vectors); only the row's last tile can be
-// partial and is read with bounds checks.  With TILES (slices of at most TILE_MASSES tiles) G[v] receives
-// the mass of the slice's tile v relative to the slice maximum.  Result valid in thread 0.
-template <typename DT, bool ARG, bool TILES>
-__device__ __forceinline__ Partial slice_stats(const DT *row, int V, int tb, int te, const Scale &sc,
-                                               CombineLds &lds, double (&G)[TILE_MASSES])
-{
-    constexpr int N = VecOf<DT>::N, NB = 32 / N;
-    const int tid = threadIdx.x;
-    float m = neg_inf(), ones = 0.f, S = 0.f, t = 0.f;
-    float g[TILE_MASSES];
-#pragma unroll
-    for (int v = 0; v < TILE_MASSES; ++v) g[v] = 0.f;
-    int idx = -1;
-    const int fe = min(te, V / (WG * N));      // end of the tiles that are wholly inside the row
-    int t0 = tb;
-    for (; t0 + NB <= fe; t0 += NB) stats_batch<DT, NB, ARG, TILES>(row, t0, m, ones, S, t, idx, sc, g, t0 - tb);
-    if (NB == 8 && t0 + 4 <= fe) { stats_batch<DT, 4, ARG, TILES>(row, t0, m, ones, S, t, idx, sc, g, t0 - tb); t0 += 4; }
-    if (t0 + 2 <= fe) { stats_batch<DT, 2, ARG, TILES>(row, t0, m, ones, S, t, idx, sc, g, t0 - tb); t0 += 2; }
-    if (t0 + 1 <= fe) { stats_batch<DT, 1, ARG, TILES>(row, t0, m, ones, S, t, idx, sc, g, t0 - tb); t0 += 1; }
-    if (t0 < te) {
-        float z[1][N];
-        unpack<DT>(load_raw_checked(row, t0 * WG + tid, V), z[0]);
-        accumulate<N, 1, ARG, TILES, WG>(z, m, ones, S, t, sc, idx, t0, g, t0 - tb);
-    }
-    return wg_combine<ARG, TILES>(m, ones, S, t, sc, lds, idx, g, G);
-}
 
 // ---- logsumexp only (statistics pass of verification) -----------------------------------------
 //

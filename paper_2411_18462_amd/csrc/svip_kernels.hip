@@ -1,9 +1,9 @@
 // SVIP hot path for MI355X (gfx950): launch code and the C ABI declared in include/svip.h; the kernels
 // live in draft_kernels.h, verify_kernels.h, greedy_kernels.h, pair_kernels.h and warp_kernels.h.
 //
-// svip_draft_step  =  k_draft_step     grid (rows * slices)      per-slice (m, S, t) of every active row; the
-//                                      workgroup that finishes a row last merges its slices: entropy, stop
-//                                      test, inverse CDF (greedy: the first maximum, no search)
+// svip_draft_step  =  k_draft_stats    grid (rows * records / 4) one wave per record: (m, S, t) of a tile of a row
+//                     k_draft_finish   grid (rows)               merge of the records: entropy, stop test, inverse
+//                                      CDF inside the one record that holds the draw (greedy: the first maximum)
 // svip_verify      =  k_verify_stats   grid (stat rows * slices) per-slice (reference, sum) of every needed row
 //                     k_accept         grid (sequences), 1 wave  p/q tests, ballot scan for the first rejection
 //                     k_resid          grid (sequences * slices) slice masses of the residual / bonus row; the
@@ -18,8 +18,8 @@
 // svip_warp_logits =  k_warp           grid (rows), 1024 threads  top-k / top-p thresholds by radix select, masked copy
 //
 // The passes are bound by HBM reads of the logits; there is no dense contraction, hence no MFMA.
-// Nothing spins or waits on the device: kernels of one call are ordered by the stream, and inside a
-// kernel the "last workgroup" hand-over of exchange.h lets a row's remaining work follow its slices
+// Nothing spins or waits on the device: kernels of one call are ordered by the stream; inside the
+// residual pass the "last workgroup" hand-over of exchange.h lets a sequence's draw follow its slices
 // without a second launch.  Each finishing step issues all of its independent loads before the first
 // dependent one, because at small batches a step is bound by round trips to memory, not by bandwidth.
 #include <hip/hip_runtime.h>
@@ -95,7 +95,7 @@ static __device__ __align__(256) unsigned char scratch[SVIP_STATIC_SCRATCH_BYTES
 // Launch-shape overrides for experiments (svip_bench_set_tuning; all zero = the library's own choice).
 // Workspace sizes are always computed for the library's own choice; a forced shape that needs more than
 // the workspace holds is rejected by the call.
-static svip_bench_tuning g_tune = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+static svip_bench_tuning g_tune = {0, 0, 0, 0, 0, 0, 0};
 
 // Slices per row: enough workgroups to fill 256 CUs several times over, at most MAX_SLICES,
 // and (want_one_batch) slices of at most LOCATE_UNROLL tiles so the sampler scans one batch.
@@ -196,7 +196,7 @@ static size_t ws_fixed_bytes(int B, int mass_slices)
     return HEADER_BYTES + ws_rec_bytes(B) + ws_mass_bytes(B, mass_slices) + ws_ticket_bytes(B);
 }
 
-static size_t need_draft(int B, const Geo &g) { return ws_fixed_bytes(B, 0) + align256((size_t)B * g.ns * sizeof(DraftSlot)); }
+static size_t need_draft(int B, const Geo &g) { return ws_fixed_bytes(B, 0) + align256((size_t)B * g.ns * sizeof(Partial)); }
 static size_t need_verify_greedy(int B, int k, const Geo &g)
 {
     return ws_fixed_bytes(B, 0) + align256((size_t)B * (k + 1) * g.ns * sizeof(unsigned long long));
@@ -218,7 +218,24 @@ static size_t need_pair(int B, int k, bool recompute_lse, const Geo &g, const Ge
 }
 
 // The slicing each pass uses (forced = an experiment's override, 0 = the library's choice).
-static Geo geo_draft(int B, int V, int vec, int forced) { return make_geo(V, vec, B, true, forced); }
+// The draft step: one record (= one wave of the statistics launch) per tile of 32 logits per thread, so the
+// search reads a single tile again; rows of more than MAX_SLICES tiles put more tiles into a record, and so
+// do batches of 192 rows and more, where the per-wave cost of a record outweighs the shorter search
+// (256 rows of 128K logits: 21.3 us a step with 32 records against 22.3 us with 63; 128 rows: 15.6 against 14.7).
+static Geo geo_draft(int B, int V, int vec, int forced)
+{
+    Geo g;
+    g.V = V;
+    const int nvec = (V + vec - 1) / vec;
+    g.ntiles = (nvec + WG - 1) / WG;
+    int ns = B >= 192 ? MAX_SLICES / 2 : MAX_SLICES;
+    if (forced > 0) ns = forced < MAX_SLICES ? forced : MAX_SLICES;
+    if (ns > g.ntiles) ns = g.ntiles;
+    if (ns < 1) ns = 1;
+    g.tps = (g.ntiles + ns - 1) / ns;
+    g.ns = (g.ntiles + g.tps - 1) / g.tps;
+    return g;
+}
 static Geo geo_stats(long long stat_rows, int V, int vec, int forced) { return make_geo(V, vec, stat_rows, false, forced); }
 // the residual pass: slices of four tiles like the draft step (at 64 sequences of 128K logits, 16 slices of
 // 4 tiles take 13 us, 32 slices of 2 tiles 16 us, 8 slices 20 us, one tile per slice 26 us)
@@ -266,35 +283,18 @@ svip_status draft_step_call(const DraftCall &c)
     a.draft_len = c.draft_len_out;
     a.io_stride = c.io_stride;
     a.part = w.part;
-    a.tickets = w.tickets;
     hipStream_t st = static_cast<hipStream_t>(c.stream);
-    const unsigned grid = (unsigned)a.geo.ns * (unsigned)c.B;
+    const unsigned waves = (unsigned)a.geo.ns * (unsigned)c.B, rows = (unsigned)c.B;
+    const unsigned grid = (waves + NWAVE - 1) / NWAVE;
     bool ok = false;
-    // one launch while all workgroups fit on the GPU at once (the hand-over inside the launch then costs less
-    // than a kernel boundary), two launches beyond that
-    const int mode = g_tune.draft_launches ? g_tune.draft_launches : (grid <= 1536u ? 1 : 2);
-    // tile masses shorten the last step and lengthen the statistics: they pay in the single launch only
-    // (two launches at 256 rows: 28 us without, 29.5 us with)
-    const bool tiles = a.geo.tps <= TILE_MASSES && (g_tune.draft_no_tile_masses ? false : mode == 1 || g_tune.draft_launches == 2);
     by_dtype(c.dtype, [&](auto tag) {
         using DT = decltype(tag);
-        const int cls = SVIP_BENCH_K_DRAFT_STEP;
-        if (mode == 1) {
-            if (c.greedy) ok = launch(k_draft_step<DT, true, false, 0>, grid, WG, st, a, cls);
-            else if (tiles) ok = launch(k_draft_step<DT, false, true, 0>, grid, WG, st, a, cls);
-            else ok = launch(k_draft_step<DT, false, false, 0>, grid, WG, st, a, cls);
-        } else {
-            const unsigned rows = (unsigned)c.B;
-            if (c.greedy)
-                ok = launch(k_draft_step<DT, true, false, 1>, grid, WG, st, a, cls) &&
-                     launch(k_draft_step<DT, true, false, 2>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
-            else if (tiles)
-                ok = launch(k_draft_step<DT, false, true, 1>, grid, WG, st, a, cls) &&
-                     launch(k_draft_step<DT, false, true, 2>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
-            else
-                ok = launch(k_draft_step<DT, false, false, 1>, grid, WG, st, a, cls) &&
-                     launch(k_draft_step<DT, false, false, 2>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
-        }
+        if (c.greedy)
+            ok = launch(k_draft_stats<DT, true>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STATS) &&
+                 launch(k_draft_finish<DT, true>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
+        else
+            ok = launch(k_draft_stats<DT, false>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STATS) &&
+                 launch(k_draft_finish<DT, false>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
     });
     return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
@@ -451,7 +451,7 @@ size_t svip_workspace_bytes(int B, int k_max, int V)
     // a row has at most `tiles` slices (fp32 rows have the most vectors)
     const size_t tiles = ((size_t)V + 4 * WG - 1) / (4 * WG);
     const size_t ns_max = tiles < MAX_SLICES ? tiles : MAX_SLICES;
-    size_t part_bytes = (size_t)B * ns_max * sizeof(DraftSlot);
+    size_t part_bytes = (size_t)B * ns_max * sizeof(Partial);
     if ((vrows + 8192) * sizeof(Partial) > part_bytes) part_bytes = (vrows + 8192) * sizeof(Partial);
     // diagnostics: two logsumexps per position and three sums per slice of its second pass
     const size_t pos = (size_t)B * (size_t)k_max;
@@ -733,25 +733,12 @@ svip_status svip_bench_stream_read(const void *buf, size_t bytes, int vectors_pe
     return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
 
-#ifdef SVIP_STAGE_CLOCK
-// Only in builds with -DSVIP_STAGE_CLOCK (not declared in any header): copies the stage notes of the
-// first `groups` workgroups of the last instrumented launch to the host; synchronises the device.
-svip_status svip_bench_stage_clock(unsigned long long *out_host, int groups)
-{
-    if (!out_host || groups < 1 || groups > STAGE_GROUPS) return SVIP_ERR_PARAM;
-    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(g_stage_clock), sizeof(unsigned long long) * STAGE_SLOTS * groups) ==
-                   hipSuccess
-               ? SVIP_OK
-               : SVIP_ERR_HIP;
-}
-#endif
-
 svip_status svip_bench_set_tuning(const svip_bench_tuning *tuning)
 {
-    const svip_bench_tuning zero = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const svip_bench_tuning zero = {0, 0, 0, 0, 0, 0, 0};
     const svip_bench_tuning t = tuning ? *tuning : zero;
     if (t.draft_slices < 0 || t.stats_slices < 0 || t.resid_slices < 0 || t.pair_slices < 0 ||
-        t.stats_workgroups < 0 || t.draft_launches < 0 || t.draft_launches > 2)
+        t.stats_workgroups < 0)
         return SVIP_ERR_PARAM;
     g_tune = t;
     return SVIP_OK;

@@ -27,7 +27,7 @@ def test_bench_hooks_reject_bad_arguments_and_never_change_workspace_sizes():
     assert lib.svip_bench_time_kernels(0, None, None, 0) == 0 and lib.svip_bench_events_used(0) == 0
     assert lib.svip_bench_events_used(9) == -1
     before = [svip.workspace_needed(c, __import__("torch").bfloat16, 64, 16, 128256) for c in range(6)]
-    svip.bench_set_tuning(draft_slices=64, stats_slices=64, resid_slices=64, pair_slices=64, draft_launches=2)
+    svip.bench_set_tuning(draft_slices=64, stats_slices=64, resid_slices=64, pair_slices=64)
     try:
         assert before == [svip.workspace_needed(c, __import__("torch").bfloat16, 64, 16, 128256) for c in range(6)]
     finally:

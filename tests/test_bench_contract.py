@@ -48,12 +48,12 @@ def test_bench_prints_one_json_line_with_the_required_objects():
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9 and 0.05 < r["frac"] < 1.0
     # the roofline object describes the kernel that holds the largest share of the step
     ks = d["kernels"]
-    assert set(ks) == {"k_draft_step", "k_verify_stats", "k_accept", "k_resid"}
+    assert set(ks) == {"k_draft_stats", "k_draft_finish", "k_verify_stats", "k_accept", "k_resid"}
     top = max(ks, key=lambda n: ks[n]["us_per_step"])
     assert r["kernel"].startswith(top) and r["bytes_per_launch"] == ks[top]["bytes_per_launch"]
     assert abs(sum(k["share_of_step_kernel_time"] for k in ks.values()) - 1.0) < 1e-9
     assert ks["k_verify_stats"]["bytes_per_launch"] == 64 * 17 * 128256 * 2
-    assert ks["k_draft_step"]["bytes_per_launch"] == 64 * 128256 * 2 and ks["k_draft_step"]["launches_per_step"] == 16
+    assert ks["k_draft_stats"]["bytes_per_launch"] == 64 * 128256 * 2 and ks["k_draft_stats"]["launches_per_step"] == 16
     # the calls, priced on algorithmic bytes: nothing beats the peak, the step is the sum of its parts
     rc = d["roofline_calls"]
     for name in ("draft_step", "verify", "whole_step"):
