@@ -43,10 +43,10 @@
  *     recorded in a sticky flag word inside the workspace (svip_workspace_flags).
  *   - `workspace` is device scratch of at least svip_workspace_bytes(B, k_max, V) bytes,
  *     256-byte aligned, that svip_workspace_reset has cleared once after allocation.  Besides
- *     partial results it holds, at its end, the counters with which the workgroups of a kernel
- *     hand a row's remaining work to whichever of them finishes last; every call leaves them
- *     at zero again.  Pass the same `workspace_bytes` with a workspace on every call.  Calls that
- *     run concurrently must use different workspaces.
+ *     partial results it holds, at its end, the counters with which the workgroups of svip_verify's
+ *     residual pass hand a sequence's draw to whichever of them finishes last; every call leaves
+ *     them at zero again.  Pass the same `workspace_bytes` with a workspace on every call.  Calls
+ *     that run concurrently must use different workspaces.
  *   - Same inputs give bit-identical outputs (no floating-point atomics, fixed combine order).
  */
 #ifndef SVIP_H
@@ -121,9 +121,10 @@ svip_status svip_workspace_flags(const void *workspace, void *hip_stream, unsign
  *   token_out, entropy_out = H, q_tok_out = q[token], lse_out = logsumexp(logits / temperature),
  * plus stop_out[b] and, if draft_len_out != NULL, draft_len_out[b] = step_j + 1.
  * Rows with stop_in[b] != 0 get token_out = -1 and stop_out[b] = 1 and nothing else is written
- * for them.  Their logits do not enter any result but may still be read (the flag and the logits
- * are fetched together: a step is bound by memory round trips, and waiting for the flag first
- * costs 0.13 us of a 12.9 us step at 64 rows), so draft_logits must be readable for every row.
+ * for them.  Their logits do not enter any result but may still be read (the flag and the first
+ * loads of the logits are requested together: a step is bound by memory round trips, and waiting
+ * for the flag first costs 0.25 us of an 11.3 us step at 64 rows), so draft_logits must be
+ * readable for every row.
  *
  * io_stride lets the per-row arrays be columns of [B, k_max] buffers (pass the address of
  * column step_j and io_stride = k_max), which is the layout svip_verify consumes; likewise
@@ -150,15 +151,15 @@ svip_status svip_draft_step(
 /*
  * svip_draft_step for callers that cannot allocate device memory or hand a workspace through: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
- * and results as svip_draft_step (bit for bit), without the workspace: the slice records and ticket
- * counters live in a fixed array of SVIP_STATIC_SCRATCH_BYTES inside the library's device code, one
- * copy per GPU, held until the process ends.  The call allocates nothing and frees nothing.
+ * and results as svip_draft_step (bit for bit), without the workspace: the rows' statistics records
+ * live in a fixed array of SVIP_STATIC_SCRATCH_BYTES inside the library's device code, one copy per
+ * GPU, held until the process ends.  The call allocates nothing and frees nothing.
  *   - Sizes whose records do not fit that array (svip_workspace_needed(SVIP_CALL_DRAFT_STEP, ...) >
- *     SVIP_STATIC_SCRATCH_BYTES; a few thousand rows of a 128K vocabulary) return SVIP_ERR_WORKSPACE.
+ *     SVIP_STATIC_SCRATCH_BYTES; about 1200 rows of a 128K vocabulary) return SVIP_ERR_WORKSPACE.
  *   - All calls on one GPU share the array: calls that overlap on one GPU (different streams, or
  *     threads) race and must be serialised by the caller.  Device-data flags are not reported.
- *   - The first call on a GPU looks the array up and enqueues a fill kernel that clears it; make that
- *     call before capturing a graph if the capture should hold the draft step alone.
+ *   - The first call on a GPU asks the runtime for the array's address on that GPU (no allocation,
+ *     nothing enqueued); nothing in the array has to be cleared.
  */
 #define SVIP_STATIC_SCRATCH_BYTES (1 << 20)
 svip_status svip_draft_step_static(

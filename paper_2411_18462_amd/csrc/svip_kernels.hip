@@ -97,8 +97,9 @@ static __device__ __align__(256) unsigned char scratch[SVIP_STATIC_SCRATCH_BYTES
 // the workspace holds is rejected by the call.
 static svip_bench_tuning g_tune = {0, 0, 0, 0, 0, 0, 0};
 
-// Slices per row: enough workgroups to fill 256 CUs several times over, at most MAX_SLICES,
-// and (want_one_batch) slices of at most LOCATE_UNROLL tiles so the sampler scans one batch.
+// Slices per row of the passes that give a slice to a workgroup: enough workgroups to fill 256 CUs several
+// times over, at most MAX_SLICES; want_one_batch (the residual pass): slices of min_tiles tiles, which the
+// sampler scans as one batch and whose tiles each get a mass of their own.
 static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int forced_ns, int min_tiles = 4)
 {
     Geo g;
@@ -107,8 +108,7 @@ static Geo make_geo(int V, int vec, long long rows, bool want_one_batch, int for
     g.ntiles = (nvec + WG - 1) / WG;
     long long ns;
     if (want_one_batch) {
-        // slices of min_tiles tiles (4: one batch of the statistics loop, and few enough tiles for tile masses);
-        // measured at 128K logits from 1 to 256 rows, 16 slices of 4 tiles beat both finer and coarser cuts
+        // slices of min_tiles tiles (4: 32 logits per thread, and few enough tiles for tile masses)
         long long cap = g.ntiles / min_tiles;
         if (cap < 1) cap = 1;
         ns = cap;
@@ -300,9 +300,9 @@ svip_status draft_step_call(const DraftCall &c)
 }
 
 // Device address of `scratch` on the current device, or nullptr.  The first call on a device looks the
-// symbol up (hipGetSymbolAddress with that device current) and clears the array with a fill kernel on the
-// given stream (the ticket counters must start at zero; every call leaves them at zero again).
-static void *static_scratch(hipStream_t st)
+// symbol up (hipGetSymbolAddress with that device current); every GPU holds its own copy of the array at
+// its own address.  Nothing in it has to start at zero: a draft step writes every record before it reads it.
+static void *static_scratch()
 {
     constexpr int MAX_DEVICES = 64;
     static void *ptr[MAX_DEVICES] = {};
@@ -311,11 +311,6 @@ static void *static_scratch(hipStream_t st)
     if (!ptr[dev]) {
         void *p = nullptr;
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
-        ZeroArgs z;
-        z.flags = static_cast<unsigned *>(p);
-        z.tail = static_cast<uint4 *>(p);
-        z.n16 = SVIP_STATIC_SCRATCH_BYTES / 16;
-        if (!launch(k_zero, 256u, 256u, st, z)) return nullptr;
         ptr[dev] = p;
     }
     return ptr[dev];
@@ -531,7 +526,7 @@ svip_status svip_draft_step_static(const void *draft_logits, int dtype, int B, i
     if (B <= 0 || B > MAX_BATCH || V <= 0) return SVIP_ERR_SHAPE;
     if (need_draft(B, geo_draft(B, V, vec_of(dtype), g_tune.draft_slices)) > (size_t)SVIP_STATIC_SCRATCH_BYTES)
         return SVIP_ERR_WORKSPACE;
-    void *ws = static_scratch(static_cast<hipStream_t>(hip_stream));
+    void *ws = static_scratch();
     if (!ws) return SVIP_ERR_HIP;
     const DraftCall c{false, draft_logits, dtype, B, V, row_stride, nullptr, 0, nullptr, temperature, h, step_j,
                       k_max, u_sample, stop_in, token_out, entropy_out, q_tok_out, lse_out, stop_out,
