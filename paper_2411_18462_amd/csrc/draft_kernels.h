@@ -200,7 +200,9 @@ __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
     };
     float wtok;
     const int tb = fin.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
-    const int tok = locate_in_slice<N, 1>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs);
+    // a record of one tile is searched as one batch of one tile, longer records two tiles at a time
+    const int tok = a.geo.tps == 1 ? locate_in_slice<N, 1>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs)
+                                   : locate_in_slice<N, 2>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs);
     if (tid == 0) {
         a.token[o] = tok;
         if (a.q_tok) a.q_tok[o] = (float)((double)wtok / fin.S);

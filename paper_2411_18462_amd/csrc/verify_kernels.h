@@ -214,7 +214,7 @@ __global__ __launch_bounds__(WG, 4) void k_resid(VerifyArgs a)
         const int wave = tid >> 6, lane = tid & 63;
 #pragma unroll
         for (int v = 0; v < TILE_MASSES; ++v) {
-            const double Wd = wave_sum_matrix((double)Wt[v]), Pd = wave_sum_matrix((double)Pt[v]);
+            const double Wd = wave_sum((double)Wt[v]), Pd = wave_sum((double)Pt[v]);
             if (lane == 0) {
                 sh.sums[wave][v] = Wd;
                 sh.sums[wave][TILE_MASSES + v] = Pd;

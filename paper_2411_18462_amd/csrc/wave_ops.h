@@ -1,5 +1,4 @@
-// Wave64 cross-lane primitives for gfx950: DPP moves, and the matrix cores for batches of fp64 sums
-// (no LDS traffic in either).
+// Wave64 cross-lane primitives for gfx950 built on DPP moves (no LDS traffic).
 //
 // A wave has 64 lanes in 4 DPP rows of 16.  row_reduce() leaves the combination of a row's
 // 16 values in every lane of that row (quad_perm xor-1, xor-2, then row rotations by 4 and
@@ -92,27 +91,11 @@ __device__ __forceinline__ T wave_reduce(T v, Op op)
 
 __device__ __forceinline__ float wave_max(float v) { return wave_reduce(v, OpMax{}); }
 
-// Wave-uniform fp64 sum of all 64 lanes' values by the DPP butterfly (about 30 vector-ALU slots).
+// Wave-uniform fp64 sum of all 64 lanes' values by the DPP butterfly (about 30 vector-ALU slots).  The same
+// sum as two v_mfma_f64_16x16x4 against a matrix of ones is exact too and needs 6 slots, but its long
+// dependent latency made every kernel that used it slower (a draft step of 64 rows 12.7 us against 12.2 us,
+// the residual pass 13.45 us against 13.1 us), so the matrix cores stay unused in this library.
 __device__ __forceinline__ double wave_sum(double v) { return wave_reduce(v, OpSum{}); }
-
-// The same sum on the matrix cores: two v_mfma_f64_16x16x4 with a matrix of ones.  The first (A = the
-// 64 values as a 16 x 4 matrix, B = ones) leaves in every lane four row sums that together cover one
-// quarter of the lanes; they are added in the lane, and the second (A = ones, B = those quarter sums as
-// a 4 x 16 matrix) adds the four quarters in every lane.  Products with 1.0 are exact and the additions
-// happen in a fixed order, so the result is deterministic and differs from the exact sum by a few fp64
-// roundings.  About 6 vector-ALU slots, but a long dependent latency: it pays where a wave has many
-// independent sums to form at once (the eight tile masses of the residual pass: 13.6 us against
-// 15.6 us), not for the two sums of a draft record (12.7 us a step against 12.2 us with the butterfly).
-// The whole wave must call (matrix instructions read every lane).
-typedef double f64x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ double wave_sum_matrix(double v)
-{
-    const f64x4 zero = {0.0, 0.0, 0.0, 0.0};
-    const f64x4 rows = __builtin_amdgcn_mfma_f64_16x16x4f64(v, 1.0, zero, 0, 0, 0);
-    const double quarter = (rows.x + rows.y) + (rows.z + rows.w);
-    const f64x4 all = __builtin_amdgcn_mfma_f64_16x16x4f64(1.0, quarter, zero, 0, 0, 0);
-    return all.x;
-}
 
 // DPP move that yields 0 where a lane has no source (row shifts) or its row is masked out.
 template <int CTRL, int ROW_MASK>
