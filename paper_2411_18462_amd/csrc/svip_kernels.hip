@@ -219,16 +219,19 @@ static size_t need_pair(int B, int k, bool recompute_lse, const Geo &g, const Ge
 
 // The slicing each pass uses (forced = an experiment's override, 0 = the library's choice).
 // The draft step: one record (= one wave of the statistics launch) per tile of 32 logits per thread, so the
-// search reads a single tile again; rows of more than MAX_SLICES tiles put more tiles into a record, and so
-// do batches of 192 rows and more, where the per-wave cost of a record outweighs the shorter search
-// (256 rows of 128K logits: 21.3 us a step with 32 records against 22.3 us with 63; 128 rows: 15.6 against 14.7).
+// search reads a single tile again; rows of more than MAX_SLICES tiles put more tiles into a record, and so do
+// batches that would otherwise launch 4000 waves or more (four per SIMD): about a quarter of a wave's
+// instructions are per-record overhead, which then outweighs the shorter search (rows of 128K logits, us per
+// step with 63 and with 32 records: 32 rows 9.4 / 10.0, 64 rows 11.5 / 11.3, 128 rows 14.5 / 14.7,
+// 256 rows 22.2 / 20.5).
 static Geo geo_draft(int B, int V, int vec, int forced)
 {
     Geo g;
     g.V = V;
     const int nvec = (V + vec - 1) / vec;
     g.ntiles = (nvec + WG - 1) / WG;
-    int ns = B >= 192 ? MAX_SLICES / 2 : MAX_SLICES;
+    int ns = g.ntiles < MAX_SLICES ? g.ntiles : MAX_SLICES;
+    if ((long long)B * ns >= 4000 && ns == g.ntiles && ns > 1) ns = (ns + 1) / 2;
     if (forced > 0) ns = forced < MAX_SLICES ? forced : MAX_SLICES;
     if (ns > g.ntiles) ns = g.ntiles;
     if (ns < 1) ns = 1;
