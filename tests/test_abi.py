@@ -214,3 +214,25 @@ def test_header_is_plain_c(tmp_path):
                    "}\n")
     subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
                            "-c", str(src), "-o", str(tmp_path / "use_svip.o")])
+
+
+def test_binding_structs_match_the_headers(tmp_path):
+    """The ctypes mirrors of the headers' structs must have the C compiler's sizes and field offsets: a field
+    added on one side only would silently shift every later field."""
+    import subprocess
+    from paper_2411_18462_amd import binding
+    t_fields = [f for f, _ in binding.BenchTuning._fields_]
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stddef.h>\n#include <stdio.h>\n#include "svip.h"\n#include "svip_bench.h"\n'
+                   "int main(void) {\n"
+                   '    printf("%zu\\n", sizeof(svip_bench_tuning));\n' +
+                   "".join(f'    printf("%zu\\n", offsetof(svip_bench_tuning, {f}));\n' for f in t_fields) +
+                   "    return 0;\n}\n")
+    exe = tmp_path / "sizes"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    out = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    assert out[0] == ctypes.sizeof(binding.BenchTuning)
+    assert out[1:] == [getattr(binding.BenchTuning, f).offset for f in t_fields]
+    header = open(os.path.join(ROOT, "include", "svip_bench.h")).read()
+    body = header[header.index("typedef struct svip_bench_tuning {"):header.index("} svip_bench_tuning;")]
+    assert re.findall(r"int (\w+);", body) == t_fields
