@@ -221,18 +221,22 @@ def test_binding_structs_match_the_headers(tmp_path):
     added on one side only would silently shift every later field."""
     import subprocess
     from paper_2411_18462_amd import binding
-    t_fields = [f for f, _ in binding.BenchTuning._fields_]
+    pairs = [("svip_bench_tuning", binding.BenchTuning), ("svip_loop_config", binding.LoopConfig)]
+    lines = []
+    for cname, cls in pairs:
+        lines.append(f'    printf("%zu\\n", sizeof({cname}));\n')
+        lines += [f'    printf("%zu\\n", offsetof({cname}, {f}));\n' for f, _ in cls._fields_]
     src = tmp_path / "sizes.c"
     src.write_text('#include <stddef.h>\n#include <stdio.h>\n#include "svip.h"\n#include "svip_bench.h"\n'
-                   "int main(void) {\n"
-                   '    printf("%zu\\n", sizeof(svip_bench_tuning));\n' +
-                   "".join(f'    printf("%zu\\n", offsetof(svip_bench_tuning, {f}));\n' for f in t_fields) +
-                   "    return 0;\n}\n")
+                   "int main(void) {\n" + "".join(lines) + "    return 0;\n}\n")
     exe = tmp_path / "sizes"
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
     out = [int(x) for x in subprocess.check_output([str(exe)]).split()]
-    assert out[0] == ctypes.sizeof(binding.BenchTuning)
-    assert out[1:] == [getattr(binding.BenchTuning, f).offset for f in t_fields]
+    for cname, cls in pairs:
+        n = len(cls._fields_)
+        assert out[0] == ctypes.sizeof(cls), cname
+        assert out[1:n + 1] == [getattr(cls, f).offset for f, _ in cls._fields_], cname
+        out = out[n + 1:]
     header = open(os.path.join(ROOT, "include", "svip_bench.h")).read()
     body = header[header.index("typedef struct svip_bench_tuning {"):header.index("} svip_bench_tuning;")]
-    assert re.findall(r"int (\w+);", body) == t_fields
+    assert re.findall(r"int (\w+);", body) == [f for f, _ in binding.BenchTuning._fields_]
