@@ -55,6 +55,23 @@ __device__ __forceinline__ void write_row_outputs(const DraftArgs &a, int b, lon
 // rows of 128K logits and slower beyond, and was dropped for this simpler form.
 
 // One batch of a wave: chunks [c0, c0 + NU) of 64 vectors each; CHECKED for the row's last, partial tile.
+// A row's stop flag, requested without looking at it: with no flag array the load goes to the start of the
+// records (any valid address) and the value is ignored.  flag_after_loads() is where the value is first looked
+// at: no access to memory moves across it, and the flag cannot be consumed earlier.  Together they keep the flag
+// and the loads issued between them in flight at the same time; written as `stop_in && stop_in[b]` followed by
+// an early return, the compiler waits for the flag first and only then issues the other loads (it sinks them
+// below the return, or moves the flag to a scalar register at once), one more trip to memory per kernel.
+__device__ __forceinline__ unsigned request_stop_flag(const DraftArgs &a, int b)
+{
+    const unsigned char *p = a.stop_in ? a.stop_in + b : reinterpret_cast<const unsigned char *>(a.part);
+    return *p;
+}
+__device__ __forceinline__ bool flag_after_loads(const DraftArgs &a, unsigned flag)
+{
+    asm volatile("" : "+v"(flag) : : "memory");
+    return a.stop_in && flag;
+}
+
 template <typename DT, int NU, bool CHECKED>
 __device__ __forceinline__ void wave_load(const DT *row, int V, int c0, typename RawOf<DT>::type (&raw)[NU])
 {
@@ -90,11 +107,11 @@ __global__ __launch_bounds__(WG, 8) void k_draft_stats(DraftArgs a)
     int idx = -1;
     // The record's first tile is requested before the row's stop flag is looked at, so that the two travel
     // together (a step is bound by round trips to memory); a stopped row costs those loads and nothing else.
-    const bool stopped = a.stop_in && a.stop_in[b];
+    const unsigned flag = request_stop_flag(a, b);
     typename RawOf<DT>::type raw[CPT];
     if (tb < fe) wave_load<DT, CPT, false>(row, a.geo.V, tb * CPT, raw);
     else wave_load<DT, CPT, true>(row, a.geo.V, tb * CPT, raw);
-    if (stopped) return;
+    if (flag_after_loads(a, flag)) return;
     wave_accumulate<DT, CPT, ARG>(raw, tb * CPT, m, ones, S, t, idx, a.sc);
     for (int t0 = tb + 1; t0 < te; ++t0) {
         if (t0 < fe) wave_load<DT, CPT, false>(row, a.geo.V, t0 * CPT, raw);
@@ -137,7 +154,7 @@ __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
     const int b = blockIdx.x, tid = threadIdx.x, nrec = a.geo.ns;
     const long long o = (long long)b * a.io_stride;
     // independent loads first: the row's flag, its uniform and its records travel together
-    const bool stopped = a.stop_in && a.stop_in[b];
+    const unsigned flag = request_stop_flag(a, b);
     Partial p;
     p.m = neg_inf();
     p.idx = -1;
@@ -148,7 +165,7 @@ __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
         if (tid < nrec) p = a.part[(size_t)b * nrec + tid];
         if (!ARG) u = a.u[o];
     }
-    if (stopped) {
+    if (flag_after_loads(a, flag)) {
         if (tid == 0) {
             a.token[o] = -1;
             a.stop[b] = 1;
