@@ -91,15 +91,30 @@ __device__ __forceinline__ void wave_accumulate(const typename RawOf<DT>::type (
     accumulate<N, NU, ARG>(z, m, ones, S, t, sc, idx, c0);
 }
 
-// grid (ceil(rows * records / 4)), one wave per record.
-template <typename DT, bool ARG>
-__global__ __launch_bounds__(WG, 8) void k_draft_stats(DraftArgs a)
+// grid (ceil(rows * records / 4)), one wave per record.  TWO: the launch's records hold two tiles; a record of
+// two whole tiles then requests both before it works on the first (the arithmetic of the first runs while the
+// second is still on its way: 0.2 us of an 11.2 us step at 64 rows of 128K logits, 0.55 of 21 us at 256), which
+// takes 65 registers; with one tile per record that form is 0.2 us slower, so those launches keep the other.
+template <typename DT, bool ARG, bool TWO>
+__global__ __launch_bounds__(WG, TWO ? 6 : 8) void k_draft_stats(DraftArgs a)
 {
     constexpr int N = VecOf<DT>::N, CPT = WG / 64;       // chunks of 64 vectors per tile
     const int lane = threadIdx.x & 63, nrec = a.geo.ns;
-    const unsigned gw = blockIdx.x * NWAVE + (threadIdx.x >> 6);
-    if (gw >= (unsigned)a.B * (unsigned)nrec) return;
-    const int b = (int)(gw / (unsigned)nrec), r = (int)(gw - (unsigned)b * (unsigned)nrec);
+    int b, r;
+    if (a.rows_by_xcd) {
+        // Workgroups go to the chip's 8 XCDs in turn, and so do the rows' workgroups of k_draft_finish: keeping
+        // row b on XCD b % 8 lets that kernel find the row's records and the tile it reads again in the L2 of
+        // its own XCD.  The grid is ceil(B / 8) * 8 * ceil(nrec / 4) workgroups; those of rows past B exit.
+        const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, wpr = ((unsigned)nrec + NWAVE - 1) / NWAVE;
+        b = (int)((slot / wpr) * 8u + xcd);
+        r = (int)((slot % wpr) * NWAVE + (threadIdx.x >> 6));
+        if (b >= a.B || r >= nrec) return;
+    } else {
+        const unsigned gw = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+        if (gw >= (unsigned)a.B * (unsigned)nrec) return;
+        b = (int)(gw / (unsigned)nrec);
+        r = (int)(gw - (unsigned)b * (unsigned)nrec);
+    }
     const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
     const int tb = r * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
     const int fe = min(te, a.geo.V / (WG * N));           // end of the tiles wholly inside the row
@@ -109,14 +124,23 @@ __global__ __launch_bounds__(WG, 8) void k_draft_stats(DraftArgs a)
     // together (a step is bound by round trips to memory); a stopped row costs those loads and nothing else.
     const unsigned flag = request_stop_flag(a, b);
     typename RawOf<DT>::type raw[CPT];
-    if (tb < fe) wave_load<DT, CPT, false>(row, a.geo.V, tb * CPT, raw);
-    else wave_load<DT, CPT, true>(row, a.geo.V, tb * CPT, raw);
-    if (flag_after_loads(a, flag)) return;
-    wave_accumulate<DT, CPT, ARG>(raw, tb * CPT, m, ones, S, t, idx, a.sc);
-    for (int t0 = tb + 1; t0 < te; ++t0) {
-        if (t0 < fe) wave_load<DT, CPT, false>(row, a.geo.V, t0 * CPT, raw);
-        else wave_load<DT, CPT, true>(row, a.geo.V, t0 * CPT, raw);
-        wave_accumulate<DT, CPT, ARG>(raw, t0 * CPT, m, ones, S, t, idx, a.sc);
+    if (TWO && te - tb == 2 && te <= fe) {
+        typename RawOf<DT>::type raw2[CPT];
+        wave_load<DT, CPT, false>(row, a.geo.V, tb * CPT, raw);
+        wave_load<DT, CPT, false>(row, a.geo.V, (tb + 1) * CPT, raw2);
+        if (flag_after_loads(a, flag)) return;
+        wave_accumulate<DT, CPT, ARG>(raw, tb * CPT, m, ones, S, t, idx, a.sc);
+        wave_accumulate<DT, CPT, ARG>(raw2, (tb + 1) * CPT, m, ones, S, t, idx, a.sc);
+    } else {
+        if (tb < fe) wave_load<DT, CPT, false>(row, a.geo.V, tb * CPT, raw);
+        else wave_load<DT, CPT, true>(row, a.geo.V, tb * CPT, raw);
+        if (flag_after_loads(a, flag)) return;
+        wave_accumulate<DT, CPT, ARG>(raw, tb * CPT, m, ones, S, t, idx, a.sc);
+        for (int t0 = tb + 1; t0 < te; ++t0) {
+            if (t0 < fe) wave_load<DT, CPT, false>(row, a.geo.V, t0 * CPT, raw);
+            else wave_load<DT, CPT, true>(row, a.geo.V, t0 * CPT, raw);
+            wave_accumulate<DT, CPT, ARG>(raw, t0 * CPT, m, ones, S, t, idx, a.sc);
+        }
     }
     // the wave's lanes to one record: maximum first, then sums rescaled to it in fp64
     const float mw = wave_max(m);

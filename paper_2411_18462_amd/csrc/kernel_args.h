@@ -83,6 +83,7 @@ struct DraftArgs {
     int *draft_len;
     long long io_stride;
     Partial *part;          // [B][ns] records of the row's waves
+    int rows_by_xcd;        // k_draft_stats: workgroup -> (row, records) mapping, see there
 };
 
 struct VerifyArgs {

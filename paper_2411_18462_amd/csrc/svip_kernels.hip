@@ -288,15 +288,24 @@ svip_status draft_step_call(const DraftCall &c)
     a.part = w.part;
     hipStream_t st = static_cast<hipStream_t>(c.stream);
     const unsigned waves = (unsigned)a.geo.ns * (unsigned)c.B, rows = (unsigned)c.B;
-    const unsigned grid = (waves + NWAVE - 1) / NWAVE;
+    // Rows pinned to XCDs (see k_draft_stats) while the launch is one round of waves: measured, rows of 128K bf16
+    // logits, us per step without / with: 16 rows 8.15 / 8.07, 32 rows 9.2 / 8.9, 64 rows 11.2 / 10.8, 128 rows
+    // 14.5 / 14.0; 64 and 256 rows of 32000 logits 8.4 / 8.0 and 13.0 / 12.6; but 256 rows of 128K (8192 waves)
+    // 20.65 / 20.8.
+    a.rows_by_xcd = waves <= 4096u;
+    const unsigned grid = a.rows_by_xcd ? ((rows + 7u) / 8u) * 8u * (((unsigned)a.geo.ns + NWAVE - 1) / NWAVE)
+                                        : (waves + NWAVE - 1) / NWAVE;
     bool ok = false;
     by_dtype(c.dtype, [&](auto tag) {
         using DT = decltype(tag);
+        const bool two = a.geo.tps == 2;
         if (c.greedy)
-            ok = launch(k_draft_stats<DT, true>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STATS) &&
+            ok = launch(two ? k_draft_stats<DT, true, true> : k_draft_stats<DT, true, false>, grid, WG, st, a,
+                        SVIP_BENCH_K_DRAFT_STATS) &&
                  launch(k_draft_finish<DT, true>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
         else
-            ok = launch(k_draft_stats<DT, false>, grid, WG, st, a, SVIP_BENCH_K_DRAFT_STATS) &&
+            ok = launch(two ? k_draft_stats<DT, false, true> : k_draft_stats<DT, false, false>, grid, WG, st, a,
+                        SVIP_BENCH_K_DRAFT_STATS) &&
                  launch(k_draft_finish<DT, false>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
     });
     return ok ? SVIP_OK : SVIP_ERR_HIP;
