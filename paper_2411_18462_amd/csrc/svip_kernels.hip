@@ -415,7 +415,7 @@ svip_status verify_call(const VerifyCall &c)
     a.stat_items = stat_rows * a.geo.ns;
     unsigned g_stats = (unsigned)a.stat_items;
     if (g_tune.stats_workgroups > 0 && (unsigned)g_tune.stats_workgroups < g_stats) g_stats = (unsigned)g_tune.stats_workgroups;
-    const unsigned g_resid = (unsigned)a.geo_s.ns * (unsigned)c.B;
+    const unsigned g_resid = (unsigned)a.geo_s.ns * (((unsigned)c.B + 7u) / 8u) * 8u;   // sequences by XCD, see k_resid
     bool ok = false;
     by_dtype(c.dtype, [&](auto tag) {
         using DT = decltype(tag);

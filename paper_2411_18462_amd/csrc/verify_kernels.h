@@ -197,7 +197,12 @@ __global__ __launch_bounds__(WG, 4) void k_resid(VerifyArgs a)
     constexpr int N = VecOf<DT>::N;
     __shared__ ResidLds sh;
     const int ns = a.geo_s.ns;
-    const int b = blockIdx.x / ns, s = blockIdx.x - b * ns, tid = threadIdx.x;
+    // Workgroups go to the chip's 8 XCDs in turn: all slices of sequence b are kept on XCD b % 8, so the
+    // workgroup that finishes the sequence reads the chosen tile again from the L2 that already streamed it
+    // (13.2 -> 12.9 us at 64 sequences of 128K logits, 35 -> 33 us at 256).  The grid is ceil(B / 8) * 8 * ns.
+    const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+    const int b = (int)((slot / (unsigned)ns) * 8u + xcd), s = (int)(slot % (unsigned)ns), tid = threadIdx.x;
+    if (b >= a.B) return;
     if (a.skip && a.skip[b]) return;
     const SeqRec rec = a.ws.rec[b];
     const DT *prow = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, rec.r);
