@@ -335,7 +335,7 @@ class Loop:
 
     def __init__(self, target_trace, draft_trace, *, temperature, h, gamma0, gamma_max, gamma_inc=0, gamma_dec=0,
                  n0=0, max_new, rounds, greedy=False, u_sample=None, u_accept=None, u_resample=None,
-                 log=True, check_every=4, stream=None):
+                 log=True, check_every=8, stream=None):
         if target_trace.dim() != 3 or target_trace.shape != draft_trace.shape:
             raise ValueError("traces must both be [B, L, V]")
         if target_trace.dtype != draft_trace.dtype or draft_trace.dtype not in _DTYPES:
