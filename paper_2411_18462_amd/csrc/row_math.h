@@ -170,17 +170,33 @@ __device__ __forceinline__ void unpack<f16>(const u32x4 &v, float (&z)[8])
     }
 }
 
+// One stored logit widened to fp32 (exact).  Kept apart from the load so that a caller can request a value and
+// only look at it later.
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(bf16 v) { return __uint_as_float((uint32_t)v.bits << 16); }
+__device__ __forceinline__ float widen(f16 v) { return half_bits_to_float(v.bits); }
 template <typename DT>
-__device__ __forceinline__ float load_one(const DT *row, int i);
-template <>
-__device__ __forceinline__ float load_one<float>(const float *row, int i) { return row[i]; }
-template <>
-__device__ __forceinline__ float load_one<bf16>(const bf16 *row, int i)
+__device__ __forceinline__ float load_one(const DT *row, int i) { return widen(row[i]); }
+// The value unchanged, but not looked at (so not waited for) before this point of the program.
+__device__ __forceinline__ float not_before_here(float v)
 {
-    return __uint_as_float((uint32_t)row[i].bits << 16);
+    asm volatile("" : "+v"(v));
+    return v;
 }
-template <>
-__device__ __forceinline__ float load_one<f16>(const f16 *row, int i) { return half_bits_to_float(row[i].bits); }
+__device__ __forceinline__ bf16 not_before_here(bf16 v)
+{
+    unsigned t = v.bits;
+    asm volatile("" : "+v"(t));
+    v.bits = (uint16_t)t;
+    return v;
+}
+__device__ __forceinline__ f16 not_before_here(f16 v)
+{
+    unsigned t = v.bits;
+    asm volatile("" : "+v"(t));
+    v.bits = (uint16_t)t;
+    return v;
+}
 
 template <int N>
 __device__ __forceinline__ float tree_sum(const float (&v)[N])

@@ -22,6 +22,9 @@
 // residual pass the "last workgroup" hand-over of exchange.h lets a sequence's draw follow its slices
 // without a second launch.  Each finishing step issues all of its independent loads before the first
 // dependent one, because at small batches a step is bound by round trips to memory, not by bandwidth.
+// Workgroups are handed to the chip's 8 XCDs in turn and each XCD has its own L2: k_draft_stats and k_resid
+// map workgroups to (row, records) so that everything of row b runs on XCD b % 8, where the workgroup that
+// finishes the row reads records and a tile again.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <math.h>

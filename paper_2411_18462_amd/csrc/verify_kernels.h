@@ -55,21 +55,23 @@ __global__ __launch_bounds__(WG, 8) void k_verify_stats(VerifyArgs a)
 // brought to the largest reference with single-precision exp2 of the (small, exactly formed)
 // reference differences and added in fp64.  Slices are fetched four at a time so that the loads
 // of a chunk are in flight together.
+template <int CH = 4>       // slices fetched together
 __device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns)
 {
-    constexpr int CH = 4;       // slices fetched together (more would cost the streaming kernel registers)
     float r = neg_inf();
     double S = 0.0;
     for (int s0 = 0; s0 < ns; s0 += CH) {
         float pm[CH];
         double pS[CH];
 #pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const bool in = s0 + u < ns;
-            const Partial *p = part + y * ns + (in ? s0 + u : 0);
+        for (int u = 0; u < CH; ++u) {          // the loads first, all of them ...
+            const Partial *p = part + y * ns + (s0 + u < ns ? s0 + u : 0);
             pm[u] = p->m;
             pS[u] = p->S;
-            if (!in || !(pS[u] > 0.0)) {
+        }
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {          // ... then what depends on them (else each load is waited for in turn)
+            if (!(s0 + u < ns) || !(pS[u] > 0.0)) {
                 pm[u] = neg_inf();
                 pS[u] = 0.0;
             }
@@ -97,7 +99,20 @@ __device__ __forceinline__ double row_L(const Partial *part, size_t y, int ns)
 template <typename DT>
 __device__ __forceinline__ SeqRec accept_sequence(const VerifyArgs &a, int b, int lane, bool publish)
 {
-    const int graw = a.draft_len[b];
+    // One wave, a chain of trips to memory: the draft length, then tokens / uniforms / logsumexps / slice
+    // statistics, then the two gathered logits.  The first pass's loads that need no draft length (everything
+    // indexed by position j < k) are requested together with it, and the gathers before the slice statistics
+    // are merged, so a sequence takes three trips instead of five.
+    int graw = a.draft_len[b];
+    int x0 = 0;
+    float u0 = 0.f;
+    double lse0 = 0.0;
+    if (lane < a.k) {
+        x0 = a.tokens[(size_t)b * a.k + lane];
+        u0 = a.u_accept[(size_t)b * a.k + lane];
+        if (a.draft_lse) lse0 = a.draft_lse[(size_t)b * a.k + lane];
+    }
+    asm volatile("" : "+v"(graw) : : "memory");     // the draft length is first looked at here
     const int g = clamp_len(graw, a.k);
     if (publish && graw != g && lane == 0) atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_DRAFT_LEN);
     const DT *tgt = static_cast<const DT *>(a.target) + row_offset(a, a.seq_t, b, 0);
@@ -111,23 +126,26 @@ __device__ __forceinline__ SeqRec accept_sequence(const VerifyArgs &a, int b, in
         bool reject = false;
         double Lp = 0.0, Lq = 0.0;
         if (j <= g) {
-            // loads that do not depend on each other: token, uniform, draft logsumexp, slot statistics
-            int x = 0;
-            double u = 0.0, lse_q = 0.0;
-            if (j < g) {
+            int x = x0;
+            double u = (double)u0, lse_q = lse0;
+            if (j0 > 0 && j < g) {
                 x = a.tokens[(size_t)b * a.k + j];
                 u = (double)a.u_accept[(size_t)b * a.k + j];
                 if (a.draft_lse) lse_q = a.draft_lse[(size_t)b * a.k + j];
             }
-            Lp = row_L(a.ws.part, stat_row(a, b, a.kd + j), a.geo.ns);
+            DT zp_stored = DT(), zq_stored = DT();          // requested here, widened after the statistics are merged
             if (j < g) {
-                Lq = a.draft_lse ? lse_q * LOG2E : row_L(a.ws.part, stat_row(a, b, j), a.geo.ns);
                 if (x < 0 || x >= a.geo.V) {
                     if (publish) atomicOr(a.ws.flags, (unsigned)SVIP_FLAG_BAD_TOKEN);
                     x = x < 0 ? 0 : a.geo.V - 1;
                 }
-                const double zp = (double)load_one<DT>(tgt + (long long)j * a.row_stride, x);
-                const double zq = (double)load_one<DT>(drf + (long long)j * a.row_stride, x);
+                zp_stored = (tgt + (long long)j * a.row_stride)[x];
+                zq_stored = (drf + (long long)j * a.row_stride)[x];
+            }
+            Lp = row_L<8>(a.ws.part, stat_row(a, b, a.kd + j), a.geo.ns);
+            if (j < g) {
+                Lq = a.draft_lse ? lse_q * LOG2E : row_L<8>(a.ws.part, stat_row(a, b, j), a.geo.ns);
+                const double zp = (double)widen(not_before_here(zp_stored)), zq = (double)widen(not_before_here(zq_stored));
                 const double p = exp2(zp * a.sc.c - Lp);
                 const double q = exp2(zq * a.sc.c - Lq);
                 reject = !(u * q < p);
