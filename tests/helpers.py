@@ -43,12 +43,12 @@ class Round:
         self.accept_prob = torch.full((B, k), float("nan"), dtype=torch.float32, device=dev)
         self.ws = svip.new_workspace(B, k, self.V)
 
-    def draft_all(self, chain=True):
+    def draft_all(self, chain=True, greedy=False):
         """k draft steps; chain=True threads the stop flags like Algorithm 1's drafting loop,
-        chain=False evaluates every position of every row."""
+        chain=False evaluates every position of every row; greedy=True takes the first maximum."""
         for j in range(self.k):
             self.svip.draft_step(
-                self.draft[:, j], temperature=self.T, h=self.h, step_j=j, k_max=self.k,
+                self.draft[:, j], temperature=self.T, h=self.h, step_j=j, k_max=self.k, greedy=greedy,
                 u_sample=self.u_sample[:, j], stop_in=self.stop if chain else None,
                 token_out=self.tokens[:, j], entropy_out=self.entropy[:, j],
                 q_tok_out=self.q_tok[:, j], lse_out=self.lse[:, j],

@@ -291,3 +291,32 @@ def test_small_entropies_keep_their_relative_accuracy(svip, dtype):
             want = oracle.entropy_row(p)
             assert 1e-9 < want < 0.5
             assert abs(H[b, j] - want) <= REL * want, f"row {b} step {j}: H {H[b, j]} vs {want}"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+def test_every_launch_shape_of_the_draft_step(svip, dtype):
+    """The draft step picks records per row (one tile each, two tiles each with both requested at once, longer
+    ones), and places rows by XCD or not, from the batch and the row length.  Here every one of those shapes
+    is forced on the same ragged rows (sampled and greedy) and each is compared with the oracle; B = 11 is
+    no multiple of the 8 XCDs and the record counts are no multiples of a workgroup's 4 waves."""
+    B, k = 11, 2
+    mult, tile = (4, 1024) if dtype == torch.float32 else (8, 2048)
+    V = 13 * tile + 5 * mult + 3                      # 14 tiles, the last one ragged
+    draft, target, us, ua, ur = _make(B, k, V, dtype, seed=77)
+    try:
+        for records in (0, 14, 13, 7, 5, 3, 1):       # 0: the library's own choice; 7: two tiles each; 5, 3, 1: longer
+            svip.bench_set_tuning(draft_slices=records)
+            for greedy in (False, True):
+                r = Round(svip, draft, target, us, ua, ur, 1.0, 1.5)
+                r.draft = _padded(draft, dtype, mult)
+                r.draft_all(chain=False, greedy=greedy)
+                if greedy:
+                    tok = r.tokens.cpu().numpy()
+                    want = draft.double().numpy().argmax(-1)          # numpy's argmax is the first maximum
+                    assert (tok == want).all(), f"records={records}: greedy tokens"
+                else:
+                    st = check_draft_rows(draft, 1.0, 1.5, k, us, r)
+                    assert st["tok_excluded_diff"] <= 1 and st["stop_excluded"] == 0, (records, st)
+            _say(f"{dtype} records={records}: {st}")
+    finally:
+        svip.bench_set_tuning()
