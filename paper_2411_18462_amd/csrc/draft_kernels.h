@@ -54,7 +54,6 @@ __device__ __forceinline__ void write_row_outputs(const DraftArgs &a, int b, lon
 // write-through stores and a ticket, as the residual pass of verification does) measured the same at 64
 // rows of 128K logits and slower beyond, and was dropped for this simpler form.
 
-// One batch of a wave: chunks [c0, c0 + NU) of 64 vectors each; CHECKED for the row's last, partial tile.
 // A row's stop flag, requested without looking at it: with no flag array the load goes to the start of the
 // records (any valid address) and the value is ignored.  flag_after_loads() is where the value is first looked
 // at: no access to memory moves across it, and the flag cannot be consumed earlier.  Together they keep the flag
@@ -72,6 +71,7 @@ __device__ __forceinline__ bool flag_after_loads(const DraftArgs &a, unsigned fl
     return a.stop_in && flag;
 }
 
+// One batch of a wave: chunks [c0, c0 + NU) of 64 vectors each; CHECKED for the row's last, partial tile.
 template <typename DT, int NU, bool CHECKED>
 __device__ __forceinline__ void wave_load(const DT *row, int V, int c0, typename RawOf<DT>::type (&raw)[NU])
 {

@@ -294,8 +294,8 @@ svip_status draft_step_call(const DraftCall &c)
     // Rows pinned to XCDs (see k_draft_stats) while the launch is one round of waves: measured, rows of 128K bf16
     // logits, us per step without / with: 16 rows 8.15 / 8.07, 32 rows 9.2 / 8.9, 64 rows 11.2 / 10.8, 128 rows
     // 14.5 / 14.0; 64 and 256 rows of 32000 logits 8.4 / 8.0 and 13.0 / 12.6; but 256 rows of 128K (8192 waves)
-    // 20.65 / 20.8.
-    a.rows_by_xcd = waves <= 4096u;
+    // 20.65 / 20.8.  Rows of fewer than four records would leave most of a workgroup's waves without one.
+    a.rows_by_xcd = waves <= 4096u && a.geo.ns >= NWAVE;
     const unsigned grid = a.rows_by_xcd ? ((rows + 7u) / 8u) * 8u * (((unsigned)a.geo.ns + NWAVE - 1) / NWAVE)
                                         : (waves + NWAVE - 1) / NWAVE;
     bool ok = false;
