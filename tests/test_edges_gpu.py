@@ -244,16 +244,18 @@ def test_large_batch_of_short_rows(svip):
     _say(f"B={B}: chain {st} verify {sv}")
 
 
-def test_wide_batch_of_long_rows(svip):
-    """B = 200 rows of the 128K vocabulary: from 192 rows on a draft record holds two tiles and the search
-    takes them as one batch; a sample of rows against the oracle, every output of the batch finite."""
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
+def test_wide_batch_of_long_rows(svip, dtype):
+    """B = 200 rows of the 128K vocabulary: a launch of more than 4096 waves, so a draft record holds two tiles,
+    the search takes them as one batch and rows are not placed by XCD; a sample of rows against the oracle,
+    every output of the batch finite."""
     B, k, V = 200, 2, 128256
     g = torch.Generator().manual_seed(77)
     draft = torch.randn(B, k, V, generator=g)
     low = torch.rand(B, k, generator=g) < 0.7
     draft = torch.where(low[..., None], draft, 0.5 * draft)
     draft[torch.arange(B)[:, None], torch.arange(k)[None, :], torch.randint(0, V, (B, k), generator=g)] += 9.0
-    draft = draft.to(torch.bfloat16)
+    draft = draft.to(dtype)
     target = torch.cat([draft, draft[:, :1]], 1)
     u = torch.rand(3, B, k, generator=g)
     r = Round(svip, draft.cuda(), target.cuda(), u[0], u[1], u[2][:, 0].contiguous(), 1.0, 3.0)
@@ -265,7 +267,7 @@ def test_wide_batch_of_long_rows(svip):
     # tail cells of these rows are about 5e-6 wide, so about four draws in ten lie within 1e-6 of a cell edge
     # (a property of the rows, computed by the oracle alone); they are checked for validity, the rest exactly
     assert st["stop_excluded"] == 0 and st["tok_excluded"] <= 0.55 * st["rows"]
-    _say(f"B={B} V={V}: {st}")
+    _say(f"{dtype} B={B} V={V}: {st}")
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
