@@ -169,6 +169,19 @@ __global__ __launch_bounds__(WG, TWO ? 6 : 8) void k_draft_stats(DraftArgs a)
     }
 }
 
+// What the thread that finds the draft token does with it (see locate_batch's `report`).
+struct StoreDraftToken {
+    static constexpr bool active = true;
+    const DraftArgs &a;
+    long long o;
+    double S;
+    __device__ __forceinline__ void operator()(int tok, float w) const
+    {
+        a.token[o] = tok;
+        if (a.q_tok) a.q_tok[o] = (float)((double)w / S);
+    }
+};
+
 // grid (rows): the rows' last step over the records of k_draft_stats.
 template <typename DT, bool ARG>
 __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
@@ -239,15 +252,13 @@ __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
     auto row_outputs = [&]() {
         if (tid == WG - 1) write_row_outputs(a, b, o, fin.m, fin.S, fin.tt);
     };
+    // the thread that finds the token stores it; nothing else in this kernel has used fin.loc
+    const StoreDraftToken store{a, o, fin.S};
     float wtok;
     const int tb = fin.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
     // a record of one tile is searched as one batch of one tile, longer records two tiles at a time
-    const int tok = a.geo.tps == 1 ? locate_in_slice<N, 1>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs)
-                                   : locate_in_slice<N, 2>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs);
-    if (tid == 0) {
-        a.token[o] = tok;
-        if (a.q_tok) a.q_tok[o] = (float)((double)wtok / fin.S);
-    }
+    if (a.geo.tps == 1) locate_in_slice<N, 1>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs, true, store);
+    else locate_in_slice<N, 2>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs, true, store);
 }
 
 }  // namespace svip

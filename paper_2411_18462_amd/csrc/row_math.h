@@ -516,9 +516,17 @@ constexpr int NOKEY = 0x7FFFFFFF;
 // One batch: w[u] holds the weights of vector (t0 + u) * WG + tid, all zero for absent tiles.
 // Returns true (uniform) if the crossing lies in this batch (L.tok / L.w are then set);
 // otherwise adds the batch mass to `run`.
-template <int N, int LU>
+// `report` (optional): called by the one thread that finds the token, with (token, its weight); the token is
+// then not passed through LDS and the batch ends one barrier earlier.  `lds_is_free`: no thread can still be
+// reading L from an earlier use, so the batch need not wait before writing it.
+struct NoReport {
+    static constexpr bool active = false;
+    __device__ __forceinline__ void operator()(int, float) const {}
+};
+template <int N, int LU, typename Report = NoReport>
 __device__ __forceinline__ bool locate_batch(const float (&w)[LU][N], int t0, int ntile,
-                                             double target, double &run, int &last, LocateLds &L)
+                                             double target, double &run, int &last, LocateLds &L,
+                                             bool lds_is_free = false, Report report = Report())
 {
     static_assert(LU <= LOCATE_UNROLL, "batch wider than the LDS block");
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -532,7 +540,7 @@ __device__ __forceinline__ bool locate_batch(const float (&w)[LU][N], int t0, in
 #pragma unroll
     for (int u = 0; u < LU; ++u)
         if (u < ntile) incl[u] = wave_inclusive_sum((double)g[u]);
-    __syncthreads();                      // LDS of an earlier batch / caller is free again
+    if (!lds_is_free) __syncthreads();    // LDS of an earlier batch / caller is free again
     if (lane == 63) {
 #pragma unroll
         for (int u = 0; u < LU; ++u) L.wtot[wave][u] = incl[u];
@@ -591,12 +599,16 @@ __device__ __forceinline__ bool locate_batch(const float (&w)[LU][N], int t0, in
 #pragma unroll
                 for (int e = 0; e < N; ++e)
                     if (e == pick) wv = w[u][e];
-                L.tok = ((t0 + u) * WG + tid) * N + pick;
-                L.w = wv;
+                if constexpr (Report::active) {
+                    report(((t0 + u) * WG + tid) * N + pick, wv);
+                } else {
+                    L.tok = ((t0 + u) * WG + tid) * N + pick;
+                    L.w = wv;
+                }
             }
         }
     }
-    __syncthreads();
+    if constexpr (!Report::active) __syncthreads();
     return true;
 }
 
@@ -636,9 +648,10 @@ struct NoHook {
 
 // `between` runs once, after the loads of the first batch have been issued and before their data is
 // used: work that does not depend on the search hides behind the memory round trip there.
-template <int N, int LU, typename WF, typename Hook = NoHook>
+template <int N, int LU, typename WF, typename Hook = NoHook, typename Report = NoReport>
 __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double target, LocateLds &L,
-                                               float *weight_out, Hook between = Hook())
+                                               float *weight_out, Hook between = Hook(), bool lds_is_free = false,
+                                               Report report = Report())
 {
     const int tid = threadIdx.x;
     const int fe = min(te, wf.V / (WG * N));   // end of the tiles wholly inside the row
@@ -663,11 +676,19 @@ __device__ __forceinline__ int locate_in_slice(WF &wf, int tb, int te, double ta
                 for (int e = 0; e < N; ++e) w[u][e] = 0.f;
             }
         }
-        found = locate_batch<N, LU>(w, t0, min(LU, te - t0), target, run, last, L);
+        found = locate_batch<N, LU, Report>(w, t0, min(LU, te - t0), target, run, last, L, lds_is_free && t0 == tb, report);
     }
-    if (!found) locate_fallback<N>(wf, last, L);
-    *weight_out = L.w;
-    return L.tok;
+    if constexpr (Report::active) {       // the finder has reported; without a crossing thread 0 reports the fallback
+        if (!found) {
+            locate_fallback<N>(wf, last, L);
+            if (tid == 0) report(L.tok, L.w);
+        }
+        return 0;
+    } else {
+        if (!found) locate_fallback<N>(wf, last, L);
+        *weight_out = L.w;
+        return L.tok;
+    }
 }
 
 }  // namespace svip

@@ -203,6 +203,14 @@ struct ResidLds {
     int last;
 };
 
+// What the thread that finds the correction or bonus token does with it (see locate_batch's `report`).
+struct StoreNextToken {
+    static constexpr bool active = true;
+    int *next_token;
+    int b;
+    __device__ __forceinline__ void operator()(int tok, float) const { next_token[b] = tok; }
+};
+
 // grid (sequences * slices), the whole residual / bonus draw in one launch.  Every workgroup sums
 // the weights of its slice tile by tile -- residual max(0, p - q) at the rejected position, and target p
 // of the row to sample -- and publishes them; the workgroup that draws the sequence's final ticket
@@ -318,16 +326,16 @@ __global__ __launch_bounds__(WG, 4) void k_resid(VerifyArgs a)
         te = tb + 1;
     }
     constexpr int LU = TILES ? 1 : 2;
+    // the thread that finds the token stores it; nothing else in this kernel has used sh.fin.loc
+    const StoreNextToken store{a.next_token, b};
     float wtok;
-    int tok;
     if (sh.fin.use_resid) {
         ResidualWeights<DT> wf{prow, qrow, a.geo_s.V, ep, eq};
-        tok = locate_in_slice<N, LU>(wf, tb, te, sh.fin.target, sh.fin.loc, &wtok);
+        locate_in_slice<N, LU>(wf, tb, te, sh.fin.target, sh.fin.loc, &wtok, NoHook(), true, store);
     } else {
         SoftmaxWeights<DT> wf{prow, a.geo_s.V, ep};
-        tok = locate_in_slice<N, LU>(wf, tb, te, sh.fin.target, sh.fin.loc, &wtok);
+        locate_in_slice<N, LU>(wf, tb, te, sh.fin.target, sh.fin.loc, &wtok, NoHook(), true, store);
     }
-    if (tid == 0) a.next_token[b] = tok;
 }
 
 }  // namespace svip
