@@ -187,10 +187,13 @@ template <typename DT, bool ARG>
 __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
 {
     constexpr int N = VecOf<DT>::N;
-    __shared__ FinishLds fin;
-    const int b = blockIdx.x, tid = threadIdx.x, nrec = a.geo.ns;
+    __shared__ LocateLds loc;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, nrec = a.geo.ns;
     const long long o = (long long)b * a.io_stride;
-    // independent loads first: the row's flag, its uniform and its records travel together
+    if (ARG && tid >= 64) return;          // the greedy token takes one wave and no search
+    // independent loads first: the row's flag, its uniform and its records travel together.  Every wave loads and
+    // merges the records for itself (a record per lane): the waves then agree on the record to search without
+    // passing anything through LDS or waiting for one another.
     const unsigned flag = request_stop_flag(a, b);
     Partial p;
     p.m = neg_inf();
@@ -198,10 +201,8 @@ __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
     p.S = 0.0;
     p.t = 0.0;
     float u = 0.f;
-    if (tid < 64) {
-        if (tid < nrec) p = a.part[(size_t)b * nrec + tid];
-        if (!ARG) u = a.u[o];
-    }
+    if (lane < nrec) p = a.part[(size_t)b * nrec + lane];
+    if (!ARG) u = a.u[o];
     if (flag_after_loads(a, flag)) {
         if (tid == 0) {
             a.token[o] = -1;
@@ -210,55 +211,43 @@ __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
         return;
     }
     const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);
-    if (tid < 64) {
-        // everything relative to the row maximum: this lane's record by the factor f
-        const float mrow = wave_max(p.m);
-        double f = 0.0, xd = 0.0;
-        if (p.m != neg_inf() && p.S > 0.0) {
-            xd = ((double)p.m - (double)mrow) * a.sc.c;
-            f = exp2(xd);
-        }
-        const double M = f * p.S;
-        const double incl = wave_inclusive_sum(M);
-        const double S = read_lane(incl, 63);
-        const double tt = wave_sum(f * (p.t + xd * p.S));
-        if (ARG) {
-            // records are in index order: the first that reaches the row maximum holds its first index
-            const unsigned long long at_max = __ballot(p.m == mrow && p.idx >= 0);
-            const int tok = at_max ? read_lane(p.idx, __ffsll((long long)at_max) - 1) : -1;
-            if (tid == 0) {
-                a.token[o] = tok;
-                if (a.q_tok) a.q_tok[o] = (float)(1.0 / S);           // the maximum has weight exp2(0) = 1
-                write_row_outputs(a, b, o, mrow, S, tt);
-            }
-        } else {
-            double local;
-            const int rec = pick_slice(M, (double)u * S, incl, &local);
-            if (tid == 0) {
-                fin.target = local;
-                fin.L = (double)mrow * a.sc.c;
-                fin.S = S;
-                fin.tt = tt;
-                fin.m = mrow;
-                fin.slice = rec;
-            }
-        }
+    // everything relative to the row maximum: this lane's record by the factor f
+    const float mrow = wave_max(p.m);
+    double f = 0.0, xd = 0.0;
+    if (p.m != neg_inf() && p.S > 0.0) {
+        xd = ((double)p.m - (double)mrow) * a.sc.c;
+        f = exp2(xd);
     }
-    if (ARG) return;
-    __syncthreads();
-    SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, fin.L)};
+    const double M = f * p.S;
+    const double incl = wave_inclusive_sum(M);
+    const double S = read_lane(incl, 63);
+    const double tt = wave_sum(f * (p.t + xd * p.S));
+    if (ARG) {
+        // records are in index order: the first that reaches the row maximum holds its first index
+        const unsigned long long at_max = __ballot(p.m == mrow && p.idx >= 0);
+        const int tok = at_max ? read_lane(p.idx, __ffsll((long long)at_max) - 1) : -1;
+        if (tid == 0) {
+            a.token[o] = tok;
+            if (a.q_tok) a.q_tok[o] = (float)(1.0 / S);           // the maximum has weight exp2(0) = 1
+            write_row_outputs(a, b, o, mrow, S, tt);
+        }
+        return;
+    }
+    double target;
+    const int rec = pick_slice(M, (double)u * S, incl, &target);
+    SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, (double)mrow * a.sc.c)};
     // entropy, logsumexp and the stop test do not depend on the token: one thread of the last wave
     // computes and stores them while the logits are on their way
     auto row_outputs = [&]() {
-        if (tid == WG - 1) write_row_outputs(a, b, o, fin.m, fin.S, fin.tt);
+        if (tid == WG - 1) write_row_outputs(a, b, o, mrow, S, tt);
     };
-    // the thread that finds the token stores it; nothing else in this kernel has used fin.loc
-    const StoreDraftToken store{a, o, fin.S};
+    // the thread that finds the token stores it; nothing else in this kernel has used the search's LDS
+    const StoreDraftToken store{a, o, S};
     float wtok;
-    const int tb = fin.slice * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
+    const int tb = rec * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
     // a record of one tile is searched as one batch of one tile, longer records two tiles at a time
-    if (a.geo.tps == 1) locate_in_slice<N, 1>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs, true, store);
-    else locate_in_slice<N, 2>(wf, tb, te, fin.target, fin.loc, &wtok, row_outputs, true, store);
+    if (a.geo.tps == 1) locate_in_slice<N, 1>(wf, tb, te, target, loc, &wtok, row_outputs, true, store);
+    else locate_in_slice<N, 2>(wf, tb, te, target, loc, &wtok, row_outputs, true, store);
 }
 
 }  // namespace svip

@@ -61,7 +61,11 @@ def test_bench_prints_one_json_line_with_the_required_objects():
     assert rc["whole_step"]["bytes"] == 16 * rc["draft_step"]["bytes"] + rc["verify"]["bytes"]
     assert abs(rc["whole_step"]["us"] - 1e3 * d["ms_per_step"]) < 1e-6
     sum_kernels = sum(k["us_per_step"] for k in ks.values())
-    assert sum_kernels < 1.05 * rc["whole_step"]["us"]             # kernel time cannot exceed the wall time of the step
+    # Kernel time against the wall time of the step: the kernels are timed one by one in eager launches, the
+    # step is a graph replay in which a kernel starts while its predecessor's last waves drain, so the sum of
+    # the durations comes out 5-13 % above the step (the rocprofv3 trace under profiles/ shows the same); the
+    # bound only catches a sum that cannot belong to this step.
+    assert sum_kernels < 1.25 * rc["whole_step"]["us"]
     sp = d["stream_read_peak"]
     assert 0.5 < sp["frac_of_hbm_peak"] < 1.0
     c = d["cpu_baseline"]
