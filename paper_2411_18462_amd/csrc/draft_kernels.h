@@ -182,15 +182,17 @@ struct StoreDraftToken {
     }
 };
 
-// grid (rows): the rows' last step over the records of k_draft_stats.
+// grid (rows): the rows' last step over the records of k_draft_stats.  Sampling: WG + 64 threads, greedy: 64.
+// Waves 0 .. 3 search for the token; the extra wave writes entropy, logsumexp and stop flag and ends, so that
+// work (an fp64 logarithm and a square root, 0.3 us) neither sits in front of the search nor holds up its barriers.
+constexpr int FINISH_THREADS = WG + 64;
 template <typename DT, bool ARG>
-__global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
+__global__ __launch_bounds__(FINISH_THREADS, 4) void k_draft_finish(DraftArgs a)
 {
     constexpr int N = VecOf<DT>::N;
     __shared__ LocateLds loc;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, nrec = a.geo.ns;
     const long long o = (long long)b * a.io_stride;
-    if (ARG && tid >= 64) return;          // the greedy token takes one wave and no search
     // independent loads first: the row's flag, its uniform and its records travel together.  Every wave loads and
     // merges the records for itself (a record per lane): the waves then agree on the record to search without
     // passing anything through LDS or waiting for one another.
@@ -233,21 +235,22 @@ __global__ __launch_bounds__(WG, 4) void k_draft_finish(DraftArgs a)
         }
         return;
     }
+    // the extra wave: the outputs that do not depend on the token.  The test is on a scalar register, so the wave
+    // branches to the end of the program and is gone before the other waves' first barrier.
+    if (__builtin_amdgcn_readfirstlane(tid >> 6) == NWAVE) {
+        if (lane == 0) write_row_outputs(a, b, o, mrow, S, tt);
+        return;
+    }
     double target;
     const int rec = pick_slice(M, (double)u * S, incl, &target);
     SoftmaxWeights<DT> wf{row, a.geo.V, make_exp_ref(a.sc, (double)mrow * a.sc.c)};
-    // entropy, logsumexp and the stop test do not depend on the token: one thread of the last wave
-    // computes and stores them while the logits are on their way
-    auto row_outputs = [&]() {
-        if (tid == WG - 1) write_row_outputs(a, b, o, mrow, S, tt);
-    };
     // the thread that finds the token stores it; nothing else in this kernel has used the search's LDS
     const StoreDraftToken store{a, o, S};
     float wtok;
     const int tb = rec * a.geo.tps, te = min(tb + a.geo.tps, a.geo.ntiles);
     // a record of one tile is searched as one batch of one tile, longer records two tiles at a time
-    if (a.geo.tps == 1) locate_in_slice<N, 1>(wf, tb, te, target, loc, &wtok, row_outputs, true, store);
-    else locate_in_slice<N, 2>(wf, tb, te, target, loc, &wtok, row_outputs, true, store);
+    if (a.geo.tps == 1) locate_in_slice<N, 1>(wf, tb, te, target, loc, &wtok, NoHook(), true, store);
+    else locate_in_slice<N, 2>(wf, tb, te, target, loc, &wtok, NoHook(), true, store);
 }
 
 }  // namespace svip

@@ -305,11 +305,11 @@ svip_status draft_step_call(const DraftCall &c)
         if (c.greedy)
             ok = launch(two ? k_draft_stats<DT, true, true> : k_draft_stats<DT, true, false>, grid, WG, st, a,
                         SVIP_BENCH_K_DRAFT_STATS) &&
-                 launch(k_draft_finish<DT, true>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
+                 launch(k_draft_finish<DT, true>, rows, 64, st, a, SVIP_BENCH_K_DRAFT_FINISH);
         else
             ok = launch(two ? k_draft_stats<DT, false, true> : k_draft_stats<DT, false, false>, grid, WG, st, a,
                         SVIP_BENCH_K_DRAFT_STATS) &&
-                 launch(k_draft_finish<DT, false>, rows, WG, st, a, SVIP_BENCH_K_DRAFT_FINISH);
+                 launch(k_draft_finish<DT, false>, rows, FINISH_THREADS, st, a, SVIP_BENCH_K_DRAFT_FINISH);
     });
     return ok ? SVIP_OK : SVIP_ERR_HIP;
 }
