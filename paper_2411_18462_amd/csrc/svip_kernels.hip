@@ -223,10 +223,11 @@ static size_t need_pair(int B, int k, bool recompute_lse, const Geo &g, const Ge
 // The slicing each pass uses (forced = an experiment's override, 0 = the library's choice).
 // The draft step: one record (= one wave of the statistics launch) per tile of 32 logits per thread, so the
 // search reads a single tile again; rows of more than MAX_SLICES tiles put more tiles into a record, and so do
-// batches that would otherwise launch 4000 waves or more (four per SIMD): about a quarter of a wave's
-// instructions are per-record overhead, which then outweighs the shorter search (rows of 128K logits, us per
-// step with 63 and with 32 records: 32 rows 9.4 / 10.0, 64 rows 11.5 / 11.3, 128 rows 14.5 / 14.7,
-// 256 rows 22.2 / 20.5).
+// batches that would otherwise launch more than 8100 waves (eight per SIMD): about a quarter of a one-tile
+// wave's instructions are per-record overhead, which then outweighs the finer grain and the shorter search
+// (rows of 128K logits, us per step with 63 and with 32 records, rows placed by XCD in both: 48 rows 9.5 / 10.0,
+// 64 rows 10.2 / 10.5, 80 rows 11.0 / 11.9, 96 rows 11.7 / 12.1, 112 rows 12.3 / 13.2, 128 rows 13.2 / 13.6,
+// 144 rows 14.95 / 14.6).
 static Geo geo_draft(int B, int V, int vec, int forced)
 {
     Geo g;
@@ -234,7 +235,7 @@ static Geo geo_draft(int B, int V, int vec, int forced)
     const int nvec = (V + vec - 1) / vec;
     g.ntiles = (nvec + WG - 1) / WG;
     int ns = g.ntiles < MAX_SLICES ? g.ntiles : MAX_SLICES;
-    if ((long long)B * ns >= 4000 && ns == g.ntiles && ns > 1) ns = (ns + 1) / 2;
+    if ((long long)B * ns > 8100 && ns == g.ntiles && ns > 1) ns = (ns + 1) / 2;
     if (forced > 0) ns = forced < MAX_SLICES ? forced : MAX_SLICES;
     if (ns > g.ntiles) ns = g.ntiles;
     if (ns < 1) ns = 1;
@@ -291,11 +292,12 @@ svip_status draft_step_call(const DraftCall &c)
     a.part = w.part;
     hipStream_t st = static_cast<hipStream_t>(c.stream);
     const unsigned waves = (unsigned)a.geo.ns * (unsigned)c.B, rows = (unsigned)c.B;
-    // Rows pinned to XCDs (see k_draft_stats) while the launch is one round of waves: measured, rows of 128K bf16
-    // logits, us per step without / with: 16 rows 8.15 / 8.07, 32 rows 9.2 / 8.9, 64 rows 11.2 / 10.8, 128 rows
-    // 14.5 / 14.0; 64 and 256 rows of 32000 logits 8.4 / 8.0 and 13.0 / 12.6; but 256 rows of 128K (8192 waves)
-    // 20.65 / 20.8.  Rows of fewer than four records would leave most of a workgroup's waves without one.
-    a.rows_by_xcd = waves <= 4096u && a.geo.ns >= NWAVE;
+    // Rows pinned to XCDs (see k_draft_stats) while the launch has at most 8100 waves: measured, rows of 128K bf16
+    // logits, us per step without / with: 16 rows 8.15 / 8.07, 32 rows 9.2 / 8.9, 64 rows 11.2 / 10.8, 72 rows
+    // (4536 one-tile waves) 11.5 / 10.85, 88 rows 12.3 / 11.5, 192 rows (6144 two-tile waves) 16.8 / 16.4; 64 and
+    // 256 rows of 32000 logits 8.4 / 8.0 and 13.0 / 12.6; but 256 rows of 128K (8192 two-tile waves) 20.65 / 20.8.
+    // Rows of fewer than four records would leave most of a workgroup's waves without one.
+    a.rows_by_xcd = waves <= 8100u && a.geo.ns >= NWAVE;
     const unsigned grid = a.rows_by_xcd ? ((rows + 7u) / 8u) * 8u * (((unsigned)a.geo.ns + NWAVE - 1) / NWAVE)
                                         : (waves + NWAVE - 1) / NWAVE;
     bool ok = false;

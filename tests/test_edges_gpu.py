@@ -246,10 +246,10 @@ def test_large_batch_of_short_rows(svip):
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
 def test_wide_batch_of_long_rows(svip, dtype):
-    """B = 200 rows of the 128K vocabulary: a launch of more than 4096 waves, so a draft record holds two tiles,
-    the search takes them as one batch and rows are not placed by XCD; a sample of rows against the oracle,
-    every output of the batch finite."""
-    B, k, V = 200, 2, 128256
+    """B = 261 rows of the 128K vocabulary: a launch that would have more than 8100 one-tile waves, so a draft
+    record holds two tiles, the search takes them as one batch, and with 8352 waves rows are not placed by XCD;
+    a sample of rows against the oracle, every output of the batch finite."""
+    B, k, V = 261, 2, 128256
     g = torch.Generator().manual_seed(77)
     draft = torch.randn(B, k, V, generator=g)
     low = torch.rand(B, k, generator=g) < 0.7
@@ -260,7 +260,7 @@ def test_wide_batch_of_long_rows(svip, dtype):
     u = torch.rand(3, B, k, generator=g)
     r = Round(svip, draft.cuda(), target.cuda(), u[0], u[1], u[2][:, 0].contiguous(), 1.0, 3.0)
     r.draft_all(chain=False)
-    rows = list(range(0, B, 9))
+    rows = list(range(0, B, 11))
     st = check_draft_rows(draft, 1.0, 3.0, k, u[0], r, rows=rows)
     tok = r.tokens.cpu().numpy()
     assert ((tok >= 0) & (tok < V)).all() and torch.isfinite(r.entropy).all() and torch.isfinite(r.lse).all()
