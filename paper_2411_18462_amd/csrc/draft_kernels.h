@@ -100,19 +100,24 @@ __global__ __launch_bounds__(WG, TWO ? 6 : 8) void k_draft_stats(DraftArgs a)
 {
     constexpr int N = VecOf<DT>::N, CPT = WG / 64;       // chunks of 64 vectors per tile
     const int lane = threadIdx.x & 63, nrec = a.geo.ns;
+    // Which record this wave takes is the same in all its lanes: worked out in scalar registers, with the one
+    // division done by a multiplication the host prepared, so that none of it takes vector-ALU slots (a wave of one
+    // tile has about 500 vector instructions in all, and they are what bounds this kernel).
+    const unsigned wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int b, r;
     if (a.rows_by_xcd) {
         // Workgroups go to the chip's 8 XCDs in turn, and so do the rows' workgroups of k_draft_finish: keeping
         // row b on XCD b % 8 lets that kernel find the row's records and the tile it reads again in the L2 of
         // its own XCD.  The grid is ceil(B / 8) * 8 * ceil(nrec / 4) workgroups; those of rows past B exit.
-        const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3, wpr = ((unsigned)nrec + NWAVE - 1) / NWAVE;
-        b = (int)((slot / wpr) * 8u + xcd);
-        r = (int)((slot % wpr) * NWAVE + (threadIdx.x >> 6));
+        const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;           // div = workgroups per row
+        const unsigned q = a.div == 1u ? slot : __umulhi(slot, a.div_magic);
+        b = (int)(q * 8u + xcd);
+        r = (int)((slot - q * a.div) * NWAVE + wv);
         if (b >= a.B || r >= nrec) return;
     } else {
-        const unsigned gw = blockIdx.x * NWAVE + (threadIdx.x >> 6);
+        const unsigned gw = blockIdx.x * NWAVE + wv;                            // div = records per row
         if (gw >= (unsigned)a.B * (unsigned)nrec) return;
-        b = (int)(gw / (unsigned)nrec);
+        b = (int)(a.div == 1u ? gw : __umulhi(gw, a.div_magic));
         r = (int)(gw - (unsigned)b * (unsigned)nrec);
     }
     const DT *row = static_cast<const DT *>(a.logits) + draft_row_offset(a, b);

@@ -84,6 +84,7 @@ struct DraftArgs {
     long long io_stride;
     Partial *part;          // [B][ns] records of the row's waves
     int rows_by_xcd;        // k_draft_stats: workgroup -> (row, records) mapping, see there
+    unsigned div, div_magic;  // its one division, by div: n / div = div == 1 ? n : umulhi(n, div_magic), exact for n * div < 2^32
 };
 
 struct VerifyArgs {

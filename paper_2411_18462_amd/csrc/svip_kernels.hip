@@ -300,6 +300,9 @@ svip_status draft_step_call(const DraftCall &c)
     a.rows_by_xcd = waves <= 8100u && a.geo.ns >= NWAVE;
     const unsigned grid = a.rows_by_xcd ? ((rows + 7u) / 8u) * 8u * (((unsigned)a.geo.ns + NWAVE - 1) / NWAVE)
                                         : (waves + NWAVE - 1) / NWAVE;
+    // the kernel's division: floor(n / d) = umulhi(n, floor(2^32 / d) + 1) while n * d < 2^32 (n < 2^26 waves, d <= 64)
+    a.div = a.rows_by_xcd ? ((unsigned)a.geo.ns + NWAVE - 1) / NWAVE : (unsigned)a.geo.ns;
+    a.div_magic = a.div > 1u ? (unsigned)(0x100000000ull / a.div) + 1u : 0u;
     bool ok = false;
     by_dtype(c.dtype, [&](auto tag) {
         using DT = decltype(tag);

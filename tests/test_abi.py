@@ -240,3 +240,16 @@ def test_binding_structs_match_the_headers(tmp_path):
     header = open(os.path.join(ROOT, "include", "svip_bench.h")).read()
     body = header[header.index("typedef struct svip_bench_tuning {"):header.index("} svip_bench_tuning;")]
     assert re.findall(r"int (\w+);", body) == [f for f, _ in binding.BenchTuning._fields_]
+
+
+def test_division_by_multiplication_is_exact_over_the_kernels_range():
+    """k_draft_stats divides a wave number by the records (or workgroups) per row as umulhi(n, floor(2^32 / d) + 1),
+    with n < 2^26 (MAX_BATCH rows of at most 64 records) and d <= 64: exact while n * d < 2^32."""
+    import numpy as np
+    rng = np.random.default_rng(0)
+    for d in range(2, 65):
+        magic = (1 << 32) // d + 1
+        n = np.concatenate([np.arange(0, 4096), rng.integers(0, 1 << 26, 20000), (1 << 26) - 1 - np.arange(0, 4096),
+                            np.arange(1, 3000) * d - 1, np.arange(1, 3000) * d]).astype(np.uint64)
+        n = n[n < (1 << 26)]
+        assert ((n * np.uint64(magic)) >> np.uint64(32) == n // np.uint64(d)).all(), d
