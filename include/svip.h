@@ -282,8 +282,14 @@ svip_status svip_pair_stats(
  * at absolute position n (independent of the tokens chosen before).  A sequence starts a new round
  * while it has produced fewer than max_new tokens and its trace holds limit + 1 more rows; a round
  * produces the accepted draft tokens followed by the correction or bonus token.  Everything per
- * round stays on the device; the host reads one counter per round (and, if check_every > 0, one
- * more every check_every draft steps to end the drafting phase early).
+ * round stays on the device; the host learns one counter per round (and, if check_every > 0, one
+ * more every check_every draft steps to end the drafting phase early).  The counters come as
+ * messages the counting kernels store into pinned host memory -- no copy is enqueued and the stream
+ * is not synchronised between rounds -- and the host launches one round ahead of the counter it
+ * waits for: a round launched after the last sequence finished changes nothing (its sequences are
+ * all marked done) except that, with a log, it may fill its round_log entries with -1.  The first
+ * svip_loop_run of a host thread allocates 512 bytes of pinned host memory for those messages and
+ * keeps them until the process ends.
  *
  * state[b, :] (int32): 0 position, 1 length limit of the next round, 2 finished, 3 rounds,
  * 4 drafted tokens, 5 accepted tokens, 6 produced tokens, 7 start position.
@@ -324,8 +330,9 @@ size_t svip_loop_workspace_bytes(int B, int gamma_max, int V);
 svip_status svip_loop_init(const svip_loop_config *config /* host */);
 
 /* Run rounds first_round .. first_round + max_rounds - 1 (or until every sequence has finished).
- * Synchronises the stream.  *rounds_run_host and *running_host (host, optional) receive the rounds
- * executed and the sequences still running. */
+ * Synchronises the stream before it returns.  *rounds_run_host and *running_host (host, optional)
+ * receive the rounds executed (a round launched ahead that found every sequence finished is not
+ * counted) and the sequences still running. */
 svip_status svip_loop_run(const svip_loop_config *config /* host */, int first_round, int max_rounds,
                           int *rounds_run_host, int *running_host);
 

@@ -8,10 +8,17 @@
 //             verify         -> svip_verify kernels on trace rows pos[b] .. pos[b] + draft_len[b]
 //             k_round_end    -> appends the produced tokens, advances positions, applies the length
 //                               rule, updates the counters and counts the sequences still running
-// The host synchronises once per round (to read that count) and never per draft step unless asked to.
+// The two counts reach the host as messages: the counting kernel stores (ticket, count) as one 8-byte word
+// into pinned host memory and the host reads that word until the ticket shows.  No copy is enqueued and the
+// stream is never synchronised inside the loop; the host launches one round ahead of the count it waits for,
+// so the GPU always has the next round queued (a round launched after the last sequence finished finds
+// every sequence marked done and changes nothing).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <string.h>
+
+#include <chrono>
 
 #include "../../include/svip.h"
 #include "svip_internal.h"
@@ -40,7 +47,92 @@ struct LoopArgs {
     int *out_tokens;
     long long out_stride;
     int *round_log;            // [rounds, B, 4] or nullptr
+    unsigned long long *mail;  // k_round_end: where the count of running sequences goes (pinned host memory)
+    unsigned ticket;           // and the ticket it goes with
 };
+
+// ---- messages from the device to the host ----------------------------------------------------
+//
+// A host thread's mailbox: MAIL_SLOTS words of pinned host memory, allocated by the thread's first
+// svip_loop_run and kept until the process ends.  A message is (ticket << 32 | value), stored by one
+// thread of a kernel with a single system-scope store; tickets count up per host thread and never repeat
+// within 2^32 messages, message t uses word t % MAIL_SLOTS, and the loop never has more than three
+// messages outstanding, so a word is not reused before it has been read.
+constexpr unsigned MAIL_SLOTS = 64;
+struct Mailbox {
+    unsigned long long *host, *dev;
+    unsigned next;
+};
+static thread_local Mailbox g_mail = {nullptr, nullptr, 0};
+
+struct Ticket {
+    unsigned id;
+    unsigned long long *dev;            // what the kernel gets
+    const unsigned long long *host;     // what the host reads
+};
+
+static bool mailbox_ready()
+{
+    if (g_mail.host) return true;
+    void *h = nullptr, *d = nullptr;
+    if (hipHostMalloc(&h, MAIL_SLOTS * sizeof(unsigned long long), hipHostMallocPortable | hipHostMallocMapped) != hipSuccess)
+        return false;
+    memset(h, 0, MAIL_SLOTS * sizeof(unsigned long long));
+    if (hipHostGetDevicePointer(&d, h, 0) != hipSuccess) {
+        (void)hipHostFree(h);
+        return false;
+    }
+    g_mail.host = static_cast<unsigned long long *>(h);
+    g_mail.dev = static_cast<unsigned long long *>(d);
+    g_mail.next = 0;
+    return true;
+}
+
+static Ticket new_ticket()
+{
+    Ticket t;
+    t.id = ++g_mail.next;
+    if (t.id == 0) t.id = ++g_mail.next;       // 0 is what an unused word holds
+    t.dev = g_mail.dev + t.id % MAIL_SLOTS;
+    t.host = g_mail.host + t.id % MAIL_SLOTS;
+    return t;
+}
+
+__device__ __forceinline__ void post(unsigned long long *word, unsigned ticket, int value)
+{
+    __hip_atomic_store(word, ((unsigned long long)ticket << 32) | (unsigned)value, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// Waits until the message of ticket t is there.  The kernel that posts it is already in the stream, so the
+// wait ends when the GPU gets there; if nothing shows for a while the stream is asked: one that has drained
+// without the message has failed.
+static svip_status await(const Ticket &t, int *value, hipStream_t st)
+{
+    typedef std::chrono::steady_clock clock;
+    clock::time_point t0 = clock::now();
+    for (unsigned spins = 1;; ++spins) {
+        unsigned long long v = __atomic_load_n(t.host, __ATOMIC_ACQUIRE);
+        if ((unsigned)(v >> 32) == t.id) {
+            *value = (int)(unsigned)v;
+            return SVIP_OK;
+        }
+        if ((spins & 4095u) == 0 && clock::now() - t0 > std::chrono::milliseconds(200)) {
+            const hipError_t q = hipStreamQuery(st);
+            if (q == hipErrorNotReady) {
+                (void)hipGetLastError();        // "not ready" is no error of the loop's: do not leave it behind
+                t0 = clock::now();
+                continue;
+            }
+            v = __atomic_load_n(t.host, __ATOMIC_ACQUIRE);
+            if (q == hipSuccess && (unsigned)(v >> 32) == t.id) {
+                *value = (int)(unsigned)v;
+                return SVIP_OK;
+            }
+            return SVIP_ERR_HIP;
+        }
+    }
+}
 
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -125,13 +217,17 @@ __global__ __launch_bounds__(LOOP_WG) void k_round_begin(LoopArgs a)
 }
 
 // one workgroup: number of sequences that are still drafting
-__global__ __launch_bounds__(LOOP_WG) void k_count_drafting(const unsigned char *stop, int B, int *counter)
+__global__ __launch_bounds__(LOOP_WG) void k_count_drafting(const unsigned char *stop, int B, int *counter,
+                                                            unsigned long long *mail, unsigned ticket)
 {
     __shared__ int lds[LOOP_WG / 64];
     int n = 0;
     for (int b = threadIdx.x; b < B; b += LOOP_WG) n += stop[b] ? 0 : 1;
     const int total = block_count(n, lds);
-    if (threadIdx.x == 0) counter[1] = total;
+    if (threadIdx.x == 0) {
+        counter[1] = total;
+        post(mail, ticket, total);
+    }
 }
 
 // one workgroup: bookkeeping of the round for every running sequence
@@ -171,7 +267,10 @@ __global__ __launch_bounds__(LOOP_WG) void k_round_end(LoopArgs a)
         running += !done;
     }
     const int total = block_count(running, lds);
-    if (threadIdx.x == 0) a.rb.counter[0] = total;
+    if (threadIdx.x == 0) {
+        a.rb.counter[0] = total;
+        post(a.mail, a.ticket, total);
+    }
 }
 
 static svip_status read_counter(const int *dev, int *host, hipStream_t st)
@@ -238,8 +337,16 @@ svip_status svip_loop_run(const svip_loop_config *c, int first_round, int max_ro
     int running = 0, done_rounds = 0;
     svip_status r = read_counter(rb.counter, &running, st);
     if (r != SVIP_OK) return r;
+    if (running > 0 && max_rounds > 0 && !mailbox_ready()) return SVIP_ERR_HIP;
+    // `running` is the count after the last round whose message has been read; `before` is the ticket of the
+    // round launched since, whose message has not been read yet.  Round i is launched on the strength of
+    // the count after round i - 2; if the count after round i - 1 then turns out to be zero, round i has
+    // run (or is being dropped) with every sequence marked done and is not counted.
+    Ticket before = {0, nullptr, nullptr};
+    bool have_before = false;
     for (int i = 0; i < max_rounds && running > 0; ++i) {
         const int round = first_round + i;
+        const Ticket mine = new_ticket();
         LoopArgs a;
         a.state = c->state;
         a.B = B;
@@ -253,9 +360,12 @@ svip_status svip_loop_run(const svip_loop_config *c, int first_round, int max_ro
         a.out_tokens = c->out_tokens;
         a.out_stride = c->out_stride;
         a.round_log = c->round_log;
+        a.mail = mine.dev;
+        a.ticket = mine.id;
         hipLaunchKernelGGL(k_round_begin, dim3(1), dim3(LOOP_WG), 0, st, a);
 
         const size_t uoff = (size_t)round * B * k;
+        bool idle = false;        // the round before this one finished the last sequence
         for (int j = 0; j < k; ++j) {
             DraftCall d;
             d.greedy = c->greedy != 0;
@@ -286,13 +396,26 @@ svip_status svip_loop_run(const svip_loop_config *c, int first_round, int max_ro
             r = draft_step_call(d);
             if (r != SVIP_OK) return r;
             if (c->check_every > 0 && (j + 1) % c->check_every == 0 && j + 1 < k) {
-                hipLaunchKernelGGL(k_count_drafting, dim3(1), dim3(LOOP_WG), 0, st, rb.stop, B, rb.counter);
+                const Ticket poll = new_ticket();
+                hipLaunchKernelGGL(k_count_drafting, dim3(1), dim3(LOOP_WG), 0, st, rb.stop, B, rb.counter, poll.dev,
+                                   poll.id);
+                if (hipPeekAtLastError() != hipSuccess) return SVIP_ERR_HIP;
                 int drafting = 0;
-                r = read_counter(rb.counter + 1, &drafting, st);
+                r = await(poll, &drafting, st);
                 if (r != SVIP_OK) return r;
+                if (have_before) {                // the GPU is inside this round: the one before has posted
+                    r = await(before, &running, st);
+                    if (r != SVIP_OK) return r;
+                    have_before = false;
+                    if (running == 0) {
+                        idle = true;
+                        break;
+                    }
+                }
                 if (drafting == 0) break;
             }
         }
+        if (idle) break;
 
         VerifyCall v;
         v.greedy = c->greedy != 0;
@@ -324,10 +447,21 @@ svip_status svip_loop_run(const svip_loop_config *c, int first_round, int max_ro
 
         hipLaunchKernelGGL(k_round_end, dim3(1), dim3(LOOP_WG), 0, st, a);
         if (hipPeekAtLastError() != hipSuccess) return SVIP_ERR_HIP;
-        r = read_counter(rb.counter, &running, st);
-        if (r != SVIP_OK) return r;
+        if (have_before) {        // with this round queued behind it, wait for the count of the round before
+            r = await(before, &running, st);
+            if (r != SVIP_OK) return r;
+            have_before = false;
+            if (running == 0) break;              // this round was idle
+        }
+        before = mine;
+        have_before = true;
         ++done_rounds;
     }
+    if (have_before) {
+        r = await(before, &running, st);
+        if (r != SVIP_OK) return r;
+    }
+    if (hipStreamSynchronize(st) != hipSuccess) return SVIP_ERR_HIP;
     if (rounds_run_host) *rounds_run_host = done_rounds;
     if (running_host) *running_host = running;
     return SVIP_OK;
