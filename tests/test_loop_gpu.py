@@ -47,6 +47,9 @@ def _run(svip, tr, w, policy, max_new, greedy=False, check_every=4, chunks=None,
     else:
         _, running = loop.run()
     assert running == 0 and loop.flags() == 0
+    # a sequence takes part in every round until it has finished, so the longest-running one saw all of them: the
+    # round the loop launches ahead of the last count (and finds nothing to do in) must not be counted
+    assert loop.next_round == int(loop.state[:, 3].max())
     return dict(state=loop.state.cpu().numpy(), out=loop.out_tokens.cpu().numpy(),
                 log=loop.round_log.cpu().numpy()[:loop.next_round], rounds=loop.next_round)
 
