@@ -75,7 +75,10 @@ static bool mailbox_ready()
 {
     if (g_mail.host) return true;
     void *h = nullptr, *d = nullptr;
-    if (hipHostMalloc(&h, MAIL_SLOTS * sizeof(unsigned long long), hipHostMallocPortable | hipHostMallocMapped) != hipSuccess)
+    // coherent (fine-grained) memory: a word stored by a running kernel is seen by the host without waiting for
+    // the kernel to end; without the flag the other two would make the allocation non-coherent
+    if (hipHostMalloc(&h, MAIL_SLOTS * sizeof(unsigned long long),
+                      hipHostMallocCoherent | hipHostMallocPortable | hipHostMallocMapped) != hipSuccess)
         return false;
     memset(h, 0, MAIL_SLOTS * sizeof(unsigned long long));
     if (hipHostGetDevicePointer(&d, h, 0) != hipSuccess) {
